@@ -1,0 +1,140 @@
+/*
+ * hccs.h -- C ABI of the gfx950 implementation of the Head-Calibrated
+ * Clipped-Linear Softmax (HCCS), "Taming the Exponential: A Fast Softmax
+ * Surrogate for Integer-Native Edge Inference".
+ *
+ * Conventions for every entry point
+ *   - Pointers named *_dev are device (HBM) addresses owned by the caller;
+ *     pointers named *_host are host addresses, read during the call only.
+ *   - Tensors are dense, row-major, innermost dimension contiguous.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns after the enqueue; nothing is
+ *     synchronised, nothing is allocated or freed, there is no global state.
+ *   - Per-head constants travel by value in the kernel arguments, so the host
+ *     table may be freed as soon as the call returns.
+ *   - All checks run on the host before anything is launched.  A call that
+ *     returns non-zero has launched nothing and has not touched its outputs.
+ *   - Return value: HCCS_OK (0) or a negative hccs_status.
+ */
+#ifndef HCCS_H
+#define HCCS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HCCS_API __attribute__((visibility("default")))
+
+/* Per-head calibrated constants theta_h = (B_h, S_h, Dmax_h) of Sec. III-A / III-C:
+ * score s = B - S * min(max_j x_j - x, Dmax)   (Eq. (2), (3)). */
+typedef struct {
+    int32_t B;        /* intercept, 1..32767                       */
+    int32_t S;        /* slope, 0..127 (an int8 MAC operand)       */
+    int32_t Dmax;     /* clamp on the distance to the row maximum, 0..127 */
+    int32_t reserved; /* ignored                                   */
+} hccs_head_params;
+
+/* Fixed-point rescale of the fused block's int32 Q.K^T accumulator to an
+ * int8 logit:  x = clamp((acc * mult + 2^(shift-1)) >> shift, -128, 127)
+ * with a flooring shift (round half up).  1 <= mult <= 4096, 1 <= shift <= 23.
+ * The paper starts from int8 logits and does not define this step. */
+typedef struct {
+    int32_t mult;
+    int32_t shift;
+} hccs_requant;
+
+typedef enum {
+    HCCS_OK = 0,
+    HCCS_E_NULL = -1,        /* a required pointer is NULL                               */
+    HCCS_E_SHAPE = -2,       /* a dimension is out of the supported range                */
+    HCCS_E_ALIGN = -3,       /* a device pointer is not aligned as documented            */
+    HCCS_E_SCALE = -4,       /* unsupported output scale / reciprocal kind / band value  */
+    HCCS_E_PARAM_RANGE = -5, /* Dmax, S or B outside its range, or B - S*Dmax < 0        */
+    HCCS_E_PARAM_FLOOR = -6, /* n*(B - S*Dmax) < 256: the row sum could drop below 256   */
+    HCCS_E_PARAM_CEIL = -7,  /* n*B above the band's ceiling                             */
+    HCCS_E_HIP = -8,         /* the HIP runtime refused the launch                       */
+    HCCS_E_REQUANT = -9      /* mult or shift outside its range                          */
+} hccs_status;
+
+/* Admissibility bands (Sec. IV-C "Integer Range Constraints", Eq. (11)).
+ * Both require 0 <= Dmax <= 127, 0 <= S <= 127, 1 <= B <= 32767,
+ * B - S*Dmax >= 0 and n*(B - S*Dmax) >= 256 (so Z >= 256 and the shifted
+ * reciprocal of Eq. (8) fits 15 bits).
+ * HCCS_BAND_STRICT adds n*B <= 32767 (Z <= 32767, needed by the 16-bit path).
+ * HCCS_BAND_U8 replaces that by n*B <= 255*2^15 (reciprocal of Eq. (8) >= 1),
+ * which is all the 8-bit path needs. */
+#define HCCS_BAND_U8 0
+#define HCCS_BAND_STRICT 1
+
+#define HCCS_MAX_HEADS 64        /* table entries carried in the kernel arguments */
+#define HCCS_MAX_ROW_LENGTH 65536
+
+/* Reciprocal kinds for hccs_calibrated_softmax_i8_ex. */
+#define HCCS_RECIP_EXACT 0       /* floor division, Eq. (6) / Eq. (8)           */
+#define HCCS_RECIP_CLB 1         /* leading-bit approximation, Eq. (9)          */
+
+/* Checks H table entries against a band for rows of length n (Sec. IV-C).
+ * table_host: H entries.  first_bad_head (may be NULL) receives the index of
+ * the first entry that fails, or -1.  Pure host function, no GPU needed.
+ * Returns HCCS_OK or the status naming the violated constraint. */
+HCCS_API int hccs_validate_params(const hccs_head_params *table_host, int32_t H, int32_t n, int32_t band,
+                         int32_t *first_bad_head);
+
+/* HCCS over every row of an int8 logit tensor, 8-bit output (Alg. 1 with the
+ * "int8 output path" of Sec. III-B: rho = floor(255*2^15 / Z), p = (s*rho) >> 15).
+ *   logits_dev  [B,H,Lq,Lk] int8; a row is the Lk keys of one (b,h,q); row r
+ *               uses the constants of head (r / Lq) mod H (Sec. IV-D).
+ *   probs_dev   same shape, uint8 in [0,255]; may be the same buffer as
+ *               logits_dev (in place) but must not partially overlap it.
+ *   B,H,Lq      >= 0 for B and Lq (an empty tensor is a no-op), 1 <= H <= HCCS_MAX_HEADS,
+ *               B <= 65535.
+ *   Lk          1..HCCS_MAX_ROW_LENGTH.  Rows whose length is a multiple of 16 with
+ *               16-byte aligned base pointers take the vectorised kernels; any other
+ *               length or alignment takes a slower byte-wise kernel.
+ *   table_host  H entries, validated against `band` with n = Lk.
+ *   out_scale_T must be 255.
+ * Errors: NULL pointers, bad shapes, out_scale_T != 255, inadmissible table. */
+HCCS_API int hccs_calibrated_softmax_i8(const int8_t *logits_dev, uint8_t *probs_dev, int32_t B, int32_t H,
+                               int32_t Lq, int32_t Lk, const hccs_head_params *table_host,
+                               int32_t out_scale_T, int32_t band, void *hip_stream);
+
+/* Fused int8 attention block for one tensor set:
+ *   A = Q.K^T (int32)  ->  x = requant_h(A) (int8)  ->  P = HCCS_u8(x) row-wise, n = L
+ *   ->  O = P.V (int32).  Logits and probabilities never reach HBM.
+ *   q_dev,k_dev,v_dev [B,H,L,d] int8, 16-byte aligned; o_dev [B,H,L,d] int32, 16-byte aligned.
+ *   Supported shapes: d = 64; L a multiple of 64, 64 <= L <= 512; 1 <= H <= HCCS_MAX_HEADS.
+ *   table_host H entries validated against `band` with n = L; requant_host H entries.
+ * The block is motivated, not defined, by the paper (Sec. I, Sec. II); the
+ * rescale rule is the one documented at hccs_requant. */
+HCCS_API int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev,
+                      int32_t B, int32_t H, int32_t L, int32_t d,
+                      const hccs_head_params *table_host, const hccs_requant *requant_host,
+                      int32_t out_scale_T, int32_t band, void *hip_stream);
+
+/* Comparison kernel for benchmarks only (never parity-checked): exact-exponential
+ * float32 softmax of the same int8 logits, out = rint(255 * softmax(scale_h * x)),
+ * same traffic (1 byte in, 1 byte out per element).  scale_host: H floats.
+ * Requires Lk a multiple of 16, Lk <= 16384, 16-byte aligned pointers. */
+HCCS_API int hccs_exp_softmax_i8_f32(const int8_t *logits_dev, uint8_t *probs_dev, int32_t B, int32_t H,
+                            int32_t Lq, int32_t Lk, const float *scale_host, void *hip_stream);
+
+/* Test hook: runs the kernels' reciprocal routine, rho = floor(255*2^15 / Z),
+ * over an array.  z_dev, rho_dev: count uint32 values on the device, every
+ * Z in [256, 255*2^15] (the range the admissibility band guarantees).  Lets
+ * the exhaustive check of Eq. (8) reach the GPU code. */
+HCCS_API int hccs_reciprocal_u8(const uint32_t *z_dev, uint32_t *rho_dev, int64_t count, void *hip_stream);
+
+/* Plain device-to-device copy kernel (uint4 per lane), used to scale hardware
+ * byte counters and as the streaming reference point in benchmarks.
+ * bytes must be a multiple of 16; pointers 16-byte aligned. */
+HCCS_API int hccs_copy_bytes(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream);
+
+/* Static description of a status code. */
+HCCS_API const char *hccs_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCCS_H */

@@ -252,7 +252,7 @@ int hccs_oracle_softmax(const int8_t *logits, void *out, int64_t Bt, int64_t H, 
  *             with a flooring (arithmetic) shift: round half up
  *   p[i][.] = HCCS 8-bit row of x[i][.] with n = L and head h's constants
  *   O[i][t] = sum_j p[i][j]*V[j][t]
- * requant holds H pairs (mult, shift), 1 <= mult <= 4096, 1 <= shift <= 24.
+ * requant holds H pairs (mult, shift), 1 <= mult <= 4096, 1 <= shift <= 23.
  * This requantisation rule is this repository's definition, not the paper's. */
 int hccs_oracle_attention_i8(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o,
                              int64_t Bt, int64_t H, int64_t L, int64_t d, const int32_t *table,
@@ -264,7 +264,7 @@ int hccs_oracle_attention_i8(const int8_t *q, const int8_t *k, const int8_t *v, 
         int rc = hccs_oracle_check_params(table[3 * h], table[3 * h + 1], table[3 * h + 2], L, band);
         if (rc != ORACLE_OK) return rc;
         if (requant[2 * h] < 1 || requant[2 * h] > 4096) return ORACLE_E_ARG;
-        if (requant[2 * h + 1] < 1 || requant[2 * h + 1] > 24) return ORACLE_E_ARG;
+        if (requant[2 * h + 1] < 1 || requant[2 * h + 1] > 23) return ORACLE_E_ARG;
     }
     int status = ORACLE_OK;
     if (threads < 1) threads = 1;
@@ -322,7 +322,7 @@ int hccs_oracle_requant_logits(const int8_t *q, const int8_t *k, int8_t *x, int6
     for (int64_t bh = 0; bh < Bt * H; ++bh) {
         const int64_t h = bh % H;
         const int64_t mult = requant[2 * h], shift = requant[2 * h + 1];
-        if (mult < 1 || mult > 4096 || shift < 1 || shift > 24) return ORACLE_E_ARG;
+        if (mult < 1 || mult > 4096 || shift < 1 || shift > 23) return ORACLE_E_ARG;
         const int8_t *Q = q + bh * L * d, *K = k + bh * L * d;
         for (int64_t i = 0; i < L; ++i)
             for (int64_t j = 0; j < L; ++j) {

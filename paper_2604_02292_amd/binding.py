@@ -1,0 +1,172 @@
+"""Thin ctypes binding over libhccs.so.  Argument marshalling only: every step
+of the method runs in the HIP kernels behind the C ABI (include/hccs.h).
+
+PyTorch is used for device memory and streams.  There is no CPU fallback: if
+the shared library is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhccs.so")
+
+BAND_U8, BAND_STRICT = 0, 1
+RECIP_EXACT, RECIP_CLB = 0, 1
+
+EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_attention_i8",
+           "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_copy_bytes", "hccs_status_string"]
+
+
+class HccsError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"hccs status {status}: {message}")
+        self.status = status
+
+
+class HeadParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("S", ctypes.c_int32), ("Dmax", ctypes.c_int32),
+                ("reserved", ctypes.c_int32)]
+
+
+class Requant(ctypes.Structure):
+    _fields_ = [("mult", ctypes.c_int32), ("shift", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Opens the library on first use; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise HccsError(-8, f"{LIB_PATH} not found: build it with `python -m paper_2604_02292_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+        L.hccs_validate_params.argtypes = [ctypes.POINTER(HeadParams), i32, i32, i32, ctypes.POINTER(i32)]
+        L.hccs_calibrated_softmax_i8.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(HeadParams), i32, i32, vp]
+        L.hccs_attention_i8.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, ctypes.POINTER(HeadParams),
+                                        ctypes.POINTER(Requant), i32, i32, vp]
+        L.hccs_exp_softmax_i8_f32.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_float), vp]
+        L.hccs_reciprocal_u8.argtypes = [vp, vp, i64, vp]
+        L.hccs_copy_bytes.argtypes = [vp, vp, i64, vp]
+        L.hccs_status_string.argtypes = [i32]
+        L.hccs_status_string.restype = ctypes.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().hccs_status_string(int(status)).decode()
+
+
+def _check(status):
+    if status != 0:
+        raise HccsError(status, status_string(status))
+
+
+def head_table(table):
+    """[H,3] integers (B, S, Dmax) -> C array of hccs_head_params."""
+    t = np.asarray(table, dtype=np.int64).reshape(-1, 3)
+    arr = (HeadParams * t.shape[0])()
+    for h, (B, S, D) in enumerate(t.tolist()):
+        arr[h] = HeadParams(int(np.clip(B, -2**31, 2**31 - 1)), int(np.clip(S, -2**31, 2**31 - 1)),
+                            int(np.clip(D, -2**31, 2**31 - 1)), 0)
+    return arr, t.shape[0]
+
+
+def requant_table(requant):
+    t = np.asarray(requant, dtype=np.int64).reshape(-1, 2)
+    arr = (Requant * t.shape[0])()
+    for h, (m, s) in enumerate(t.tolist()):
+        arr[h] = Requant(int(m), int(s))
+    return arr, t.shape[0]
+
+
+def validate_params(table, n, band):
+    """Returns (status, first_bad_head).  Host only; needs no GPU."""
+    arr, H = head_table(table)
+    bad = ctypes.c_int32(-1)
+    rc = lib().hccs_validate_params(arr, H, int(n), int(band), ctypes.byref(bad))
+    return rc, bad.value
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def calibrated_softmax_i8(logits, table, band, out=None, out_scale_T=255, stream=None):
+    """logits: int8 CUDA tensor [B,H,Lq,Lk] (contiguous).  Returns the uint8 tensor of
+    probabilities (allocated here unless `out` is given)."""
+    import torch
+    assert logits.is_cuda and logits.dtype == torch.int8 and logits.is_contiguous() and logits.dim() == 4
+    if out is None:
+        out = torch.empty(logits.shape, dtype=torch.uint8, device=logits.device)
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous() and out.shape == logits.shape
+    B, H, Lq, Lk = logits.shape
+    arr, Ht = head_table(table)
+    if Ht != H:
+        raise HccsError(-2, "table must have one entry per head")
+    _check(lib().hccs_calibrated_softmax_i8(ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                            B, H, Lq, Lk, arr, int(out_scale_T), int(band),
+                                            _stream_handle(stream)))
+    return out
+
+
+def attention_i8(q, k, v, table, requant, band, out=None, out_scale_T=255, stream=None):
+    """q,k,v: int8 CUDA tensors [B,H,L,d].  Returns O int32 [B,H,L,d]."""
+    import torch
+    for t in (q, k, v):
+        assert t.is_cuda and t.dtype == torch.int8 and t.is_contiguous() and t.dim() == 4 and t.shape == q.shape
+    if out is None:
+        out = torch.empty(q.shape, dtype=torch.int32, device=q.device)
+    assert out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and out.shape == q.shape
+    B, H, L, d = q.shape
+    arr, Ht = head_table(table)
+    rq, Hr = requant_table(requant)
+    if Ht != H or Hr != H:
+        raise HccsError(-2, "table and requant must have one entry per head")
+    _check(lib().hccs_attention_i8(ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()),
+                                   ctypes.c_void_p(v.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                   B, H, L, d, arr, rq, int(out_scale_T), int(band), _stream_handle(stream)))
+    return out
+
+
+def exp_softmax_i8_f32(logits, scale, out=None, stream=None):
+    """Benchmark comparison kernel: uint8 rint(255*softmax(scale_h*x))."""
+    import torch
+    assert logits.is_cuda and logits.dtype == torch.int8 and logits.is_contiguous() and logits.dim() == 4
+    if out is None:
+        out = torch.empty(logits.shape, dtype=torch.uint8, device=logits.device)
+    B, H, Lq, Lk = logits.shape
+    sc = (ctypes.c_float * H)(*[float(s) for s in scale])
+    _check(lib().hccs_exp_softmax_i8_f32(ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                         B, H, Lq, Lk, sc, _stream_handle(stream)))
+    return out
+
+
+def reciprocal_u8(z, out=None, stream=None):
+    """z: uint32 values held in an int32/uint32 CUDA tensor; returns floor(255*2^15 / z) per element."""
+    import torch
+    assert z.is_cuda and z.dtype == torch.int32 and z.is_contiguous()
+    if out is None:
+        out = torch.empty_like(z)
+    _check(lib().hccs_reciprocal_u8(ctypes.c_void_p(z.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                    z.numel(), _stream_handle(stream)))
+    return out
+
+
+def copy_bytes(src, dst, stream=None):
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    _check(lib().hccs_copy_bytes(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()),
+                                 nbytes, _stream_handle(stream)))
+    return dst

@@ -1,0 +1,165 @@
+// C ABI of the library (see include/hccs.h): argument checks, the admissibility
+// test of Sec. IV-C, and hand-off to the kernel launchers.  Host code only.
+#include <hip/hip_runtime.h>
+
+#include "hccs_device.h"
+
+namespace hccs {
+hipError_t launch_softmax_u8(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
+                             bool aligned, hipStream_t st);
+hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hipStream_t st);
+hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
+hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
+                            int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st);
+hipError_t launch_exp_softmax(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const float *scale,
+                              hipStream_t st);
+}  // namespace hccs
+
+namespace {
+
+// One head against one band, Sec. IV-C.  64-bit products: n*B can pass 2^31.
+int check_head(const hccs_head_params &hp, int64_t n, int band)
+{
+    const int64_t B = hp.B, S = hp.S, D = hp.Dmax;
+    if (D < 0 || D > 127) return HCCS_E_PARAM_RANGE;
+    if (S < 0 || S > 127) return HCCS_E_PARAM_RANGE;
+    if (B < 1 || B > 32767) return HCCS_E_PARAM_RANGE;
+    if (B - S * D < 0) return HCCS_E_PARAM_RANGE;
+    if (n * (B - S * D) < 256) return HCCS_E_PARAM_FLOOR;
+    const int64_t ceiling = (band == HCCS_BAND_STRICT) ? 32767 : (int64_t)hccs::kRecipNumerator;
+    if (n * B > ceiling) return HCCS_E_PARAM_CEIL;
+    return HCCS_OK;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+int fill_table(const hccs_head_params *table_host, int H, hccs::HeadTable &out)
+{
+    for (int h = 0; h < H; ++h) out.e[h] = make_int4(table_host[h].B, table_host[h].S, table_host[h].Dmax, 0);
+    for (int h = H; h < HCCS_MAX_HEADS; ++h) out.e[h] = make_int4(0, 0, 0, 0);
+    return HCCS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hccs_validate_params(const hccs_head_params *table_host, int32_t H, int32_t n, int32_t band,
+                         int32_t *first_bad_head)
+{
+    if (first_bad_head) *first_bad_head = -1;
+    if (!table_host) return HCCS_E_NULL;
+    if (H < 1 || n < 1 || n > HCCS_MAX_ROW_LENGTH) return HCCS_E_SHAPE;
+    if (band != HCCS_BAND_U8 && band != HCCS_BAND_STRICT) return HCCS_E_SCALE;
+    for (int h = 0; h < H; ++h) {
+        const int rc = check_head(table_host[h], n, band);
+        if (rc != HCCS_OK) {
+            if (first_bad_head) *first_bad_head = h;
+            return rc;
+        }
+    }
+    return HCCS_OK;
+}
+
+int hccs_calibrated_softmax_i8(const int8_t *logits_dev, uint8_t *probs_dev, int32_t B, int32_t H, int32_t Lq,
+                               int32_t Lk, const hccs_head_params *table_host, int32_t out_scale_T, int32_t band,
+                               void *hip_stream)
+{
+    if (!table_host) return HCCS_E_NULL;
+    if (B < 0 || B > 65535 || H < 1 || H > HCCS_MAX_HEADS || Lq < 0 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH)
+        return HCCS_E_SHAPE;
+    if (out_scale_T != 255) return HCCS_E_SCALE;
+    const int rc = hccs_validate_params(table_host, H, Lk, band, nullptr);
+    if (rc != HCCS_OK) return rc;
+    const bool empty = (B == 0 || Lq == 0);
+    if (!empty && (!logits_dev || !probs_dev)) return HCCS_E_NULL;
+    if (empty) return HCCS_OK;
+    const int64_t bytes = (int64_t)B * H * Lq * Lk;
+    const uintptr_t a = (uintptr_t)logits_dev, b = (uintptr_t)probs_dev;
+    if (a != b && a < b + (uint64_t)bytes && b < a + (uint64_t)bytes) return HCCS_E_ALIGN;  // partial overlap
+    hccs::HeadTable tab;
+    fill_table(table_host, H, tab);
+    const bool aligned = aligned16(logits_dev) && aligned16(probs_dev);
+    const hipError_t e =
+        hccs::launch_softmax_u8(logits_dev, probs_dev, B, H, Lq, Lk, tab, aligned, (hipStream_t)hip_stream);
+    return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev, int32_t B,
+                      int32_t H, int32_t L, int32_t d, const hccs_head_params *table_host,
+                      const hccs_requant *requant_host, int32_t out_scale_T, int32_t band, void *hip_stream)
+{
+    if (!table_host || !requant_host) return HCCS_E_NULL;
+    if (B < 0 || H < 1 || H > HCCS_MAX_HEADS || (int64_t)B * H > 0x7fffffff) return HCCS_E_SHAPE;
+    if (d != 64 || L < 64 || L > 512 || L % 64 != 0) return HCCS_E_SHAPE;
+    if (out_scale_T != 255) return HCCS_E_SCALE;
+    const int rc = hccs_validate_params(table_host, H, L, band, nullptr);
+    if (rc != HCCS_OK) return rc;
+    for (int h = 0; h < H; ++h) {
+        if (requant_host[h].mult < 1 || requant_host[h].mult > 4096) return HCCS_E_REQUANT;
+        if (requant_host[h].shift < 1 || requant_host[h].shift > 23) return HCCS_E_REQUANT;
+    }
+    if (B == 0) return HCCS_OK;
+    if (!q_dev || !k_dev || !v_dev || !o_dev) return HCCS_E_NULL;
+    if (!aligned16(q_dev) || !aligned16(k_dev) || !aligned16(v_dev) || !aligned16(o_dev)) return HCCS_E_ALIGN;
+    hccs::HeadTable tab;
+    fill_table(table_host, H, tab);
+    hccs::RequantTable rq;
+    for (int h = 0; h < HCCS_MAX_HEADS; ++h)
+        rq.e[h] = h < H ? make_int2(requant_host[h].mult, requant_host[h].shift) : make_int2(1, 1);
+    const hipError_t e =
+        hccs::launch_attention(q_dev, k_dev, v_dev, o_dev, B, H, L, d, tab, rq, (hipStream_t)hip_stream);
+    return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+int hccs_exp_softmax_i8_f32(const int8_t *logits_dev, uint8_t *probs_dev, int32_t B, int32_t H, int32_t Lq,
+                            int32_t Lk, const float *scale_host, void *hip_stream)
+{
+    if (!scale_host) return HCCS_E_NULL;
+    if (B < 0 || B > 65535 || H < 1 || H > HCCS_MAX_HEADS || Lq < 0 || Lk < 16 || Lk > 16384 || Lk % 16 != 0)
+        return HCCS_E_SHAPE;
+    if (B == 0 || Lq == 0) return HCCS_OK;
+    if (!logits_dev || !probs_dev) return HCCS_E_NULL;
+    if (!aligned16(logits_dev) || !aligned16(probs_dev)) return HCCS_E_ALIGN;
+    const hipError_t e =
+        hccs::launch_exp_softmax(logits_dev, probs_dev, B, H, Lq, Lk, scale_host, (hipStream_t)hip_stream);
+    return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+int hccs_reciprocal_u8(const uint32_t *z_dev, uint32_t *rho_dev, int64_t count, void *hip_stream)
+{
+    if (count < 0) return HCCS_E_SHAPE;
+    if (count == 0) return HCCS_OK;
+    if (!z_dev || !rho_dev) return HCCS_E_NULL;
+    const hipError_t e = hccs::launch_reciprocal(z_dev, rho_dev, count, (hipStream_t)hip_stream);
+    return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+int hccs_copy_bytes(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream)
+{
+    if (bytes < 0 || bytes % 16 != 0) return HCCS_E_SHAPE;
+    if (bytes == 0) return HCCS_OK;
+    if (!src_dev || !dst_dev) return HCCS_E_NULL;
+    if (!aligned16(src_dev) || !aligned16(dst_dev)) return HCCS_E_ALIGN;
+    const hipError_t e = hccs::launch_copy(src_dev, dst_dev, bytes, (hipStream_t)hip_stream);
+    return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+const char *hccs_status_string(int status)
+{
+    switch (status) {
+        case HCCS_OK: return "ok";
+        case HCCS_E_NULL: return "a required pointer is NULL";
+        case HCCS_E_SHAPE: return "a dimension is outside the supported range";
+        case HCCS_E_ALIGN: return "a device pointer is misaligned or buffers partially overlap";
+        case HCCS_E_SCALE: return "unsupported output scale, reciprocal kind or band";
+        case HCCS_E_PARAM_RANGE: return "head constants out of range (Dmax, S, B, or B - S*Dmax < 0)";
+        case HCCS_E_PARAM_FLOOR: return "n*(B - S*Dmax) < 256: row sum could fall below 256";
+        case HCCS_E_PARAM_CEIL: return "n*B exceeds the ceiling of the chosen band";
+        case HCCS_E_HIP: return "the HIP runtime reported an error at launch";
+        case HCCS_E_REQUANT: return "requantisation multiplier or shift out of range";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

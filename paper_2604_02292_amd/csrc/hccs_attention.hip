@@ -1,0 +1,227 @@
+// Fused int8 attention block: A = Q.K^T (int8 MFMA, int32 accumulate), per-head
+// fixed-point rescale to int8 logits, row-wise HCCS (Alg. 1 with the 8-bit output
+// path of Sec. III-B, n = L), O = P.V (int8 MFMA).  Logits and probabilities stay
+// in registers; K and V are staged once per (batch, head) in LDS.
+//
+// The matrix unit is used for the two dense contractions only.  Both use
+// v_mfma_i32_16x16x64_i8, whose operand layout on a 64-lane wave is
+//   A (16 x 64): lane l holds row l%16, columns 16*(l/16) .. +15   (16 bytes)
+//   B (64 x 16): lane l holds column l%16, rows 16*(l/16) .. +15   (16 bytes)
+//   C (16 x 16): lane l holds column l%16, rows 4*(l/16) .. +3      (4 dwords)
+//
+// Step 1 computes the transposed tile (keys x queries) = K_tile . Q^T, so a lane
+// ends up holding, for ONE query (l%16), four consecutive keys of every key tile.
+// The order in which keys enter the second contraction is free as long as P and V
+// agree, so those registers, packed to bytes, are directly the A operand of
+// O = P.V -- no cross-lane movement between the two contractions.  V is re-laid
+// out once per block (4x4 byte transposes) so that its matching B operand is one
+// 16-byte LDS read.  Output column j of the d-tile dt is d = 4*j + dt, which makes
+// each lane's four results of a row contiguous in memory.
+//
+// P is unsigned (0..255) but the matrix unit multiplies signed bytes: the kernel
+// feeds P - 128 (= P ^ 0x80) and starts the accumulator at 128 * sum_j V[j][d].
+#include "hccs_device.h"
+
+namespace hccs {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// min(max(x, lo), hi); the compiler selects v_med3_i32 for it
+__device__ __forceinline__ int clamp_i32(int x, int lo, int hi) { return min(max(x, lo), hi); }
+
+constexpr int kKStride = 80;   // bytes per K row in LDS: 64 + 16 of padding against bank conflicts
+
+template <int NT, bool PRECLAMP>   // NT = L/16 key tiles (a multiple of 4)
+__global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__restrict__ q,
+                                                             const int8_t *__restrict__ k,
+                                                             const int8_t *__restrict__ v,
+                                                             int32_t *__restrict__ o, int H, HeadTable table,
+                                                             RequantTable requant)
+{
+    constexpr int L = NT * 16;
+    constexpr int NQ = NT / 4;     // 64-key groups = MFMAs along the key axis of P.V
+    __shared__ __attribute__((aligned(16))) uint8_t lds_k[L * kKStride];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_v[L * 64];
+    __shared__ __attribute__((aligned(16))) int32_t lds_colsum[64];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int head = blockIdx.x % H;
+    const int4 hp = table.e[head];
+    const int B = hp.x, S = hp.y, D = hp.z;
+    const int mult = requant.e[head].x, shift = requant.e[head].y;
+    const size_t base = (size_t)blockIdx.x * L * 64;
+
+    if (tid < 64) lds_colsum[tid] = 0;
+
+    // ---- stage K row-major (padded rows) -----------------------------------
+    for (int c = tid; c < L * 4; c += 256) {
+        const uint4 val = *(const uint4 *)(k + base + (size_t)c * 16);
+        *(uint4 *)(lds_k + (c >> 2) * kKStride + (c & 3) * 16) = val;
+    }
+    __syncthreads();   // colsum zeroed before the atomics below
+
+    // ---- stage V in operand order -------------------------------------------
+    // A thread takes a 4-key x 4-column block: keys kb*4 .. +3, columns 4*nn .. +3.
+    // Key 64*T + 16*tt + 4*g + r sits in byte r of dword tt of the operand of lane
+    // (g, nn) for the pair (T, dt = column % 4).
+    {
+        const int nn = tid & 15;
+        int cs[4] = {0, 0, 0, 0};
+        for (int kb = tid >> 4; kb < L / 4; kb += 16) {
+            const int8_t *src = v + base + (size_t)(kb * 4) * 64 + nn * 4;
+            const uint32_t r0 = *(const uint32_t *)(src), r1 = *(const uint32_t *)(src + 64),
+                           r2 = *(const uint32_t *)(src + 128), r3 = *(const uint32_t *)(src + 192);
+            const uint32_t a_lo = __builtin_amdgcn_perm(r1, r0, 0x05010400u);
+            const uint32_t a_hi = __builtin_amdgcn_perm(r1, r0, 0x07030602u);
+            const uint32_t b_lo = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
+            const uint32_t b_hi = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
+            uint32_t w[4];
+            w[0] = __builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u);
+            w[1] = __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u);
+            w[2] = __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u);
+            w[3] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
+            const int T = kb >> 4, tt = (kb >> 2) & 3, g = kb & 3;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                *(uint32_t *)(lds_v + ((((T * 4 + dt) * 4 + g) * 16 + nn) * 16) + tt * 4) = w[dt];
+                cs[dt] = __builtin_amdgcn_sdot4((int)w[dt], 0x01010101, cs[dt], false);
+            }
+        }
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) atomicAdd(&lds_colsum[nn * 4 + dt], cs[dt]);
+    }
+    __syncthreads();
+
+    const int qi = lane & 15;      // query inside the 16-row tile / output column group
+    const int g = lane >> 4;       // which quarter of the contraction slots this lane feeds
+    const int half = 1 << (shift - 1);
+    // Saturation bound for the accumulator when acc*mult could leave 32 bits: any
+    // |acc| >= lim rescales to a value beyond the int8 range already.
+    const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 20);
+
+    for (int rt = wave; rt < NT; rt += 4) {
+        // ---- A^T tiles = K_tile . Q^T ------------------------------------------
+        const v4i qop = *(const v4i *)(q + base + (size_t)(rt * 16 + qi) * 64 + g * 16);
+        v4i acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const v4i kop = *(const v4i *)(lds_k + (t * 16 + qi) * kKStride + g * 16);
+            acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
+        }
+
+        // ---- rescale to int8 logits (before saturation) and row maximum -----------
+        int mx = -(1 << 30);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                int a = acc[t][r];
+                if constexpr (PRECLAMP) a = clamp_i32(a, -lim, lim);
+                const int y = (__mul24(a, mult) + half) >> shift;
+                acc[t][r] = y;
+                mx = max(mx, y);
+            }
+        }
+        mx = max(mx, xor16(mx));
+        mx = max(mx, xor32(mx));
+        const int m = min(max(mx, -128), 127);   // saturation is monotone: max of clamped = clamp of max
+
+        // ---- x' = max(x, m - D): the logit clamped into the active window; delta = m - x' ----
+        const int lo = max(m - D, -128);
+        int sx = 0;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int xc = clamp_i32(acc[t][r], lo, 127);
+                acc[t][r] = xc;
+                sx += xc;
+            }
+        }
+        sx += xor16(sx);
+        sx += xor32(sx);
+        // Z = sum (B - S*(m - x')) = L*B - S*(L*m - sum x')      (Eq. (3), (5))
+        const uint32_t Z = (uint32_t)(L * B - S * (L * m - sx));
+        const uint32_t rho = reciprocal_u8(Z);
+        // p = ((B - S*(m - x')) * rho) >> 15 = (c1 + a*x') >> 15
+        const int a_ = (int)__umul24((uint32_t)S, rho);
+        const int c1 = (B - S * m) * (int)rho;
+
+        // ---- pack P - 128 as the A operand, O = P.V ------------------------------------
+        v4i oacc[4];
+        {
+            const v4i cs = *(const v4i *)(lds_colsum + qi * 4);
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const int init = cs[dt] * 128;
+                oacc[dt] = (v4i){init, init, init, init};
+            }
+        }
+#pragma unroll
+        for (int T = 0; T < NQ; ++T) {
+            v4i pop;
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                uint32_t w = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t p = (uint32_t)(__mul24(acc[T * 4 + tt][r], a_) + c1) >> 15;
+                    w |= p << (8 * r);
+                }
+                pop[tt] = (int)(w ^ 0x80808080u);
+            }
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const v4i vop = *(const v4i *)(lds_v + (((T * 4 + dt) * 4 + g) * 16 + qi) * 16);
+                oacc[dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[dt], 0, 0, 0);
+            }
+        }
+
+        // ---- store: lane (g, qi) holds rows 4g..4g+3 of the tile, columns 4*qi .. 4*qi+3 ----
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const v4i out = {oacc[0][r], oacc[1][r], oacc[2][r], oacc[3][r]};
+            *(v4i *)(o + base + (size_t)(rt * 16 + g * 4 + r) * 64 + qi * 4) = out;
+        }
+    }
+}
+
+template <int NT>
+static hipError_t launch_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int blocks, int H,
+                            const HeadTable &tab, const RequantTable &rq, bool preclamp, hipStream_t st)
+{
+    if (preclamp)
+        hipLaunchKernelGGL((hccs_attention_kernel<NT, true>), dim3(blocks), dim3(256), 0, st, q, k, v, o, H, tab,
+                           rq);
+    else
+        hipLaunchKernelGGL((hccs_attention_kernel<NT, false>), dim3(blocks), dim3(256), 0, st, q, k, v, o, H, tab,
+                           rq);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
+                            int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st)
+{
+    (void)d;   // 64, checked by the caller
+    // |acc| <= 64*128*128 = 2^20.  If acc*mult + 2^(shift-1) can pass 2^31 for some
+    // head, the accumulator is saturated first (same result, one more instruction).
+    bool preclamp = false;
+    for (int h = 0; h < H; ++h) {
+        const int64_t worst = ((int64_t)1 << 20) * rq.e[h].x + ((int64_t)1 << (rq.e[h].y - 1));
+        if (worst > 0x7fffffffll) preclamp = true;
+    }
+    const int blocks = Bt * H;
+    switch (L / 16) {
+        case 4: return launch_nt<4>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        case 8: return launch_nt<8>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        case 12: return launch_nt<12>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        case 16: return launch_nt<16>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        case 20: return launch_nt<20>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        case 24: return launch_nt<24>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        case 28: return launch_nt<28>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        case 32: return launch_nt<32>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace hccs

@@ -1,0 +1,221 @@
+// Row-wise HCCS on int8 logits -> uint8 probabilities (Alg. 1 with the 8-bit
+// output path of Sec. III-B).  One HBM read and one HBM write per element; the
+// three logical sweeps over a row (maximum, scores and sum, normalise) run on
+// registers.
+#include "hccs_device.h"
+
+namespace hccs {
+
+// ---------------------------------------------------------------------------
+// Register-resident kernel for rows whose length is a multiple of 16.
+//
+// A row is shared by G adjacent lanes (G = 4, 16 or 64); each lane holds V
+// 16-byte vectors of it, vector number v*G + lane_in_group, so one load
+// instruction of a group covers G*16 contiguous bytes.  A wave works on
+// R batches of 64/G rows at once (R*V loads in flight per lane).  The grid is
+// (row tiles, H, B): a block never straddles heads, so the head's constants are
+// wave-uniform.
+//
+// Vectors past the end of a short row, and rows past the end of the slab, are
+// replaced by the byte -128: that is the identity of the maximum, and its
+// distance to the maximum is (m + 128), a known amount that is taken out of
+// the sum again.
+// ---------------------------------------------------------------------------
+template <int G, int V, int R>
+__global__ __launch_bounds__(256) void hccs_rows_kernel(const int8_t *__restrict__ logits,
+                                                        uint8_t *__restrict__ probs, int Lq, int n16,
+                                                        HeadTable table)
+{
+    constexpr int kRowsPerBatch = 64 / G;
+    constexpr int kRowsPerWave = R * kRowsPerBatch;
+    constexpr int kPaddedLen = G * V * 16;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int sub = lane % G;        // position inside the row's lane group
+    const int grp = lane / G;        // row inside the batch
+    const int head = blockIdx.y;
+    const int4 hp = table.e[head];
+    const int B = hp.x, S = hp.y, D = hp.z;
+    const int n = n16 * 16;
+
+    const size_t slab = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq;
+    const int wave_row0 = ((int)blockIdx.x * 4 + wave) * kRowsPerWave;
+    if (wave_row0 >= Lq) return;   // whole wave past the slab
+    const int row0 = wave_row0 + grp;
+
+    u32x4 d[R][V];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int row = row0 + j * kRowsPerBatch;
+        const int8_t *src = logits + (slab + row) * (size_t)n;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int vi = v * G + sub;
+            if (row < Lq && vi < n16)
+                d[j][v] = load_stream(src + vi * 16);
+            else
+                d[j][v] = (u32x4){kPadWord, kPadWord, kPadWord, kPadWord};
+        }
+    }
+
+    const uint32_t D4 = (uint32_t)D * 0x01010101u;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        // stage 1: row maximum (Alg. 1, first step)
+        ByteMax bm;
+        bm.init(d[j][0][0]);
+        bm.add(d[j][0][1]);
+        bm.add(d[j][0][2]);
+        bm.add(d[j][0][3]);
+#pragma unroll
+        for (int v = 1; v < V; ++v) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) bm.add(d[j][v][c]);
+        }
+        const int m = group_max<G>(bm.result());
+        const uint32_t mu = (uint32_t)(m + 128);
+
+        // stage 2: unclamped distances; sum of the clamped ones from two byte-SAD
+        // accumulations: sum min(delta, D) = (sum delta + count*D - sum |delta - D|) / 2
+        const uint32_t neg_base4 = 0u - (uint32_t)(127 - m) * 0x01010101u;
+        uint32_t acc_d = 0, acc_abs = 0;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t dl = distance4(d[j][v][c], neg_base4);
+                d[j][v][c] = dl;
+                acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
+                acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
+            }
+        }
+        const int t = group_sum<G>((int)acc_d - (int)acc_abs);
+        const int npad = kPaddedLen - n;   // padding bytes sit at distance m+128
+        const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu, (uint32_t)D);
+
+        // stages 3-5: Z = n*B - S*sum min(delta, D)  (Eq. (3), (5)), reciprocal, normalise
+        const uint32_t Z = (uint32_t)(n * B - S * sum_clamped);
+        const RowAffine ra = row_affine(Z, B, S, D);
+
+        const int row = row0 + j * kRowsPerBatch;
+        uint8_t *dst = probs + (slab + row) * (size_t)n;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            const int vi = v * G + sub;
+            u32x4 o;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] = normalise4(d[j][v][c], ra);
+            if (row < Lq && vi < n16) store_stream(dst + vi * 16, o);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// One block per row, any length and alignment: the plain integer form of
+// Alg. 1 with byte accesses.  Slow; it exists so that every admissible shape
+// has a path.  Three passes over the row (the second and third re-read it
+// through the caches), LDS for the cross-wave maximum and sum.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void hccs_row_bytes_kernel(const int8_t *__restrict__ logits,
+                                                             uint8_t *__restrict__ probs, int Lq, int n,
+                                                             HeadTable table)
+{
+    __shared__ int red[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int head = blockIdx.y;
+    const int4 hp = table.e[head];
+    const int B = hp.x, S = hp.y, D = hp.z;
+    const size_t row = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq + blockIdx.x;
+    const int8_t *x = logits + row * (size_t)n;
+    uint8_t *p = probs + row * (size_t)n;
+
+    int m = -128;
+    for (int i = threadIdx.x; i < n; i += 256) m = max(m, (int)x[i]);
+    m = group_max<64>(m);
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    m = max(max(red[0], red[1]), max(red[2], red[3]));
+    __syncthreads();
+
+    int z = 0;
+    for (int i = threadIdx.x; i < n; i += 256) z += B - S * min(m - (int)x[i], D);
+    z = group_sum<64>(z);
+    if (lane == 0) red[wave] = z;
+    __syncthreads();
+    const uint32_t Z = (uint32_t)(red[0] + red[1] + red[2] + red[3]);
+    const uint32_t rho = reciprocal_u8(Z);
+    // every thread reads only the bytes it later overwrites, so in-place use is safe
+    for (int i = threadIdx.x; i < n; i += 256) {
+        const uint32_t s = (uint32_t)(B - S * min(m - (int)x[i], D));
+        p[i] = (uint8_t)((s * rho) >> 15);
+    }
+}
+
+__global__ void reciprocal_kernel(const uint32_t *z, uint32_t *rho, int64_t count)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) rho[i] = reciprocal_u8(z[i]);
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
+                                                   int64_t count)
+{
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if (i + k < count) dst[i + k] = src[i + k];
+}
+
+// ---------------------------------------------------------------------------
+// host side: choose the lane-group shape for a row length
+// ---------------------------------------------------------------------------
+template <int G, int V, int R>
+static hipError_t launch_rows(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int n16,
+                              const HeadTable &tab, hipStream_t st)
+{
+    constexpr int kRowsPerBlock = 4 * R * (64 / G);
+    dim3 grid((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt);
+    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R>), grid, dim3(256), 0, st, x, p, Lq, n16, tab);
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax_u8(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk,
+                             const HeadTable &tab, bool aligned, hipStream_t st)
+{
+    if (Bt == 0 || Lq == 0) return hipSuccess;
+    if (aligned && Lk % 16 == 0 && Lk <= 16384) {
+        const int n16 = Lk / 16;
+        if (n16 <= 4) return launch_rows<4, 1, 4>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 8) return launch_rows<4, 2, 4>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 16) return launch_rows<16, 1, 8>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 32) return launch_rows<16, 2, 4>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 64) return launch_rows<16, 4, 2>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 128) return launch_rows<64, 2, 4>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 256) return launch_rows<64, 4, 2>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 512) return launch_rows<64, 8, 1>(x, p, Bt, H, Lq, n16, tab, st);
+        return launch_rows<64, 16, 1>(x, p, Bt, H, Lq, n16, tab, st);
+    }
+    dim3 grid(Lq, H, Bt);
+    hipLaunchKernelGGL(hccs_row_bytes_kernel, grid, dim3(256), 0, st, x, p, Lq, Lk, tab);
+    return hipGetLastError();
+}
+
+hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hipStream_t st)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(reciprocal_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, z, rho,
+                       count);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st)
+{
+    const int64_t count = bytes / 16;
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((count + 1023) / 1024)), dim3(256), 0, st,
+                       (const u32x4 *)src, (u32x4 *)dst, count);
+    return hipGetLastError();
+}
+
+}  // namespace hccs

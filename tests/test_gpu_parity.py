@@ -1,0 +1,220 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element, bit-exact -- the method is a single-valued integer function."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from paper_2604_02292_amd import binding, synth  # noqa: E402
+
+THREADS = 16
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    binding.lib()   # raises if the library is not built: no fallback
+
+
+def gpu_softmax(x, table, band, **kw):
+    out = binding.calibrated_softmax_i8(torch.from_numpy(x).cuda(), table, band, **kw)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def check(x, table, band, oracle, label=""):
+    print(f"case {label} shape={x.shape} band={band}", flush=True)
+    want, rc = oracle.softmax(x, table, band, threads=THREADS)
+    assert rc == 0
+    got = gpu_softmax(x, table, band)
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        i = tuple(bad[0])
+        raise AssertionError(f"{label}: {bad.shape[0]} mismatches, first at {i}: got {got[i]} want {want[i]} "
+                             f"row={x[i[:3]].tolist()[:32]} params={table[i[1]].tolist()}")
+
+
+def mixed_logits(shape, seed):
+    """Rows cycling through narrow, wide, saturating and constant distributions."""
+    g = np.random.default_rng(seed)
+    Bt, H, Lq, Lk = shape
+    x = np.empty(shape, np.float64)
+    sig = np.array([3.0, 24.0, 80.0, 0.0])[np.arange(Bt * H * Lq) % 4].reshape(Bt, H, Lq, 1)
+    mu = g.uniform(-100, 100, size=(Bt, H, Lq, 1))
+    x = mu + sig * g.standard_normal(shape)
+    return np.clip(np.rint(x), -128, 127).astype(np.int8)
+
+
+# every lane-group shape of the register kernel, full tiles and ragged tails, plus the byte kernel
+SHAPES = [
+    ((1, 4, 64, 64), 1), ((3, 8, 37, 128), 1), ((2, 3, 50, 16), 1), ((2, 2, 33, 32), 1), ((2, 2, 20, 48), 1),
+    ((1, 2, 21, 96), 1), ((1, 2, 19, 112), 1), ((1, 3, 9, 256), 1), ((1, 2, 7, 208), 1), ((2, 12, 40, 512), 1),
+    ((1, 2, 130, 400), 1), ((1, 2, 5, 1024), 0), ((1, 2, 6, 880), 0), ((1, 2, 5, 2048), 0), ((1, 2, 9, 1536), 0),
+    ((1, 2, 3, 4096), 0), ((1, 1, 5, 3216), 0), ((1, 1, 3, 8192), 0), ((1, 1, 2, 5008), 0), ((1, 1, 2, 16384), 0),
+    ((1, 1, 2, 12304), 0), ((2, 1, 1, 64), 1), ((1, 1, 257, 64), 1), ((1, 1, 513, 128), 1),
+    # byte kernel: lengths that are not multiples of 16, or beyond the register kernel
+    ((1, 2, 5, 100), 1), ((1, 2, 3, 1), 1), ((1, 1, 4, 17), 1), ((1, 1, 3, 255), 0), ((1, 1, 2, 20000), 0),
+    ((1, 1, 1, 65536), 0), ((1, 2, 2, 16400), 0),
+]
+
+
+@pytest.mark.parametrize("shape,band", SHAPES)
+def test_softmax_u8_shapes(oracle, shape, band):
+    H, n = shape[1], shape[3]
+    table = synth.head_params(H, n, band, seed=n + 7 * H)
+    check(mixed_logits(shape, seed=sum(shape)), table, band, oracle, "mixed")
+
+
+@pytest.mark.parametrize("n,band", [(64, 1), (128, 1), (512, 1), (4096, 0), (100, 1)])
+def test_softmax_u8_degenerate_rows_and_params(oracle, n, band):
+    shape = (1, 6, 12, n)
+    x = mixed_logits(shape, seed=n)
+    x[0, :, 0] = -128
+    x[0, :, 1] = 127
+    x[0, :, 2] = -128
+    x[0, :, 2, n // 2] = 127          # one-hot at full int8 range
+    x[0, :, 3, ::2] = -128            # alternating extremes
+    x[0, :, 3, 1::2] = 127
+    x[0, :, 4] = np.arange(n) % 256 - 128
+    bmax = 32767 // n if band == 1 else min(32767, (255 << 15) // n)
+    f = -(-256 // n)
+    table = np.array([[bmax, 0, 127], [bmax, (bmax - f) // 127, 127], [bmax, min(127, bmax - f), 1],
+                      [f, 0, 0], [max(f, bmax // 2), 127 if bmax // 2 - f >= 127 else 0, 0],
+                      [bmax, min(127, (bmax - f) // 64), 64]], np.int32)
+    assert binding.validate_params(table, n, band) == (0, -1)
+    check(x, table, band, oracle, "degenerate")
+
+
+def test_softmax_in_place_and_unaligned(oracle):
+    shape = (2, 4, 30, 128)
+    x = mixed_logits(shape, 5)
+    table = synth.head_params(4, 128, 1, seed=3)
+    want, _ = oracle.softmax(x, table, 1)
+    t = torch.from_numpy(x).cuda()
+    out = binding.calibrated_softmax_i8(t, table, 1, out=t.view(torch.uint8))
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+    # misaligned base pointers take the byte kernel
+    buf_in = torch.zeros(x.size + 16, dtype=torch.int8, device="cuda")
+    buf_out = torch.zeros(x.size + 16, dtype=torch.uint8, device="cuda")
+    buf_in[1:1 + x.size] = torch.from_numpy(x).cuda().view(-1)
+    got = binding.calibrated_softmax_i8(buf_in[1:1 + x.size].view(shape), table, 1,
+                                        out=buf_out[3:3 + x.size].view(shape))
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want)
+    assert int(buf_out[:3].sum()) == 0 and int(buf_out[3 + x.size:].sum()) == 0
+
+
+def test_rejected_call_leaves_output_untouched():
+    x = torch.zeros((1, 1, 4, 64), dtype=torch.int8, device="cuda")
+    out = torch.full((1, 1, 4, 64), 77, dtype=torch.uint8, device="cuda")
+    with pytest.raises(binding.HccsError) as e:
+        binding.calibrated_softmax_i8(x, [[512, 0, 1]], 1, out=out)
+    assert e.value.status == -7
+    torch.cuda.synchronize()
+    assert bool((out == 77).all())
+
+
+def test_reciprocal_exhaustive(oracle):
+    """Every row sum the 8-bit band admits goes through the kernels' reciprocal routine."""
+    N = 255 << 15
+    z = np.arange(256, N + 1, dtype=np.int64)
+    want, rc = oracle.reciprocal_u8(z)
+    assert rc == 0
+    got = binding.reciprocal_u8(torch.from_numpy(z.astype(np.int32)).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().astype(np.int64), want)
+
+
+def test_other_stream(oracle):
+    shape = (2, 8, 64, 128)
+    x = mixed_logits(shape, 9)
+    table = synth.head_params(8, 128, 1, seed=9)
+    want, _ = oracle.softmax(x, table, 1)
+    s = torch.cuda.Stream()
+    t = torch.from_numpy(x).cuda()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        out = binding.calibrated_softmax_i8(t, table, 1)
+    s.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+# ---------------------------------------------------------------- the named workloads
+@pytest.mark.parametrize("name,shape", [
+    ("pr1_ref", None), ("edge_encoder", (4, 8, 128, 128)), ("stress_rows", (2, 12, 512, 512)),
+    ("long_row", (1, 16, 64, 4096)),
+])
+def test_workload_recipes_reduced(oracle, name, shape):
+    w = synth.make_workload(name, shape=shape)
+    check(w["logits"], w["table"], w["band"], oracle, name)
+
+
+@pytest.mark.parametrize("name", ["edge_encoder", "stress_rows", "long_row"])
+def test_workloads_full_size(oracle, name):
+    """Full-size tensors, same launch configuration as the benchmark; the oracle runs
+    over every element (OpenMP over rows)."""
+    w = synth.make_workload(name, threads=THREADS)
+    print(f"generated {name} {w['logits'].shape}", flush=True)
+    x, table, band = w["logits"], w["table"], w["band"]
+    got = gpu_softmax(x, table, band)
+    print("gpu done", flush=True)
+    want, rc = oracle.softmax(x, table, band, threads=THREADS)
+    assert rc == 0
+    assert np.array_equal(got, want)
+    if name == "long_row":
+        # the band of Eq. (11) at n = 4096 caps B at 7: the output is provably all zero
+        strict = synth.head_params(x.shape[1], 4096, 1, seed=3)
+        sub = np.ascontiguousarray(x[:1, :, :256])
+        got0 = gpu_softmax(sub, strict, 1)
+        want0, _ = oracle.softmax(sub, strict, 1, threads=THREADS)
+        assert np.array_equal(got0, want0) and not got0.any()
+
+
+# ---------------------------------------------------------------- fused block
+def check_attention(q, k, v, table, rq, band, oracle, label=""):
+    print(f"attention case {label} shape={q.shape}", flush=True)
+    want, rc = oracle.attention(q, k, v, table, rq, band, threads=THREADS)
+    assert rc == 0
+    got = binding.attention_i8(torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(),
+                               torch.from_numpy(v).cuda(), table, rq, band)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        i = tuple(bad[0])
+        raise AssertionError(f"{label}: {bad.shape[0]} mismatches of {got.size}, first at {i}: "
+                             f"got {got[i]} want {want[i]}")
+
+
+@pytest.mark.parametrize("shape", [(1, 2, 64, 64), (2, 3, 128, 64), (1, 2, 256, 64), (1, 1, 192, 64),
+                                   (1, 2, 320, 64), (1, 1, 384, 64), (1, 1, 448, 64), (1, 1, 512, 64),
+                                   (5, 7, 64, 64)])
+def test_attention_shapes(oracle, shape):
+    w = synth.make_workload("fused_attention", shape=shape)
+    check_attention(w["q"], w["k"], w["v"], w["table"], w["requant"], w["band"], oracle, "uniform")
+
+
+def test_attention_full_range_inputs_and_large_multiplier(oracle):
+    """int8 extremes in Q, K, V; multipliers that would leave 32 bits without the
+    accumulator saturation; probabilities above 127 (8-bit band)."""
+    g = np.random.default_rng(2)
+    shape = (2, 4, 128, 64)
+    q, k, v = (g.integers(-128, 128, size=shape, dtype=np.int8) for _ in range(3))
+    q[0, 0, :4] = 127
+    k[0, 0, :4] = 127
+    q[0, 1, :4] = -128
+    k[0, 1, :4] = -128
+    v[0, :, :8] = -128
+    table = np.array([[30000, 127, 127], [65280, 0, 0], [20000, 100, 127], [255, 1, 127]], np.int32)
+    table[1] = [32767, 127, 100]
+    assert binding.validate_params(table, 128, 0) == (0, -1)
+    rq = np.array([[4096, 23], [4096, 12], [1, 1], [2047, 16]], np.int32)
+    check_attention(q, k, v, table, rq, 0, oracle, "extremes")
+
+
+def test_attention_full_size(oracle):
+    w = synth.make_workload("fused_attention")
+    check_attention(w["q"], w["k"], w["v"], w["table"], w["requant"], w["band"], oracle, "full")

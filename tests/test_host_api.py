@@ -1,0 +1,142 @@
+"""Host-side behaviour of the C-ABI library that needs no GPU: the library loads,
+exports every symbol the header declares, and its admissibility check agrees with
+the oracle's on every boundary of Sec. IV-C.  Rejected calls launch nothing, so
+the error paths of the compute entry points are exercised here with null device
+pointers."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_02292_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2604_02292_amd.build import build
+        build()
+    return binding.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "hccs.h")).read()
+    declared = set(re.findall(r"\b(hccs_[a-z0-9_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    assert binding.status_string(0) == "ok"
+    for code in range(-9, 0):
+        assert binding.status_string(code) != "unknown status"
+    assert binding.status_string(-77) == "unknown status"
+
+
+CASES = [
+    (511, 0, 1, 64, 1), (512, 0, 1, 64, 1), (512, 0, 1, 64, 0), (130560, 0, 1, 64, 0),
+    (32767, 0, 1, 255, 0), (32767, 0, 1, 256, 0), (100, 1, 96, 64, 1), (100, 1, 97, 64, 1),
+    (100, 1, 101, 64, 1), (100, 1, 128, 64, 1), (100, 128, 0, 64, 1), (0, 0, 0, 64, 1),
+    (7, 0, 127, 4096, 1), (8, 0, 127, 4096, 1), (2040, 15, 127, 4096, 0), (2041, 15, 127, 4096, 0),
+    (100, -1, 5, 64, 1), (100, 1, -1, 64, 1), (32767, 127, 127, 65536, 0), (127, 1, 126, 256, 1),
+]
+
+
+@pytest.mark.parametrize("B,S,D,n,band", CASES)
+def test_validator_agrees_with_oracle(lib, oracle, B, S, D, n, band):
+    rc, bad = binding.validate_params([[B, S, D]], n, band)
+    assert rc == oracle.check_params(B, S, D, n, band)
+    assert bad == (-1 if rc == 0 else 0)
+
+
+def test_validator_random_sweep_agrees_with_oracle(lib, oracle):
+    g = np.random.default_rng(0)
+    for _ in range(3000):
+        n = int(g.choice([1, 2, 16, 32, 64, 100, 128, 256, 512, 4096, 65536]))
+        B = int(g.integers(-2, 40000)) if g.random() < 0.5 else int(g.integers(1, max(2, 40000 // n)))
+        S, D = int(g.integers(-1, 130)), int(g.integers(-1, 130))
+        band = int(g.integers(0, 2))
+        assert binding.validate_params([[B, S, D]], n, band)[0] == oracle.check_params(B, S, D, n, band)
+
+
+def test_validator_reports_first_bad_head(lib):
+    table = [[511, 0, 1], [511, 3, 100], [512, 0, 1], [0, 0, 0]]
+    assert binding.validate_params(table, 64, 1) == (-7, 2)
+    assert binding.validate_params(table[:2], 64, 1) == (0, -1)
+    assert binding.validate_params(table, 64, 7)[0] == -4
+    assert binding.validate_params(table, 0, 1)[0] == -2
+    assert binding.validate_params(table, 65537, 1)[0] == -2
+
+
+def test_synthetic_tables_are_admissible(lib):
+    for name, (shape, band) in synth.WORKLOADS.items():
+        n = shape[3] if name != "fused_attention" else shape[2]
+        table = synth.head_params(shape[1], n, band, synth.WORKLOAD_SEED[name])
+        assert binding.validate_params(table, n, band) == (0, -1)
+
+
+def _softmax_rc(lib, ptr_in, ptr_out, B, H, Lq, Lk, table, T=255, band=1):
+    arr, _ = binding.head_table(table)
+    return lib.hccs_calibrated_softmax_i8(ctypes.c_void_p(ptr_in), ctypes.c_void_p(ptr_out), B, H, Lq, Lk, arr,
+                                          T, band, None)
+
+
+def test_softmax_rejections_launch_nothing(lib):
+    ok = [[511, 0, 1]]
+    assert _softmax_rc(lib, 0, 0, 1, 1, 4, 64, ok) == -1            # null device pointers
+    assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 64, ok, T=32767) == -4
+    assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 64, ok, band=3) == -4
+    assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 64, [[512, 0, 1]]) == -7
+    assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 64, [[100, 1, 97]]) == -6
+    assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 64, [[100, 1, 101]]) == -5
+    assert _softmax_rc(lib, 4096, 8192, -1, 1, 4, 64, ok) == -2
+    assert _softmax_rc(lib, 4096, 8192, 1, 0, 4, 64, ok) == -2
+    assert _softmax_rc(lib, 4096, 8192, 1, 65, 4, 64, ok * 65) == -2
+    assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 0, ok) == -2
+    assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 65537, ok) == -2
+    assert _softmax_rc(lib, 4096, 4096 + 64, 1, 1, 4, 64, ok) == -3  # partial overlap
+    assert _softmax_rc(lib, 0, 0, 0, 1, 4, 64, ok) == 0             # empty tensor: no-op
+    assert _softmax_rc(lib, 0, 0, 1, 1, 0, 64, ok) == 0
+
+
+def test_attention_rejections_launch_nothing(lib):
+    arr, _ = binding.head_table([[127, 1, 126]])
+    rq, _ = binding.requant_table([[128, 16]])
+    vp = ctypes.c_void_p
+
+    def call(q=4096, k=8192, v=12288, o=16384, B=1, H=1, L=256, d=64, rq_=rq, T=255, band=1, tab=arr):
+        return lib.hccs_attention_i8(vp(q), vp(k), vp(v), vp(o), B, H, L, d, tab, rq_, T, band, None)
+
+    assert call(q=0) == -1
+    assert call(d=32) == -2 and call(L=100) == -2 and call(L=1024) == -2 and call(H=0) == -2
+    assert call(q=4100) == -3
+    assert call(T=32767) == -4
+    assert call(rq_=binding.requant_table([[4097, 16]])[0]) == -9
+    assert call(rq_=binding.requant_table([[128, 24]])[0]) == -9
+    assert call(rq_=binding.requant_table([[128, 0]])[0]) == -9
+    assert call(tab=binding.head_table([[128, 1, 126]])[0]) == -7
+    assert call(B=0, q=0, k=0, v=0, o=0) == 0
+
+
+def test_other_entry_points_reject_bad_arguments(lib):
+    vp = ctypes.c_void_p
+    assert lib.hccs_reciprocal_u8(vp(0), vp(0), 5, None) == -1
+    assert lib.hccs_reciprocal_u8(vp(0), vp(0), -1, None) == -2
+    assert lib.hccs_reciprocal_u8(vp(0), vp(0), 0, None) == 0
+    assert lib.hccs_copy_bytes(vp(4096), vp(8192), 17, None) == -2
+    assert lib.hccs_copy_bytes(vp(4097), vp(8192), 16, None) == -3
+    sc = (ctypes.c_float * 1)(0.1)
+    assert lib.hccs_exp_softmax_i8_f32(vp(4096), vp(8192), 1, 1, 4, 100, sc, None) == -2
+
+
+def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(binding.HccsError):
+        binding.lib()
