@@ -120,6 +120,47 @@ def calibrated_softmax_i8(logits, table, band, out=None, out_scale_T=255, stream
     return out
 
 
+def prepare_softmax(logits, out, table, band, out_scale_T=255):
+    """Marshals one hccs_calibrated_softmax_i8 call once and returns `launch(stream=None)`,
+    for loops where the per-call Python cost matters.  The tensors must stay alive."""
+    import torch
+    assert logits.is_cuda and logits.dtype == torch.int8 and logits.is_contiguous() and logits.dim() == 4
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous() and out.shape == logits.shape
+    B, H, Lq, Lk = logits.shape
+    arr, Ht = head_table(table)
+    if Ht != H:
+        raise HccsError(-2, "table must have one entry per head")
+    fn = lib().hccs_calibrated_softmax_i8
+    args = (ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(out.data_ptr()), B, H, Lq, Lk, arr,
+            int(out_scale_T), int(band))
+
+    def launch(stream=None):
+        rc = fn(*args, _stream_handle(stream))
+        if rc != 0:
+            _check(rc)
+
+    return launch
+
+
+def prepare_attention(q, k, v, out, table, requant, band, out_scale_T=255):
+    """Same as prepare_softmax for hccs_attention_i8."""
+    B, H, L, d = q.shape
+    arr, Ht = head_table(table)
+    rq, Hr = requant_table(requant)
+    if Ht != H or Hr != H:
+        raise HccsError(-2, "table and requant must have one entry per head")
+    fn = lib().hccs_attention_i8
+    args = (ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr()),
+            ctypes.c_void_p(out.data_ptr()), B, H, L, d, arr, rq, int(out_scale_T), int(band))
+
+    def launch(stream=None):
+        rc = fn(*args, _stream_handle(stream))
+        if rc != 0:
+            _check(rc)
+
+    return launch
+
+
 def attention_i8(q, k, v, table, requant, band, out=None, out_scale_T=255, stream=None):
     """q,k,v: int8 CUDA tensors [B,H,L,d].  Returns O int32 [B,H,L,d]."""
     import torch

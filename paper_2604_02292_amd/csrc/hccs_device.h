@@ -53,20 +53,16 @@ __device__ __forceinline__ int dpp(int v)
 __device__ __forceinline__ int xor16(int v) { return __builtin_amdgcn_ds_swizzle(v, 0x401F); }
 __device__ __forceinline__ int xor32(int v) { return __shfl_xor(v, 32); }
 
-// All-reduce over aligned groups of G lanes (G = 4, 16 or 64).
+// All-reduce over aligned groups of G lanes (G a power of two, 4..64).
 template <int G>
 __device__ __forceinline__ int group_max(int v)
 {
     v = max(v, dpp<0xB1>(v));
     v = max(v, dpp<0x4E>(v));
-    if constexpr (G >= 16) {
-        v = max(v, dpp<0x141>(v));
-        v = max(v, dpp<0x140>(v));
-    }
-    if constexpr (G >= 64) {
-        v = max(v, xor16(v));
-        v = max(v, xor32(v));
-    }
+    if constexpr (G >= 8) v = max(v, dpp<0x141>(v));
+    if constexpr (G >= 16) v = max(v, dpp<0x140>(v));
+    if constexpr (G >= 32) v = max(v, xor16(v));
+    if constexpr (G >= 64) v = max(v, xor32(v));
     return v;
 }
 
@@ -75,14 +71,10 @@ __device__ __forceinline__ int group_sum(int v)
 {
     v += dpp<0xB1>(v);
     v += dpp<0x4E>(v);
-    if constexpr (G >= 16) {
-        v += dpp<0x141>(v);
-        v += dpp<0x140>(v);
-    }
-    if constexpr (G >= 64) {
-        v += xor16(v);
-        v += xor32(v);
-    }
+    if constexpr (G >= 8) v += dpp<0x141>(v);
+    if constexpr (G >= 16) v += dpp<0x140>(v);
+    if constexpr (G >= 32) v += xor16(v);
+    if constexpr (G >= 64) v += xor32(v);
     return v;
 }
 

@@ -9,7 +9,7 @@ namespace hccs {
 // ---------------------------------------------------------------------------
 // Register-resident kernel for rows whose length is a multiple of 16.
 //
-// A row is shared by G adjacent lanes (G = 4, 16 or 64); each lane holds V
+// A row is shared by G adjacent lanes (G a power of two, 4..64); each lane holds V
 // 16-byte vectors of it, vector number v*G + lane_in_group, so one load
 // instruction of a group covers G*16 contiguous bytes.  A wave works on
 // R batches of 64/G rows at once (R*V loads in flight per lane).  The grid is
@@ -21,8 +21,8 @@ namespace hccs {
 // distance to the maximum is (m + 128), a known amount that is taken out of
 // the sum again.
 // ---------------------------------------------------------------------------
-template <int G, int V, int R>
-__global__ __launch_bounds__(256) void hccs_rows_kernel(const int8_t *__restrict__ logits,
+template <int G, int V, int R, int WPB>
+__global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__restrict__ logits,
                                                         uint8_t *__restrict__ probs, int Lq, int n16,
                                                         HeadTable table)
 {
@@ -40,7 +40,7 @@ __global__ __launch_bounds__(256) void hccs_rows_kernel(const int8_t *__restrict
     const int n = n16 * 16;
 
     const size_t slab = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq;
-    const int wave_row0 = ((int)blockIdx.x * 4 + wave) * kRowsPerWave;
+    const int wave_row0 = ((int)blockIdx.x * WPB + wave) * kRowsPerWave;
     if (wave_row0 >= Lq) return;   // whole wave past the slab
     const int row0 = wave_row0 + grp;
 
@@ -161,22 +161,27 @@ __global__ void reciprocal_kernel(const uint32_t *z, uint32_t *rho, int64_t coun
 __global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                                    int64_t count)
 {
-    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    // four vectors per lane, each a fully coalesced 4 KiB block-wide access
+    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    u32x4 v[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k)
-        if (i + k < count) dst[i + k] = src[i + k];
+        if (base + k * 256 < count) v[k] = load_stream(src + base + k * 256);
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        if (base + k * 256 < count) store_stream(dst + base + k * 256, v[k]);
 }
 
 // ---------------------------------------------------------------------------
 // host side: choose the lane-group shape for a row length
 // ---------------------------------------------------------------------------
-template <int G, int V, int R>
+template <int G, int V, int R, int WPB = 4>
 static hipError_t launch_rows(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int n16,
                               const HeadTable &tab, hipStream_t st)
 {
-    constexpr int kRowsPerBlock = 4 * R * (64 / G);
+    constexpr int kRowsPerBlock = WPB * R * (64 / G);
     dim3 grid((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt);
-    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R>), grid, dim3(256), 0, st, x, p, Lq, n16, tab);
+    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R, WPB>), grid, dim3(64 * WPB), 0, st, x, p, Lq, n16, tab);
     return hipGetLastError();
 }
 
@@ -185,14 +190,18 @@ hipError_t launch_softmax_u8(const int8_t *x, uint8_t *p, int Bt, int H, int Lq,
 {
     if (Bt == 0 || Lq == 0) return hipSuccess;
     if (aligned && Lk % 16 == 0 && Lk <= 16384) {
+        // Lane-group width G = the smallest power of two that covers the row with one
+        // 16-byte vector per lane, so that each load instruction reads G*16 contiguous
+        // bytes of a row; beyond 64 lanes the row takes V vectors per lane.  Few rows in
+        // flight per wave (R) and many waves measured faster than the reverse.
         const int n16 = Lk / 16;
-        if (n16 <= 4) return launch_rows<4, 1, 4>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 8) return launch_rows<4, 2, 4>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 16) return launch_rows<16, 1, 8>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 32) return launch_rows<16, 2, 4>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 64) return launch_rows<16, 4, 2>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 128) return launch_rows<64, 2, 4>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 256) return launch_rows<64, 4, 2>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 4) return launch_rows<4, 1, 2>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 8) return launch_rows<8, 1, 2>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 16) return launch_rows<16, 1, 2>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 32) return launch_rows<16, 2, 1>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 64) return launch_rows<64, 1, 2>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 128) return launch_rows<64, 2, 1>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 256) return launch_rows<64, 4, 1>(x, p, Bt, H, Lq, n16, tab, st);
         if (n16 <= 512) return launch_rows<64, 8, 1>(x, p, Bt, H, Lq, n16, tab, st);
         return launch_rows<64, 16, 1>(x, p, Bt, H, Lq, n16, tab, st);
     }
