@@ -40,12 +40,15 @@ def kernel_hash():
 def counter_traffic():
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, or None when
     the kernel sources changed after the counters were taken."""
-    path = os.path.join(ROOT, "profiles", "hccs_rows_edge_encoder_traffic.json")
+    path = os.path.join(ROOT, "profiles", "hccs_rows_edge_encoder_pmc.md")
     if not os.path.exists(path):
         return None
+    rec = None
     with open(path) as fh:
-        rec = json.load(fh)
-    if rec.get("kernel_hash") != kernel_hash():
+        for line in fh:
+            if line.startswith("TRAFFIC_RECORD "):
+                rec = json.loads(line[len("TRAFFIC_RECORD "):])
+    if rec is None or rec.get("kernel_hash") != kernel_hash():
         return None
     return rec.get("traffic_bytes_per_launch")
 

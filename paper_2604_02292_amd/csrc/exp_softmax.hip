@@ -62,14 +62,10 @@ __global__ __launch_bounds__(256) void exp_softmax_kernel(const int8_t *__restri
     // float all-reduce over the lane group, same pairing as the integer helpers
     sum += __builtin_bit_cast(float, dpp<0xB1>(__builtin_bit_cast(int, sum)));
     sum += __builtin_bit_cast(float, dpp<0x4E>(__builtin_bit_cast(int, sum)));
-    if constexpr (G >= 16) {
-        sum += __builtin_bit_cast(float, dpp<0x141>(__builtin_bit_cast(int, sum)));
-        sum += __builtin_bit_cast(float, dpp<0x140>(__builtin_bit_cast(int, sum)));
-    }
-    if constexpr (G >= 64) {
-        sum += __builtin_bit_cast(float, xor16(__builtin_bit_cast(int, sum)));
-        sum += __builtin_bit_cast(float, xor32(__builtin_bit_cast(int, sum)));
-    }
+    if constexpr (G >= 8) sum += __builtin_bit_cast(float, dpp<0x141>(__builtin_bit_cast(int, sum)));
+    if constexpr (G >= 16) sum += __builtin_bit_cast(float, dpp<0x140>(__builtin_bit_cast(int, sum)));
+    if constexpr (G >= 32) sum += __builtin_bit_cast(float, xor16(__builtin_bit_cast(int, sum)));
+    if constexpr (G >= 64) sum += __builtin_bit_cast(float, xor32(__builtin_bit_cast(int, sum)));
     const float inv = 255.0f * __builtin_amdgcn_rcpf(sum);
 
 #pragma unroll
@@ -106,10 +102,10 @@ hipError_t launch_exp_softmax(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
     for (int h = 0; h < HCCS_MAX_HEADS; ++h) sc.e[h] = h < H ? scale[h] : 0.f;
     const int n16 = Lk / 16;
     if (n16 <= 4) return launch_exp<4, 1>(x, p, Bt, H, Lq, n16, sc, st);
-    if (n16 <= 8) return launch_exp<4, 2>(x, p, Bt, H, Lq, n16, sc, st);
+    if (n16 <= 8) return launch_exp<8, 1>(x, p, Bt, H, Lq, n16, sc, st);
     if (n16 <= 16) return launch_exp<16, 1>(x, p, Bt, H, Lq, n16, sc, st);
     if (n16 <= 32) return launch_exp<16, 2>(x, p, Bt, H, Lq, n16, sc, st);
-    if (n16 <= 64) return launch_exp<16, 4>(x, p, Bt, H, Lq, n16, sc, st);
+    if (n16 <= 64) return launch_exp<64, 1>(x, p, Bt, H, Lq, n16, sc, st);
     if (n16 <= 128) return launch_exp<64, 2>(x, p, Bt, H, Lq, n16, sc, st);
     if (n16 <= 256) return launch_exp<64, 4>(x, p, Bt, H, Lq, n16, sc, st);
     if (n16 <= 512) return launch_exp<64, 8>(x, p, Bt, H, Lq, n16, sc, st);
