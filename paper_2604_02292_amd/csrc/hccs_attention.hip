@@ -29,8 +29,19 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 // min(max(x, lo), hi); the compiler selects v_med3_i32 for it
 __device__ __forceinline__ int clamp_i32(int x, int lo, int hi) { return min(max(x, lo), hi); }
 
+// Two signed 16-bit values -> two unsigned bytes, saturated to [0,255], in the low half.
+__device__ __forceinline__ uint32_t sat_pk_u8_i16(uint32_t v)
+{
+    uint32_t d;
+    asm("v_sat_pk_u8_i16 %0, %1" : "=v"(d) : "v"(v));
+    return d;
+}
+
 constexpr int kKStride = 80;   // bytes per K row in LDS: 64 + 16 of padding against bank conflicts
 
+// The HCCS stage works on offset-binary bytes u = x + 128 (x the int8 logit), four per
+// register, with the same byte-parallel steps as the stand-alone kernel: the 64..128 logits
+// a lane owns shrink to 16..32 registers, which is what lets several waves share a SIMD.
 template <int NT, bool PRECLAMP>   // NT = L/16 key tiles (a multiple of 4)
 __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__restrict__ q,
                                                              const int8_t *__restrict__ k,
@@ -55,8 +66,8 @@ __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__res
 
     // ---- stage K row-major (padded rows) -----------------------------------
     for (int c = tid; c < L * 4; c += 256) {
-        const uint4 val = *(const uint4 *)(k + base + (size_t)c * 16);
-        *(uint4 *)(lds_k + (c >> 2) * kKStride + (c & 3) * 16) = val;
+        const u32x4 val = *(const u32x4 *)(k + base + (size_t)c * 16);
+        *(u32x4 *)(lds_k + (c >> 2) * kKStride + (c & 3) * 16) = val;
     }
     __syncthreads();   // colsum zeroed before the atomics below
 
@@ -94,60 +105,66 @@ __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__res
 
     const int qi = lane & 15;      // query inside the 16-row tile / output column group
     const int g = lane >> 4;       // which quarter of the contraction slots this lane feeds
-    const int half = 1 << (shift - 1);
-    // Saturation bound for the accumulator when acc*mult could leave 32 bits: any
-    // |acc| >= lim rescales to a value beyond the int8 range already.
+    // Rescale constant.  Without PRECLAMP the +128 of the offset-binary form rides in it;
+    // with PRECLAMP (acc*mult could leave 32 bits) the accumulator is saturated first --
+    // any |acc| >= lim lands beyond the int8 range anyway -- and the 128 is added in 16 bits.
+    const int round_c = (1 << (shift - 1)) + (PRECLAMP ? 0 : (128 << shift));
     const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 20);
+    const uint32_t D4 = (uint32_t)D * 0x01010101u;
 
     for (int rt = wave; rt < NT; rt += 4) {
-        // ---- A^T tiles = K_tile . Q^T ------------------------------------------
+        // ---- A^T tiles = K_tile . Q^T, rescaled and packed tile by tile ----------------
         const v4i qop = *(const v4i *)(q + base + (size_t)(rt * 16 + qi) * 64 + g * 16);
-        v4i acc[NT];
+        uint32_t xb[NT];           // offset-binary logits of keys 16t + 4g + {0..3}, then their distances
+        int mx = -(1 << 30);       // running maximum of y + 128 before saturation
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const v4i kop = *(const v4i *)(lds_k + (t * 16 + qi) * kKStride + g * 16);
-            acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
-        }
-
-        // ---- rescale to int8 logits (before saturation) and row maximum -----------
-        int mx = -(1 << 30);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
+            const v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
+            int y[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                int a = acc[t][r];
+                int a = acc[r];
                 if constexpr (PRECLAMP) a = clamp_i32(a, -lim, lim);
-                const int y = (__mul24(a, mult) + half) >> shift;
-                acc[t][r] = y;
-                mx = max(mx, y);
+                y[r] = (__mul24(a, mult) + round_c) >> shift;
             }
+            typedef short short2v __attribute__((ext_vector_type(2)));
+            short2v lo16 = __builtin_amdgcn_cvt_pk_i16(y[0], y[1]);   // saturating 32 -> 16
+            short2v hi16 = __builtin_amdgcn_cvt_pk_i16(y[2], y[3]);
+            if constexpr (PRECLAMP) {
+                const short2v c128 = {128, 128};
+                lo16 = __builtin_elementwise_add_sat(lo16, c128);
+                hi16 = __builtin_elementwise_add_sat(hi16, c128);
+                mx = max(mx, max(max(y[0], y[1]), max(y[2], y[3])) + 128);
+            } else {
+                mx = max(mx, max(max(y[0], y[1]), max(y[2], y[3])));
+            }
+            const uint32_t lo8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, lo16));
+            const uint32_t hi8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, hi16));
+            xb[t] = __builtin_amdgcn_perm(hi8, lo8, 0x05040100u);
         }
         mx = max(mx, xor16(mx));
         mx = max(mx, xor32(mx));
-        const int m = min(max(mx, -128), 127);   // saturation is monotone: max of clamped = clamp of max
+        const uint32_t mu = (uint32_t)min(max(mx, 0), 255);   // saturation is monotone: max of clamped = clamp of max
 
-        // ---- x' = max(x, m - D): the logit clamped into the active window; delta = m - x' ----
-        const int lo = max(m - D, -128);
-        int sx = 0;
+        // ---- distances, sum of the clamped ones (same identity as the stand-alone kernel) ----
+        const uint32_t mu4 = mu * 0x01010101u;
+        uint32_t acc_d = 0, acc_abs = 0;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int xc = clamp_i32(acc[t][r], lo, 127);
-                acc[t][r] = xc;
-                sx += xc;
-            }
+            const uint32_t dl = mu4 - xb[t];   // every byte of xb is <= mu: no borrow
+            xb[t] = dl;
+            acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
+            acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
         }
-        sx += xor16(sx);
-        sx += xor32(sx);
-        // Z = sum (B - S*(m - x')) = L*B - S*(L*m - sum x')      (Eq. (3), (5))
-        const uint32_t Z = (uint32_t)(L * B - S * (L * m - sx));
-        const uint32_t rho = reciprocal_u8(Z);
-        // p = ((B - S*(m - x')) * rho) >> 15 = (c1 + a*x') >> 15
-        const int a_ = (int)__umul24((uint32_t)S, rho);
-        const int c1 = (B - S * m) * (int)rho;
+        int tsum = (int)acc_d - (int)acc_abs;
+        tsum += xor16(tsum);
+        tsum += xor32(tsum);
+        const int sum_clamped = (tsum + L * D) / 2;
+        const uint32_t Z = (uint32_t)(L * B - S * sum_clamped);     // Eq. (3), (5)
+        const RowAffine ra = row_affine(Z, B, S, D);
 
-        // ---- pack P - 128 as the A operand, O = P.V ------------------------------------
+        // ---- P - 128 as the A operand, O = P.V ------------------------------------
         v4i oacc[4];
         {
             const v4i cs = *(const v4i *)(lds_colsum + qi * 4);
@@ -161,15 +178,7 @@ __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__res
         for (int T = 0; T < NQ; ++T) {
             v4i pop;
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
-                uint32_t w = 0;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const uint32_t p = (uint32_t)(__mul24(acc[T * 4 + tt][r], a_) + c1) >> 15;
-                    w |= p << (8 * r);
-                }
-                pop[tt] = (int)(w ^ 0x80808080u);
-            }
+            for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(xb[T * 4 + tt], ra) ^ 0x80808080u);
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
                 const v4i vop = *(const v4i *)(lds_v + (((T * 4 + dt) * 4 + g) * 16 + qi) * 16);
@@ -181,7 +190,7 @@ __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__res
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const v4i out = {oacc[0][r], oacc[1][r], oacc[2][r], oacc[3][r]};
-            *(v4i *)(o + base + (size_t)(rt * 16 + g * 4 + r) * 64 + qi * 4) = out;
+            __builtin_nontemporal_store(out, (v4i *)(o + base + (size_t)(rt * 16 + g * 4 + r) * 64 + qi * 4));
         }
     }
 }
@@ -203,11 +212,12 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
                             int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st)
 {
     (void)d;   // 64, checked by the caller
-    // |acc| <= 64*128*128 = 2^20.  If acc*mult + 2^(shift-1) can pass 2^31 for some
-    // head, the accumulator is saturated first (same result, one more instruction).
+    // |acc| <= 64*128*128 = 2^20.  If acc*mult + 2^(shift-1) + 128*2^shift can pass 2^31 for
+    // some head, the accumulator is saturated first (same result, a few more instructions).
     bool preclamp = false;
     for (int h = 0; h < H; ++h) {
-        const int64_t worst = ((int64_t)1 << 20) * rq.e[h].x + ((int64_t)1 << (rq.e[h].y - 1));
+        const int64_t worst = ((int64_t)1 << 20) * rq.e[h].x + ((int64_t)1 << (rq.e[h].y - 1)) +
+                              ((int64_t)128 << rq.e[h].y);
         if (worst > 0x7fffffffll) preclamp = true;
     }
     const int blocks = Bt * H;
