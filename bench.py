@@ -99,9 +99,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--no-extras", action="store_true", help="headline workload only (used for counter runs)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--counter-run", action="store_true",
-                    help="for rocprofv3 --pmc: a few eager launches of the headline kernel and of the "
-                         "plain copy kernel on the same buffers, nothing else")
+    ap.add_argument("--counter-run", choices=["softmax", "attention"], default=None,
+                    help="for rocprofv3 --pmc: --steps eager launches of the headline kernel and of the plain "
+                         "copy kernel on the same buffers (softmax), or of the fused block (attention); nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: rows are independent and shard with no exchange step, "
@@ -116,6 +116,17 @@ def main():
     binding.lib()
     dev = torch.device("cuda:0")
     ncpu = min(os.cpu_count() or 1, 16)
+
+    if args.counter_run == "attention":
+        a = synth.make_workload("fused_attention")
+        q, k, v = (torch.from_numpy(a[t]).to(dev) for t in ("q", "k", "v"))
+        o = torch.empty(a["q"].shape, dtype=torch.int32, device=dev)
+        launch = binding.prepare_attention(q, k, v, o, a["table"], a["requant"], a["band"])
+        for _ in range(args.steps):
+            launch()
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_run": "attention", "launches": args.steps, "shape": list(a["q"].shape)}))
+        return
 
     # ------------------------------------------------------------------ headline workload
     name = "edge_encoder"
@@ -136,7 +147,7 @@ def main():
             launches[i % nsets]()
             binding.copy_bytes(xs[i % nsets], outs[i % nsets])
         torch.cuda.synchronize()
-        print(json.dumps({"counter_run": True, "launches_each": args.steps, "bytes_read_per_launch": elems,
+        print(json.dumps({"counter_run": "softmax", "launches_each": args.steps, "bytes_read_per_launch": elems,
                           "bytes_written_per_launch": elems, "kernel_hash": kernel_hash()}))
         return
     # GRAPH_ROUNDS passes over the buffer sets per graph: one replay costs about 8 us of
@@ -227,7 +238,22 @@ def main():
         result["copy_kernel"] = {"avg_launch_ms": round(mean(ev), 5),
                                  "GBps": round(alg_bytes / (mean(ev) * 1e-3) / 1e9, 1),
                                  "note": "plain 16-byte-per-lane copy of the same buffers"}
-        del xs2, outs2, g2, g3
+        # the other output modes of the row kernel on the same batch (16-bit output: 3 bytes per element)
+        modes = {}
+        out16 = [torch.empty(x0.shape, dtype=torch.int16, device=dev) for _ in range(nsets)]
+        for label, T, recip in (("i16_exact", 32767, 0), ("u8_leading_bit", 255, 1), ("i16_leading_bit", 32767, 1)):
+            dst = out16 if T == 32767 else outs2
+            mk = lambda i: (lambda: binding.calibrated_softmax_i8_ex(xs2[i], table, band, out_scale_T=T,
+                                                                     reciprocal=recip, out=dst[i]))
+            gm = capture(torch, [mk(i) for i in range(nsets)] * GRAPH_ROUNDS)
+            ev = graph_launch_ms(torch, gm, per, 4)
+            nb = elems * (3 if T == 32767 else 2)
+            modes[label] = {"avg_launch_ms": round(mean(ev), 5), "rows_per_s": round(rows / (mean(ev) * 1e-3), 1),
+                            "GBps": round(nb / (mean(ev) * 1e-3) / 1e9, 1),
+                            "frac_of_hbm_peak": round(nb / (mean(ev) * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            del gm
+        result["other_modes"] = modes
+        del xs2, outs2, out16, g2, g3
         torch.cuda.empty_cache()
 
         for other in ("pr1_ref", "stress_rows", "long_row"):

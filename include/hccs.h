@@ -100,6 +100,23 @@ HCCS_API int hccs_calibrated_softmax_i8(const int8_t *logits_dev, uint8_t *probs
                                int32_t Lq, int32_t Lk, const hccs_head_params *table_host,
                                int32_t out_scale_T, int32_t band, void *hip_stream);
 
+/* The other output modes of the same row operation.
+ *   out_scale_T = 255:   out_dev is uint8  [B,H,Lq,Lk], as above.
+ *   out_scale_T = 32767: out_dev is uint16 [B,H,Lq,Lk] (2-byte aligned; 16-byte aligned for the
+ *                        vectorised kernels): Alg. 1 as printed, rho = floor(32767 / Z), p = s * rho
+ *                        (Eq. (6), (7)).  Needs Z <= 32767, so the table is validated against
+ *                        HCCS_BAND_STRICT whatever `band` says.  No in-place use.
+ *   reciprocal = HCCS_RECIP_EXACT: floor division.
+ *   reciprocal = HCCS_RECIP_CLB:   leading-bit approximation of Sec. III-B, Eq. (9):
+ *                        k = floor(log2 Z), rho = floor(255*2^15 / 2^k) resp. floor(32767 / 2^k).
+ *                        The over-estimate (< 2x) can pass T; the result saturates at T (the
+ *                        paper leaves that case open).
+ * Everything else as hccs_calibrated_softmax_i8. */
+HCCS_API int hccs_calibrated_softmax_i8_ex(const int8_t *logits_dev, void *out_dev, int32_t B, int32_t H,
+                                           int32_t Lq, int32_t Lk, const hccs_head_params *table_host,
+                                           int32_t out_scale_T, int32_t reciprocal, int32_t band,
+                                           void *hip_stream);
+
 /* Fused int8 attention block for one tensor set:
  *   A = Q.K^T (int32)  ->  x = requant_h(A) (int8)  ->  P = HCCS_u8(x) row-wise, n = L
  *   ->  O = P.V (int32).  Logits and probabilities never reach HBM.

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libhccs.so")
 BAND_U8, BAND_STRICT = 0, 1
 RECIP_EXACT, RECIP_CLB = 0, 1
 
-EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_attention_i8",
+EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_calibrated_softmax_i8_ex", "hccs_attention_i8",
            "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_copy_bytes", "hccs_status_string"]
 
 
@@ -47,6 +47,8 @@ def lib():
         i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
         L.hccs_validate_params.argtypes = [ctypes.POINTER(HeadParams), i32, i32, i32, ctypes.POINTER(i32)]
         L.hccs_calibrated_softmax_i8.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(HeadParams), i32, i32, vp]
+        L.hccs_calibrated_softmax_i8_ex.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(HeadParams), i32, i32,
+                                                    i32, vp]
         L.hccs_attention_i8.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, ctypes.POINTER(HeadParams),
                                         ctypes.POINTER(Requant), i32, i32, vp]
         L.hccs_exp_softmax_i8_f32.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_float), vp]
@@ -117,6 +119,25 @@ def calibrated_softmax_i8(logits, table, band, out=None, out_scale_T=255, stream
     _check(lib().hccs_calibrated_softmax_i8(ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(out.data_ptr()),
                                             B, H, Lq, Lk, arr, int(out_scale_T), int(band),
                                             _stream_handle(stream)))
+    return out
+
+
+def calibrated_softmax_i8_ex(logits, table, band, out_scale_T=255, reciprocal=RECIP_EXACT, out=None, stream=None):
+    """Any output mode: uint8 result for out_scale_T = 255, uint16 (held in an int16 tensor,
+    values 0..32767) for out_scale_T = 32767; exact or leading-bit reciprocal."""
+    import torch
+    assert logits.is_cuda and logits.dtype == torch.int8 and logits.is_contiguous() and logits.dim() == 4
+    dtype = torch.uint8 if out_scale_T == 255 else torch.int16
+    if out is None:
+        out = torch.empty(logits.shape, dtype=dtype, device=logits.device)
+    assert out.is_cuda and out.is_contiguous() and out.shape == logits.shape
+    B, H, Lq, Lk = logits.shape
+    arr, Ht = head_table(table)
+    if Ht != H:
+        raise HccsError(-2, "table must have one entry per head")
+    _check(lib().hccs_calibrated_softmax_i8_ex(ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                               B, H, Lq, Lk, arr, int(out_scale_T), int(reciprocal), int(band),
+                                               _stream_handle(stream)))
     return out
 
 

@@ -5,8 +5,8 @@
 #include "hccs_device.h"
 
 namespace hccs {
-hipError_t launch_softmax_u8(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
-                             bool aligned, hipStream_t st);
+hipError_t launch_softmax(const int8_t *x, void *out, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
+                          int mode, bool vector_ok, hipStream_t st);
 hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hipStream_t st);
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
 hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
@@ -61,28 +61,43 @@ int hccs_validate_params(const hccs_head_params *table_host, int32_t H, int32_t 
     return HCCS_OK;
 }
 
-int hccs_calibrated_softmax_i8(const int8_t *logits_dev, uint8_t *probs_dev, int32_t B, int32_t H, int32_t Lq,
-                               int32_t Lk, const hccs_head_params *table_host, int32_t out_scale_T, int32_t band,
-                               void *hip_stream)
+int hccs_calibrated_softmax_i8_ex(const int8_t *logits_dev, void *out_dev, int32_t B, int32_t H, int32_t Lq,
+                                  int32_t Lk, const hccs_head_params *table_host, int32_t out_scale_T,
+                                  int32_t reciprocal, int32_t band, void *hip_stream)
 {
     if (!table_host) return HCCS_E_NULL;
     if (B < 0 || B > 65535 || H < 1 || H > HCCS_MAX_HEADS || Lq < 0 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH)
         return HCCS_E_SHAPE;
-    if (out_scale_T != 255) return HCCS_E_SCALE;
-    const int rc = hccs_validate_params(table_host, H, Lk, band, nullptr);
+    if (out_scale_T != 255 && out_scale_T != 32767) return HCCS_E_SCALE;
+    if (reciprocal != HCCS_RECIP_EXACT && reciprocal != HCCS_RECIP_CLB) return HCCS_E_SCALE;
+    if (band != HCCS_BAND_U8 && band != HCCS_BAND_STRICT) return HCCS_E_SCALE;
+    const bool wide = (out_scale_T == 32767);
+    // the 16-bit path needs Z <= 32767 whatever band the caller named (Sec. IV-C, last item)
+    const int rc = hccs_validate_params(table_host, H, Lk, wide ? HCCS_BAND_STRICT : band, nullptr);
     if (rc != HCCS_OK) return rc;
-    const bool empty = (B == 0 || Lq == 0);
-    if (!empty && (!logits_dev || !probs_dev)) return HCCS_E_NULL;
-    if (empty) return HCCS_OK;
-    const int64_t bytes = (int64_t)B * H * Lq * Lk;
-    const uintptr_t a = (uintptr_t)logits_dev, b = (uintptr_t)probs_dev;
-    if (a != b && a < b + (uint64_t)bytes && b < a + (uint64_t)bytes) return HCCS_E_ALIGN;  // partial overlap
+    if (B == 0 || Lq == 0) return HCCS_OK;
+    if (!logits_dev || !out_dev) return HCCS_E_NULL;
+    const uint64_t in_bytes = (uint64_t)B * H * Lq * Lk, out_bytes = in_bytes * (wide ? 2 : 1);
+    const uintptr_t a = (uintptr_t)logits_dev, b = (uintptr_t)out_dev;
+    const bool same = (a == b) && !wide;                       // in place: 8-bit modes only
+    if (!same && a < b + out_bytes && b < a + in_bytes) return HCCS_E_ALIGN;   // overlapping buffers
+    if (wide && (b & 1u)) return HCCS_E_ALIGN;
     hccs::HeadTable tab;
     fill_table(table_host, H, tab);
-    const bool aligned = aligned16(logits_dev) && aligned16(probs_dev);
+    const int mode = (wide ? 1 : 0) | (reciprocal == HCCS_RECIP_CLB ? 2 : 0);
+    const bool vector_ok = aligned16(logits_dev) && aligned16(out_dev);
     const hipError_t e =
-        hccs::launch_softmax_u8(logits_dev, probs_dev, B, H, Lq, Lk, tab, aligned, (hipStream_t)hip_stream);
+        hccs::launch_softmax(logits_dev, out_dev, B, H, Lq, Lk, tab, mode, vector_ok, (hipStream_t)hip_stream);
     return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+int hccs_calibrated_softmax_i8(const int8_t *logits_dev, uint8_t *probs_dev, int32_t B, int32_t H, int32_t Lq,
+                               int32_t Lk, const hccs_head_params *table_host, int32_t out_scale_T, int32_t band,
+                               void *hip_stream)
+{
+    if (out_scale_T != 255) return HCCS_E_SCALE;
+    return hccs_calibrated_softmax_i8_ex(logits_dev, probs_dev, B, H, Lq, Lk, table_host, 255, HCCS_RECIP_EXACT,
+                                         band, hip_stream);
 }
 
 int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev, int32_t B,

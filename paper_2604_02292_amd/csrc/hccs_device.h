@@ -28,13 +28,27 @@ struct RequantTable {
 // The loads and stores are marked non-temporal: every byte is touched once.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+#ifndef HCCS_STREAM_LOAD_NT
+#define HCCS_STREAM_LOAD_NT 1
+#endif
+#ifndef HCCS_STREAM_STORE_NT
+#define HCCS_STREAM_STORE_NT 1
+#endif
 __device__ __forceinline__ u32x4 load_stream(const void *p)
 {
+#if HCCS_STREAM_LOAD_NT
     return __builtin_nontemporal_load((const u32x4 *)p);
+#else
+    return *(const u32x4 *)p;
+#endif
 }
 __device__ __forceinline__ void store_stream(void *p, u32x4 v)
 {
+#if HCCS_STREAM_STORE_NT
     __builtin_nontemporal_store(v, (u32x4 *)p);
+#else
+    *(u32x4 *)p = v;
+#endif
 }
 constexpr uint32_t kPadWord = 0x80808080u;   // four logits of -128
 
@@ -78,23 +92,57 @@ __device__ __forceinline__ int group_sum(int v)
     return v;
 }
 
-// ---- the reciprocal of Eq. (8) -------------------------------------------
-// rho = floor(255*2^15 / Z) for 256 <= Z <= 255*2^15.  Numerator and Z are below
-// 2^24, so both are exact in float; the hardware reciprocal is good to 1 ulp and
-// the quotient is at most 32640, so the truncated float quotient is within one
-// of the true one.  The remainder test repairs it in either direction, which
-// makes the result the exact floor.
-__device__ __forceinline__ uint32_t reciprocal_u8(uint32_t Z)
+// ---- exact integer division ------------------------------------------------
+// floor(N / Z) for 1 <= Z <= N < 2^24 with a quotient below 2^16.  N and Z are
+// exact in float, the hardware reciprocal is good to 1 ulp, so the truncated float
+// quotient is within one of the true one; the remainder test repairs it in
+// either direction, which makes the result the exact floor.
+__device__ __forceinline__ uint32_t floor_div(uint32_t N, uint32_t Z)
 {
-    float qf = (float)kRecipNumerator * __builtin_amdgcn_rcpf((float)Z);
+    float qf = (float)N * __builtin_amdgcn_rcpf((float)Z);
     uint32_t q = (uint32_t)qf;
-    int32_t rem = (int32_t)kRecipNumerator - (int32_t)__umul24(q, Z);
+    int32_t rem = (int32_t)N - (int32_t)__umul24(q, Z);
     if (rem < 0) {
         q -= 1;
         rem += (int32_t)Z;
     }
     if (rem >= (int32_t)Z) q += 1;
     return q;
+}
+
+// The reciprocal of Eq. (8): rho = floor(255*2^15 / Z), 256 <= Z <= 255*2^15, so rho <= 32640.
+__device__ __forceinline__ uint32_t reciprocal_u8(uint32_t Z) { return floor_div(kRecipNumerator, Z); }
+
+// Output modes: scale T (Sec. III-B) x reciprocal kind.
+enum : int {
+    kModeU8 = 0,      // T = 255,   rho = floor(255*2^15 / Z), p = (s*rho) >> 15      Eq. (8)
+    kModeI16 = 1,     // T = 32767, rho = floor(32767 / Z),    p = s*rho              Eq. (6), (7)
+    kModeClbU8 = 2,   // T = 255,   rho = floor(255*2^15 / 2^k), k = floor(log2 Z), p saturated at 255   Eq. (9)
+    kModeClbI16 = 3   // T = 32767, rho = floor(32767 / 2^k),  p saturated at 32767                      Eq. (9)
+};
+
+// rho for a mode.  Leading-bit modes replace the division by a shift taken from the
+// position of the highest set bit of Z.
+template <int MODE>
+__device__ __forceinline__ uint32_t reciprocal_for_mode(uint32_t Z)
+{
+    if constexpr (MODE == kModeU8) return reciprocal_u8(Z);
+    if constexpr (MODE == kModeI16) return floor_div(32767u, Z);
+    const int k = 31 - __builtin_clz(Z);
+    if constexpr (MODE == kModeClbU8) return kRecipNumerator >> k;
+    return 32767u >> k;
+}
+
+// Scalar form of the last step for one score (used by the byte kernel and the
+// leading-bit 8-bit path): s*rho stays below 2^24 in every mode.
+template <int MODE>
+__device__ __forceinline__ uint32_t scale_score(uint32_t s, uint32_t rho)
+{
+    const uint32_t prod = __umul24(s, rho);
+    if constexpr (MODE == kModeU8) return prod >> 15;
+    if constexpr (MODE == kModeI16) return prod;
+    if constexpr (MODE == kModeClbU8) return min(prod >> 15, 255u);
+    return min(prod, 32767u);
 }
 
 // ---- per-row constants of the normalise stage -----------------------------
@@ -177,6 +225,28 @@ struct ByteMax {
 __device__ __forceinline__ uint32_t distance4(uint32_t x4, uint32_t neg_base4)
 {
     return (x4 ^ 0x7f7f7f7fu) + neg_base4;   // neg_base4 = -(127 - m) * 0x01010101
+}
+
+// ---- 16-bit packed arithmetic (two elements per instruction) -------------------
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+
+// bytes (b0,b1) or (b2,b3) of a dword, zero-extended to two 16-bit lanes
+__device__ __forceinline__ ushort2_t bytes_lo_pair(uint32_t w)
+{
+    return __builtin_bit_cast(ushort2_t, __builtin_amdgcn_perm(0u, w, 0x0c010c00u));
+}
+__device__ __forceinline__ ushort2_t bytes_hi_pair(uint32_t w)
+{
+    return __builtin_bit_cast(ushort2_t, __builtin_amdgcn_perm(0u, w, 0x0c030c02u));
+}
+
+// Scores of two elements from their unclamped distances: s = B - S*min(delta, Dmax)
+// (Eq. (2), (3)); s <= 32767, arithmetic modulo 2^16.
+__device__ __forceinline__ ushort2_t scores2(ushort2_t delta, unsigned short D, unsigned short negS,
+                                             unsigned short B)
+{
+    const ushort2_t d2 = {D, D}, s2 = {negS, negS}, b2 = {B, B};
+    return __builtin_elementwise_min(delta, d2) * s2 + b2;
 }
 
 }  // namespace hccs

@@ -1,10 +1,42 @@
-// Row-wise HCCS on int8 logits -> uint8 probabilities (Alg. 1 with the 8-bit
-// output path of Sec. III-B).  One HBM read and one HBM write per element; the
-// three logical sweeps over a row (maximum, scores and sum, normalise) run on
-// registers.
+// Row-wise HCCS on int8 logits (Alg. 1).  Output modes: 8-bit (Sec. III-B "int8
+// output path", Eq. (8)) or 16-bit (Eq. (6), (7)), each with the exact or the
+// leading-bit reciprocal (Eq. (9)).  One HBM read per element and one HBM write
+// of the output width; the three logical sweeps over a row (maximum, scores and
+// sum, normalise) run on registers.
 #include "hccs_device.h"
 
 namespace hccs {
+
+// Output of four elements (one dword of distances) in a 16-bit mode: two dwords.
+template <int MODE>
+__device__ __forceinline__ void normalise4_wide(uint32_t delta4, int B, int S, int D, uint32_t rho,
+                                                uint32_t &out_lo, uint32_t &out_hi)
+{
+    const unsigned short negS = (unsigned short)(0 - S);
+    const ushort2_t r2 = {(unsigned short)rho, (unsigned short)rho};
+    ushort2_t lo = scores2(bytes_lo_pair(delta4), (unsigned short)D, negS, (unsigned short)B) * r2;
+    ushort2_t hi = scores2(bytes_hi_pair(delta4), (unsigned short)D, negS, (unsigned short)B) * r2;
+    if constexpr (MODE == kModeClbI16) {
+        // s < 2^(k+1) and rho < 2^(15-k): the product fits 16 bits, then saturates at T
+        const ushort2_t cap = {32767, 32767};
+        lo = __builtin_elementwise_min(lo, cap);
+        hi = __builtin_elementwise_min(hi, cap);
+    }
+    out_lo = __builtin_bit_cast(uint32_t, lo);
+    out_hi = __builtin_bit_cast(uint32_t, hi);
+}
+
+// Leading-bit 8-bit mode: s*rho can reach 2x the exact product, so the pack trick of
+// the exact path (which needs p - pmin <= 255) does not apply; plain integer form.
+__device__ __forceinline__ uint32_t normalise4_clb_u8(uint32_t delta4, int B, int S, int D, uint32_t rho)
+{
+    const unsigned short negS = (unsigned short)(0 - S);
+    const ushort2_t lo = scores2(bytes_lo_pair(delta4), (unsigned short)D, negS, (unsigned short)B);
+    const ushort2_t hi = scores2(bytes_hi_pair(delta4), (unsigned short)D, negS, (unsigned short)B);
+    const uint32_t p0 = scale_score<kModeClbU8>(lo.x, rho), p1 = scale_score<kModeClbU8>(lo.y, rho);
+    const uint32_t p2 = scale_score<kModeClbU8>(hi.x, rho), p3 = scale_score<kModeClbU8>(hi.y, rho);
+    return p0 | (p1 << 8) | (p2 << 16) | (p3 << 24);
+}
 
 // ---------------------------------------------------------------------------
 // Register-resident kernel for rows whose length is a multiple of 16.
@@ -21,14 +53,15 @@ namespace hccs {
 // distance to the maximum is (m + 128), a known amount that is taken out of
 // the sum again.
 // ---------------------------------------------------------------------------
-template <int G, int V, int R, int WPB>
+template <int G, int V, int R, int WPB, int MODE>
 __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__restrict__ logits,
-                                                        uint8_t *__restrict__ probs, int Lq, int n16,
-                                                        HeadTable table)
+                                                             uint8_t *__restrict__ out, int Lq, int n16,
+                                                             HeadTable table)
 {
     constexpr int kRowsPerBatch = 64 / G;
     constexpr int kRowsPerWave = R * kRowsPerBatch;
     constexpr int kPaddedLen = G * V * 16;
+    constexpr int kOutBytes = (MODE & 1) ? 2 : 1;   // bytes per output element
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -96,17 +129,42 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
 
         // stages 3-5: Z = n*B - S*sum min(delta, D)  (Eq. (3), (5)), reciprocal, normalise
         const uint32_t Z = (uint32_t)(n * B - S * sum_clamped);
-        const RowAffine ra = row_affine(Z, B, S, D);
-
         const int row = row0 + j * kRowsPerBatch;
-        uint8_t *dst = probs + (slab + row) * (size_t)n;
+        uint8_t *dst = out + (slab + row) * (size_t)n * kOutBytes;
+
+        if constexpr (MODE == kModeU8) {
+            const RowAffine ra = row_affine(Z, B, S, D);
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-            const int vi = v * G + sub;
-            u32x4 o;
+            for (int v = 0; v < V; ++v) {
+                const int vi = v * G + sub;
+                u32x4 o;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) o[c] = normalise4(d[j][v][c], ra);
-            if (row < Lq && vi < n16) store_stream(dst + vi * 16, o);
+                for (int c = 0; c < 4; ++c) o[c] = normalise4(d[j][v][c], ra);
+                if (row < Lq && vi < n16) store_stream(dst + vi * 16, o);
+            }
+        } else if constexpr (MODE == kModeClbU8) {
+            const uint32_t rho = reciprocal_for_mode<MODE>(Z);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const int vi = v * G + sub;
+                u32x4 o;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) o[c] = normalise4_clb_u8(d[j][v][c], B, S, D, rho);
+                if (row < Lq && vi < n16) store_stream(dst + vi * 16, o);
+            }
+        } else {
+            const uint32_t rho = reciprocal_for_mode<MODE>(Z);
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const int vi = v * G + sub;
+                uint32_t w[8];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) normalise4_wide<MODE>(d[j][v][c], B, S, D, rho, w[2 * c], w[2 * c + 1]);
+                if (row < Lq && vi < n16) {
+                    store_stream(dst + vi * 32, (u32x4){w[0], w[1], w[2], w[3]});
+                    store_stream(dst + vi * 32 + 16, (u32x4){w[4], w[5], w[6], w[7]});
+                }
+            }
         }
     }
 }
@@ -117,8 +175,9 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
 // has a path.  Three passes over the row (the second and third re-read it
 // through the caches), LDS for the cross-wave maximum and sum.
 // ---------------------------------------------------------------------------
+template <int MODE>
 __global__ __launch_bounds__(256) void hccs_row_bytes_kernel(const int8_t *__restrict__ logits,
-                                                             uint8_t *__restrict__ probs, int Lq, int n,
+                                                             uint8_t *__restrict__ out, int Lq, int n,
                                                              HeadTable table)
 {
     __shared__ int red[4];
@@ -128,7 +187,6 @@ __global__ __launch_bounds__(256) void hccs_row_bytes_kernel(const int8_t *__res
     const int B = hp.x, S = hp.y, D = hp.z;
     const size_t row = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq + blockIdx.x;
     const int8_t *x = logits + row * (size_t)n;
-    uint8_t *p = probs + row * (size_t)n;
 
     int m = -128;
     for (int i = threadIdx.x; i < n; i += 256) m = max(m, (int)x[i]);
@@ -144,11 +202,15 @@ __global__ __launch_bounds__(256) void hccs_row_bytes_kernel(const int8_t *__res
     if (lane == 0) red[wave] = z;
     __syncthreads();
     const uint32_t Z = (uint32_t)(red[0] + red[1] + red[2] + red[3]);
-    const uint32_t rho = reciprocal_u8(Z);
-    // every thread reads only the bytes it later overwrites, so in-place use is safe
+    const uint32_t rho = reciprocal_for_mode<MODE>(Z);
+    // 8-bit modes: every thread reads only the bytes it later overwrites, so in-place use is safe
     for (int i = threadIdx.x; i < n; i += 256) {
         const uint32_t s = (uint32_t)(B - S * min(m - (int)x[i], D));
-        p[i] = (uint8_t)((s * rho) >> 15);
+        const uint32_t p = scale_score<MODE>(s, rho);
+        if constexpr (MODE & 1)
+            ((uint16_t *)out)[row * (size_t)n + i] = (uint16_t)p;
+        else
+            out[row * (size_t)n + i] = (uint8_t)p;
     }
 }
 
@@ -175,39 +237,53 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src
 // ---------------------------------------------------------------------------
 // host side: choose the lane-group shape for a row length
 // ---------------------------------------------------------------------------
-template <int G, int V, int R, int WPB = 4>
+template <int G, int V, int R, int WPB = 4, int MODE = kModeU8>
 static hipError_t launch_rows(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int n16,
                               const HeadTable &tab, hipStream_t st)
 {
     constexpr int kRowsPerBlock = WPB * R * (64 / G);
     dim3 grid((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt);
-    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R, WPB>), grid, dim3(64 * WPB), 0, st, x, p, Lq, n16, tab);
+    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R, WPB, MODE>), grid, dim3(64 * WPB), 0, st, x, p, Lq, n16, tab);
     return hipGetLastError();
 }
 
-hipError_t launch_softmax_u8(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk,
-                             const HeadTable &tab, bool aligned, hipStream_t st)
+template <int MODE>
+static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
+                              bool vector_ok, hipStream_t st)
 {
-    if (Bt == 0 || Lq == 0) return hipSuccess;
-    if (aligned && Lk % 16 == 0 && Lk <= 16384) {
+    if (vector_ok && Lk % 16 == 0 && Lk <= 16384) {
         // Lane-group width G = the smallest power of two that covers the row with one
         // 16-byte vector per lane, so that each load instruction reads G*16 contiguous
         // bytes of a row; beyond 64 lanes the row takes V vectors per lane.  Few rows in
         // flight per wave (R) and many waves measured faster than the reverse.
         const int n16 = Lk / 16;
-        if (n16 <= 4) return launch_rows<4, 1, 2>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 8) return launch_rows<8, 1, 2>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 16) return launch_rows<16, 1, 2>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 32) return launch_rows<16, 2, 1>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 64) return launch_rows<64, 1, 2>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 128) return launch_rows<64, 2, 1>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 256) return launch_rows<64, 4, 1>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 512) return launch_rows<64, 8, 1>(x, p, Bt, H, Lq, n16, tab, st);
-        return launch_rows<64, 16, 1>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 4) return launch_rows<4, 1, 2, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 8) return launch_rows<8, 1, 2, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 16) return launch_rows<16, 1, 2, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 32) return launch_rows<16, 2, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 64) return launch_rows<64, 1, 2, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 128) return launch_rows<64, 2, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 256) return launch_rows<64, 4, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        if (n16 <= 512) return launch_rows<64, 8, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        return launch_rows<64, 16, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
     }
     dim3 grid(Lq, H, Bt);
-    hipLaunchKernelGGL(hccs_row_bytes_kernel, grid, dim3(256), 0, st, x, p, Lq, Lk, tab);
+    hipLaunchKernelGGL(hccs_row_bytes_kernel<MODE>, grid, dim3(256), 0, st, x, p, Lq, Lk, tab);
     return hipGetLastError();
+}
+
+hipError_t launch_softmax(const int8_t *x, void *out, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
+                          int mode, bool vector_ok, hipStream_t st)
+{
+    if (Bt == 0 || Lq == 0) return hipSuccess;
+    uint8_t *p = (uint8_t *)out;
+    switch (mode) {
+        case kModeU8: return launch_mode<kModeU8>(x, p, Bt, H, Lq, Lk, tab, vector_ok, st);
+        case kModeI16: return launch_mode<kModeI16>(x, p, Bt, H, Lq, Lk, tab, vector_ok, st);
+        case kModeClbU8: return launch_mode<kModeClbU8>(x, p, Bt, H, Lq, Lk, tab, vector_ok, st);
+        case kModeClbI16: return launch_mode<kModeClbI16>(x, p, Bt, H, Lq, Lk, tab, vector_ok, st);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hipStream_t st)

@@ -142,6 +142,88 @@ def test_other_stream(oracle):
     assert np.array_equal(out.cpu().numpy(), want)
 
 
+# ---------------------------------------------------------------- 16-bit output and leading-bit reciprocal
+MODES = {"i16": (32767, 0, 1), "clb_u8": (255, 1, 2), "clb_i16": (32767, 1, 3)}   # name -> (T, reciprocal, oracle mode)
+MODE_SHAPES = [
+    ((1, 4, 64, 64), 1), ((3, 8, 37, 128), 1), ((2, 3, 50, 16), 1), ((2, 2, 20, 48), 1), ((1, 3, 9, 256), 1),
+    ((2, 12, 40, 512), 1), ((1, 2, 3, 4096), 1), ((1, 1, 2, 16384), 1), ((1, 2, 7, 208), 1), ((1, 2, 6, 880), 1),
+    ((1, 2, 5, 100), 1), ((1, 1, 4, 17), 1), ((1, 2, 3, 1), 1), ((1, 1, 2, 20000), 1),
+    ((1, 2, 5, 1024), 0), ((1, 2, 3, 4096), 0), ((1, 1, 3, 255), 0),
+]
+
+
+@pytest.mark.parametrize("mode", sorted(MODES))
+@pytest.mark.parametrize("shape,band", MODE_SHAPES)
+def test_softmax_other_modes(oracle, mode, shape, band):
+    T, recip, omode = MODES[mode]
+    if T == 32767 and band != 1:
+        pytest.skip("the 16-bit path exists under the strict band only")
+    H, n = shape[1], shape[3]
+    table = synth.head_params(H, n, band, seed=n + 7 * H)
+    x = mixed_logits(shape, seed=sum(shape) + omode)
+    print(f"case mode={mode} shape={shape} band={band}", flush=True)
+    want, rc = oracle.softmax(x, table, band, mode=omode, threads=THREADS)
+    assert rc == 0
+    got = binding.calibrated_softmax_i8_ex(torch.from_numpy(x).cuda(), table, band, out_scale_T=T, reciprocal=recip)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    if T == 32767:
+        got = got.view(np.uint16)
+    assert got.dtype == want.dtype
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        i = tuple(bad[0])
+        raise AssertionError(f"{mode}: {bad.shape[0]} mismatches, first at {i}: got {got[i]} want {want[i]} "
+                             f"params={table[i[1]].tolist()}")
+
+
+@pytest.mark.parametrize("mode", sorted(MODES))
+def test_other_modes_degenerate_and_saturating(oracle, mode):
+    """Rows that make the leading-bit reciprocal overshoot (one dominant element, Z just below a
+    power of two) and the extremes of the int8 range."""
+    T, recip, omode = MODES[mode]
+    n = 64
+    shape = (1, 4, 16, n)
+    x = mixed_logits(shape, seed=77)
+    x[0, :, 0] = -128
+    x[0, :, 0, 5] = 127
+    x[0, :, 1] = 127
+    x[0, :, 2, ::2] = -128
+    table = np.array([[511, 3, 127], [500, 3, 127], [511, 0, 1], [260, 2, 127]], np.int32)
+    assert binding.validate_params(table, n, 1) == (0, -1)
+    want, rc = oracle.softmax(x, table, 1, mode=omode)
+    assert rc == 0
+    got = binding.calibrated_softmax_i8_ex(torch.from_numpy(x).cuda(), table, 1, out_scale_T=T, reciprocal=recip)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    got = got.view(np.uint16) if T == 32767 else got
+    assert np.array_equal(got, want)
+    # n = 16, one dominant element: s = [1100, 20, ...], Z = 1400, k = 10 -> 1100*rho overshoots T
+    x16 = np.full((1, 1, 8, 16), -128, np.int8)
+    x16[0, 0, :, 3] = 100
+    x16[0, 0, 4:, 7] = 99
+    t16 = np.array([[1100, 12, 90]], np.int32)
+    assert binding.validate_params(t16, 16, 1) == (0, -1)
+    want, rc = oracle.softmax(x16, t16, 1, mode=omode)
+    assert rc == 0
+    got = binding.calibrated_softmax_i8_ex(torch.from_numpy(x16).cuda(), t16, 1, out_scale_T=T, reciprocal=recip)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    got = got.view(np.uint16) if T == 32767 else got
+    assert np.array_equal(got, want)
+    if recip == 1:
+        assert (want == T).any(), "the case was meant to reach saturation"
+
+
+def test_edge_encoder_full_size_i16(oracle):
+    w = synth.make_workload("edge_encoder", threads=THREADS)
+    want, rc = oracle.softmax(w["logits"], w["table"], 1, mode=1, threads=THREADS)
+    assert rc == 0
+    got = binding.calibrated_softmax_i8_ex(torch.from_numpy(w["logits"]).cuda(), w["table"], 1, out_scale_T=32767)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().view(np.uint16), want)
+
+
 # ---------------------------------------------------------------- the named workloads
 @pytest.mark.parametrize("name,shape", [
     ("pr1_ref", None), ("edge_encoder", (4, 8, 128, 128)), ("stress_rows", (2, 12, 512, 512)),

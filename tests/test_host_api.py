@@ -105,6 +105,25 @@ def test_softmax_rejections_launch_nothing(lib):
     assert _softmax_rc(lib, 0, 0, 1, 1, 0, 64, ok) == 0
 
 
+def test_ex_entry_point_rejections(lib):
+    vp = ctypes.c_void_p
+    ok, _ = binding.head_table([[511, 0, 1]])
+
+    def call(a=4096, b=1 << 20, B=1, H=1, Lq=4, Lk=64, tab=ok, T=255, recip=0, band=1):
+        return lib.hccs_calibrated_softmax_i8_ex(vp(a), vp(b), B, H, Lq, Lk, tab, T, recip, band, None)
+
+    assert call(T=100) == -4 and call(recip=2) == -4 and call(band=5) == -4
+    assert call(a=0) == -1
+    assert call(T=32767, b=(1 << 20) + 1) == -3                   # odd address for 16-bit output
+    assert call(T=32767, a=4096, b=4096) == -3                    # no in-place use in the 16-bit modes
+    assert call(T=32767, a=4096, b=4096 + 128) == -3              # overlapping
+    assert call(T=255, a=4096, b=4096 + 128) == -3
+    # the 16-bit path enforces the strict band even if the caller names the wider one
+    wide, _ = binding.head_table([[512, 0, 1]])
+    assert call(tab=wide, band=0, T=255, a=0, b=0, B=0) == 0
+    assert call(tab=wide, band=0, T=32767, a=0, b=0, B=0) == -7
+
+
 def test_attention_rejections_launch_nothing(lib):
     arr, _ = binding.head_table([[127, 1, 126]])
     rq, _ = binding.requant_table([[128, 16]])
