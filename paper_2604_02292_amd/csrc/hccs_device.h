@@ -50,6 +50,15 @@ __device__ __forceinline__ void store_stream(void *p, u32x4 v)
     *(u32x4 *)p = v;
 #endif
 }
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x2 load_stream8(const void *p)
+{
+#if HCCS_STREAM_LOAD_NT
+    return __builtin_nontemporal_load((const u32x2 *)p);
+#else
+    return *(const u32x2 *)p;
+#endif
+}
 constexpr uint32_t kPadWord = 0x80808080u;   // four logits of -128
 
 // ---- cross-lane movement -------------------------------------------------

@@ -42,11 +42,12 @@ __device__ __forceinline__ uint32_t normalise4_clb_u8(uint32_t delta4, int B, in
 // Register-resident kernel for rows whose length is a multiple of 16.
 //
 // A row is shared by G adjacent lanes (G a power of two, 4..64); each lane holds V
-// 16-byte vectors of it, vector number v*G + lane_in_group, so one load
-// instruction of a group covers G*16 contiguous bytes.  A wave works on
-// R batches of 64/G rows at once (R*V loads in flight per lane).  The grid is
-// (row tiles, H, B): a block never straddles heads, so the head's constants are
-// wave-uniform.
+// vectors of it, vector number v*G + lane_in_group, so one load instruction of a
+// group covers G contiguous vectors.  A vector is 16 input bytes in the 8-bit modes
+// and 8 input bytes in the 16-bit modes, i.e. always 16 output bytes: every store
+// instruction of a group writes G*16 contiguous bytes.  A wave works on R batches
+// of 64/G rows at once (R*V loads in flight per lane).  The grid is (row tiles, H,
+// B): a block never straddles heads, so the head's constants are wave-uniform.
 //
 // Vectors past the end of a short row, and rows past the end of the slab, are
 // replaced by the byte -128: that is the identity of the maximum, and its
@@ -55,13 +56,15 @@ __device__ __forceinline__ uint32_t normalise4_clb_u8(uint32_t delta4, int B, in
 // ---------------------------------------------------------------------------
 template <int G, int V, int R, int WPB, int MODE>
 __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__restrict__ logits,
-                                                             uint8_t *__restrict__ out, int Lq, int n16,
+                                                             uint8_t *__restrict__ out, int Lq, int nvec,
                                                              HeadTable table)
 {
     constexpr int kRowsPerBatch = 64 / G;
     constexpr int kRowsPerWave = R * kRowsPerBatch;
-    constexpr int kPaddedLen = G * V * 16;
     constexpr int kOutBytes = (MODE & 1) ? 2 : 1;   // bytes per output element
+    constexpr int DW = 4 / kOutBytes;               // dwords per input vector
+    constexpr int kVecBytes = DW * 4;
+    constexpr int kPaddedLen = G * V * kVecBytes;
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -70,14 +73,14 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
     const int head = blockIdx.y;
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
-    const int n = n16 * 16;
+    const int n = nvec * kVecBytes;
 
     const size_t slab = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq;
     const int wave_row0 = ((int)blockIdx.x * WPB + wave) * kRowsPerWave;
     if (wave_row0 >= Lq) return;   // whole wave past the slab
     const int row0 = wave_row0 + grp;
 
-    u32x4 d[R][V];
+    uint32_t d[R][V][DW];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const int row = row0 + j * kRowsPerBatch;
@@ -85,10 +88,18 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             const int vi = v * G + sub;
-            if (row < Lq && vi < n16)
-                d[j][v] = load_stream(src + vi * 16);
-            else
-                d[j][v] = (u32x4){kPadWord, kPadWord, kPadWord, kPadWord};
+            if (row < Lq && vi < nvec) {
+                if constexpr (DW == 4) {
+                    const u32x4 t = load_stream(src + vi * 16);
+                    d[j][v][0] = t[0], d[j][v][1] = t[1], d[j][v][2] = t[2], d[j][v][3] = t[3];
+                } else {
+                    const u32x2 t = load_stream8(src + vi * 8);
+                    d[j][v][0] = t[0], d[j][v][1] = t[1];
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < DW; ++c) d[j][v][c] = kPadWord;
+            }
         }
     }
 
@@ -98,13 +109,12 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
         // stage 1: row maximum (Alg. 1, first step)
         ByteMax bm;
         bm.init(d[j][0][0]);
-        bm.add(d[j][0][1]);
-        bm.add(d[j][0][2]);
-        bm.add(d[j][0][3]);
+#pragma unroll
+        for (int c = 1; c < DW; ++c) bm.add(d[j][0][c]);
 #pragma unroll
         for (int v = 1; v < V; ++v) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) bm.add(d[j][v][c]);
+            for (int c = 0; c < DW; ++c) bm.add(d[j][v][c]);
         }
         const int m = group_max<G>(bm.result());
         const uint32_t mu = (uint32_t)(m + 128);
@@ -116,7 +126,7 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
 #pragma unroll
         for (int v = 0; v < V; ++v) {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
+            for (int c = 0; c < DW; ++c) {
                 const uint32_t dl = distance4(d[j][v][c], neg_base4);
                 d[j][v][c] = dl;
                 acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
@@ -140,7 +150,7 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
                 u32x4 o;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) o[c] = normalise4(d[j][v][c], ra);
-                if (row < Lq && vi < n16) store_stream(dst + vi * 16, o);
+                if (row < Lq && vi < nvec) store_stream(dst + vi * 16, o);
             }
         } else if constexpr (MODE == kModeClbU8) {
             const uint32_t rho = reciprocal_for_mode<MODE>(Z);
@@ -150,20 +160,17 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
                 u32x4 o;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) o[c] = normalise4_clb_u8(d[j][v][c], B, S, D, rho);
-                if (row < Lq && vi < n16) store_stream(dst + vi * 16, o);
+                if (row < Lq && vi < nvec) store_stream(dst + vi * 16, o);
             }
         } else {
             const uint32_t rho = reciprocal_for_mode<MODE>(Z);
 #pragma unroll
             for (int v = 0; v < V; ++v) {
                 const int vi = v * G + sub;
-                uint32_t w[8];
+                uint32_t w[4];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) normalise4_wide<MODE>(d[j][v][c], B, S, D, rho, w[2 * c], w[2 * c + 1]);
-                if (row < Lq && vi < n16) {
-                    store_stream(dst + vi * 32, (u32x4){w[0], w[1], w[2], w[3]});
-                    store_stream(dst + vi * 32 + 16, (u32x4){w[4], w[5], w[6], w[7]});
-                }
+                for (int c = 0; c < 2; ++c) normalise4_wide<MODE>(d[j][v][c], B, S, D, rho, w[2 * c], w[2 * c + 1]);
+                if (row < Lq && vi < nvec) store_stream(dst + vi * 16, (u32x4){w[0], w[1], w[2], w[3]});
             }
         }
     }
@@ -238,12 +245,12 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src
 // host side: choose the lane-group shape for a row length
 // ---------------------------------------------------------------------------
 template <int G, int V, int R, int WPB = 4, int MODE = kModeU8>
-static hipError_t launch_rows(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int n16,
+static hipError_t launch_rows(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int nvec,
                               const HeadTable &tab, hipStream_t st)
 {
     constexpr int kRowsPerBlock = WPB * R * (64 / G);
     dim3 grid((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt);
-    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R, WPB, MODE>), grid, dim3(64 * WPB), 0, st, x, p, Lq, n16, tab);
+    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R, WPB, MODE>), grid, dim3(64 * WPB), 0, st, x, p, Lq, nvec, tab);
     return hipGetLastError();
 }
 
@@ -253,19 +260,20 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
 {
     if (vector_ok && Lk % 16 == 0 && Lk <= 16384) {
         // Lane-group width G = the smallest power of two that covers the row with one
-        // 16-byte vector per lane, so that each load instruction reads G*16 contiguous
-        // bytes of a row; beyond 64 lanes the row takes V vectors per lane.  Few rows in
+        // vector per lane, so that each load/store instruction touches G contiguous
+        // vectors of a row; beyond 64 lanes the row takes V vectors per lane.  Few rows in
         // flight per wave (R) and many waves measured faster than the reverse.
-        const int n16 = Lk / 16;
-        if (n16 <= 4) return launch_rows<4, 1, 2, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 8) return launch_rows<8, 1, 2, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 16) return launch_rows<16, 1, 2, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 32) return launch_rows<16, 2, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 64) return launch_rows<64, 1, 2, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 128) return launch_rows<64, 2, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 256) return launch_rows<64, 4, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
-        if (n16 <= 512) return launch_rows<64, 8, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
-        return launch_rows<64, 16, 1, 4, MODE>(x, p, Bt, H, Lq, n16, tab, st);
+        const int nvec = Lk / ((MODE & 1) ? 8 : 16);
+        if (nvec <= 4) return launch_rows<4, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 8) return launch_rows<8, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 16) return launch_rows<16, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 32) return launch_rows<16, 2, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 64) return launch_rows<64, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 128) return launch_rows<64, 2, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 256) return launch_rows<64, 4, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 512) return launch_rows<64, 8, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 1024) return launch_rows<64, 16, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        return launch_rows<64, 32, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // 16-bit modes, Lk > 8192
     }
     dim3 grid(Lq, H, Bt);
     hipLaunchKernelGGL(hccs_row_bytes_kernel<MODE>, grid, dim3(256), 0, st, x, p, Lq, Lk, tab);
