@@ -20,6 +20,9 @@
 //
 // P is unsigned (0..255) but the matrix unit multiplies signed bytes: the kernel
 // feeds P - 128 (= P ^ 0x80) and starts the accumulator at 128 * sum_j V[j][d].
+//
+// Every global load of K and V is issued before the first LDS write, and the next
+// tile's Q operand is fetched while the current tile is still in its HCCS stage.
 #include "hccs_device.h"
 
 namespace hccs {
@@ -29,21 +32,37 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 // min(max(x, lo), hi); the compiler selects v_med3_i32 for it
 __device__ __forceinline__ int clamp_i32(int x, int lo, int hi) { return min(max(x, lo), hi); }
 
-// Two signed 16-bit values -> two unsigned bytes, saturated to [0,255], in the low half.
-__device__ __forceinline__ uint32_t sat_pk_u8_i16(uint32_t v)
+// D = S0.u16 * S1.u16 + S2.u32 on the low (lo) or high (hi) half of the first source.
+__device__ __forceinline__ uint32_t mad_u32_u16_lo(uint32_t a, uint32_t b, uint32_t c)
 {
     uint32_t d;
-    asm("v_sat_pk_u8_i16 %0, %1" : "=v"(d) : "v"(v));
+    asm("v_mad_u32_u16 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+__device__ __forceinline__ uint32_t mad_u32_u16_hi(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t d;
+    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(d) : "v"(a), "v"(b), "v"(c));
     return d;
 }
 
 constexpr int kKStride = 80;   // bytes per K row in LDS: 64 + 16 of padding against bank conflicts
 
-// The HCCS stage works on offset-binary bytes u = x + 128 (x the int8 logit), four per
-// register, with the same byte-parallel steps as the stand-alone kernel: the 64..128 logits
-// a lane owns shrink to 16..32 registers, which is what lets several waves share a SIMD.
-template <int NT, bool PRECLAMP>   // NT = L/16 key tiles (a multiple of 4)
-__global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__restrict__ q,
+// How the int32 accumulator becomes a 16-bit logit (before the int8 saturation):
+enum : int {
+    kRescaleHigh16 = 0,   // every head's rule was rewritten to shift 16: the logit is the high half
+    kRescaleShift = 1,    // multiply-add, arithmetic shift, saturating pack
+    kRescalePreclamp = 2  // as kRescaleShift, with the accumulator saturated first
+};
+
+// The HCCS stage runs on 16-bit pairs (two logits per register, v_pk_* instructions):
+//   x' = clamp(y, max(m - D, -128), 127), s = B - S*(m - x')             (Eq. (2), (3))
+//   Z = L*B - S*(L*m - sum x')                                           (Eq. (5))
+//   p = (s*rho) >> 15 = bits 16..23 of s*(2*rho)                         (Eq. (8))
+// so the normalise step is one 16x16->32 multiply-add per element whose byte 2 is the
+// probability; adding 0x800000 in the same instruction turns it into P - 128.
+template <int NT, int RQ, int WAVES>   // NT = L/16 key tiles (a multiple of 4), RQ = rescale kind, WAVES per block
+__global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention_kernel(const int8_t *__restrict__ q,
                                                              const int8_t *__restrict__ k,
                                                              const int8_t *__restrict__ v,
                                                              int32_t *__restrict__ o, int H, HeadTable table,
@@ -51,6 +70,9 @@ __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__res
 {
     constexpr int L = NT * 16;
     constexpr int NQ = NT / 4;     // 64-key groups = MFMAs along the key axis of P.V
+    constexpr int NTHR = 64 * WAVES;
+    constexpr int KCH = (L * 4 + NTHR - 1) / NTHR;   // 16-byte chunks of K per thread
+    constexpr int VUN = (L + NTHR - 1) / NTHR;       // V staging units per thread
     __shared__ __attribute__((aligned(16))) uint8_t lds_k[L * kKStride];
     __shared__ __attribute__((aligned(16))) uint8_t lds_v[L * 64];
     __shared__ __attribute__((aligned(16))) int32_t lds_colsum[64];
@@ -63,106 +85,145 @@ __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__res
     const size_t base = (size_t)blockIdx.x * L * 64;
 
     if (tid < 64) lds_colsum[tid] = 0;
+    __syncthreads();   // nothing is in flight yet; orders the zeroing before the atomics below
 
-    // ---- stage K row-major (padded rows) -----------------------------------
-    for (int c = tid; c < L * 4; c += 256) {
-        const u32x4 val = *(const u32x4 *)(k + base + (size_t)c * 16);
-        *(u32x4 *)(lds_k + (c >> 2) * kKStride + (c & 3) * 16) = val;
-    }
-    __syncthreads();   // colsum zeroed before the atomics below
-
-    // ---- stage V in operand order -------------------------------------------
-    // A thread takes a 4-key x 4-column block: keys kb*4 .. +3, columns 4*nn .. +3.
-    // Key 64*T + 16*tt + 4*g + r sits in byte r of dword tt of the operand of lane
-    // (g, nn) for the pair (T, dt = column % 4).
+    // ---- issue every global load of the block's K and V, then fill LDS ------------------
+    // K: row-major with padded rows.
+    // V: staging unit u = (T, g, nn) covers the 16 keys 64*T + 16*tt + 4*g + r (tt, r = 0..3) and
+    // the 4 columns 4*nn .. +3.  Each 4x4 byte block (fixed tt) is transposed with byte permutes;
+    // the four blocks of a unit then form, per column dt, exactly the 16 operand bytes of lane
+    // (g, nn) for the pair (T, dt): key 64*T + 16*tt + 4*g + r is byte r of dword tt.
     {
-        const int nn = tid & 15;
-        int cs[4] = {0, 0, 0, 0};
-        for (int kb = tid >> 4; kb < L / 4; kb += 16) {
-            const int8_t *src = v + base + (size_t)(kb * 4) * 64 + nn * 4;
-            const uint32_t r0 = *(const uint32_t *)(src), r1 = *(const uint32_t *)(src + 64),
-                           r2 = *(const uint32_t *)(src + 128), r3 = *(const uint32_t *)(src + 192);
-            const uint32_t a_lo = __builtin_amdgcn_perm(r1, r0, 0x05010400u);
-            const uint32_t a_hi = __builtin_amdgcn_perm(r1, r0, 0x07030602u);
-            const uint32_t b_lo = __builtin_amdgcn_perm(r3, r2, 0x05010400u);
-            const uint32_t b_hi = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
-            uint32_t w[4];
-            w[0] = __builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u);
-            w[1] = __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u);
-            w[2] = __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u);
-            w[3] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
-            const int T = kb >> 4, tt = (kb >> 2) & 3, g = kb & 3;
+        u32x4 kreg[KCH];
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                *(uint32_t *)(lds_v + ((((T * 4 + dt) * 4 + g) * 16 + nn) * 16) + tt * 4) = w[dt];
-                cs[dt] = __builtin_amdgcn_sdot4((int)w[dt], 0x01010101, cs[dt], false);
+        for (int i = 0; i < KCH; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < L * 4) kreg[i] = *(const u32x4 *)(k + base + (size_t)c * 16);
+        }
+        uint32_t vreg[VUN][4][4];
+#pragma unroll
+        for (int i = 0; i < VUN; ++i) {
+            const int u = tid + i * NTHR;
+            if (u < L) {
+                const int nn = u & 15, g = (u >> 4) & 3, T = u >> 6;
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    const int8_t *src = v + base + (size_t)(64 * T + 16 * tt + 4 * g) * 64 + nn * 4;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) vreg[i][tt][r] = *(const uint32_t *)(src + 64 * r);
+                }
             }
         }
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) atomicAdd(&lds_colsum[nn * 4 + dt], cs[dt]);
+        for (int i = 0; i < KCH; ++i) {
+            const int c = tid + i * NTHR;
+            if (c < L * 4) *(u32x4 *)(lds_k + (c >> 2) * kKStride + (c & 3) * 16) = kreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < VUN; ++i) {
+            const int u = tid + i * NTHR;
+            if (u < L) {
+                const int nn = u & 15, g = (u >> 4) & 3, T = u >> 6;
+                u32x4 w[4];   // w[dt][tt]
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    const uint32_t a_lo = __builtin_amdgcn_perm(vreg[i][tt][1], vreg[i][tt][0], 0x05010400u);
+                    const uint32_t a_hi = __builtin_amdgcn_perm(vreg[i][tt][1], vreg[i][tt][0], 0x07030602u);
+                    const uint32_t b_lo = __builtin_amdgcn_perm(vreg[i][tt][3], vreg[i][tt][2], 0x05010400u);
+                    const uint32_t b_hi = __builtin_amdgcn_perm(vreg[i][tt][3], vreg[i][tt][2], 0x07030602u);
+                    w[0][tt] = __builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u);
+                    w[1][tt] = __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u);
+                    w[2][tt] = __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u);
+                    w[3][tt] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
+                }
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    *(u32x4 *)(lds_v + (((T * 4 + dt) * 4 + g) * 16 + nn) * 16) = w[dt];
+                    int cs = 0;
+#pragma unroll
+                    for (int tt = 0; tt < 4; ++tt) cs = __builtin_amdgcn_sdot4((int)w[dt][tt], 0x01010101, cs, false);
+                    atomicAdd(&lds_colsum[nn * 4 + dt], cs);
+                }
+            }
+        }
     }
     __syncthreads();
 
     const int qi = lane & 15;      // query inside the 16-row tile / output column group
     const int g = lane >> 4;       // which quarter of the contraction slots this lane feeds
-    // Rescale constant.  Without PRECLAMP the +128 of the offset-binary form rides in it;
-    // with PRECLAMP (acc*mult could leave 32 bits) the accumulator is saturated first --
-    // any |acc| >= lim lands beyond the int8 range anyway -- and the 128 is added in 16 bits.
-    const int round_c = (1 << (shift - 1)) + (PRECLAMP ? 0 : (128 << shift));
+    const int round_c = 1 << (shift - 1);
+    // Saturation bound for the accumulator when acc*mult could leave 32 bits: any
+    // |acc| >= lim rescales to a value beyond the int8 range already.
     const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 20);
-    const uint32_t D4 = (uint32_t)D * 0x01010101u;
 
-    for (int rt = wave; rt < NT; rt += 4) {
-        // ---- A^T tiles = K_tile . Q^T, rescaled and packed tile by tile ----------------
-        const v4i qop = *(const v4i *)(q + base + (size_t)(rt * 16 + qi) * 64 + g * 16);
-        uint32_t xb[NT];           // offset-binary logits of keys 16t + 4g + {0..3}, then their distances
-        int mx = -(1 << 30);       // running maximum of y + 128 before saturation
+    v4i qop = {0, 0, 0, 0};
+    if (wave < NT) qop = *(const v4i *)(q + base + (size_t)(wave * 16 + qi) * 64 + g * 16);
+    for (int rt = wave; rt < NT; rt += WAVES) {
+        // ---- A^T tiles = K_tile . Q^T, rescaled to 16-bit pairs tile by tile ----------------
+        short2_t xp[NT][2];        // logits of keys 16t + 4g + {0,1} and {2,3}; later their scores
+        short2_t mx2 = {-32768, -32768};
+        // one tile ahead: the matrix unit works on tile t+1 while the vector unit rescales tile t;
+        // the scheduling barrier keeps the compiler from hoisting every operand read to the top
+        v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(*(const v4i *)(lds_k + qi * kKStride + g * 16), qop,
+                                                        (v4i){0, 0, 0, 0}, 0, 0, 0);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const v4i kop = *(const v4i *)(lds_k + (t * 16 + qi) * kKStride + g * 16);
-            const v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
+            v4i acc_next = acc;
+            if (t + 1 < NT) {
+                const v4i kop = *(const v4i *)(lds_k + ((t + 1) * 16 + qi) * kKStride + g * 16);
+                acc_next = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
+            }
             int y[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 int a = acc[r];
-                if constexpr (PRECLAMP) a = clamp_i32(a, -lim, lim);
-                y[r] = (__mul24(a, mult) + round_c) >> shift;
+                if constexpr (RQ == kRescalePreclamp) a = clamp_i32(a, -lim, lim);
+                y[r] = __mul24(a, mult) + round_c;
             }
-            typedef short short2v __attribute__((ext_vector_type(2)));
-            short2v lo16 = __builtin_amdgcn_cvt_pk_i16(y[0], y[1]);   // saturating 32 -> 16
-            short2v hi16 = __builtin_amdgcn_cvt_pk_i16(y[2], y[3]);
-            if constexpr (PRECLAMP) {
-                const short2v c128 = {128, 128};
-                lo16 = __builtin_elementwise_add_sat(lo16, c128);
-                hi16 = __builtin_elementwise_add_sat(hi16, c128);
-                mx = max(mx, max(max(y[0], y[1]), max(y[2], y[3])) + 128);
+            if constexpr (RQ == kRescaleHigh16) {
+                // shift is 16 and |acc*mult + 2^15| < 2^31: the logit is the signed high half
+                xp[t][0] = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x07060302u));
+                xp[t][1] = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x07060302u));
             } else {
-                mx = max(mx, max(max(y[0], y[1]), max(y[2], y[3])));
+                xp[t][0] = __builtin_amdgcn_cvt_pk_i16(y[0] >> shift, y[1] >> shift);   // saturating 32 -> 16
+                xp[t][1] = __builtin_amdgcn_cvt_pk_i16(y[2] >> shift, y[3] >> shift);
             }
-            const uint32_t lo8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, lo16));
-            const uint32_t hi8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, hi16));
-            xb[t] = __builtin_amdgcn_perm(hi8, lo8, 0x05040100u);
+            mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(xp[t][0], xp[t][1]));
+            acc = acc_next;
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // next tile's Q operand: in flight during the HCCS stage and the second contraction
+        if (rt + WAVES < NT) qop = *(const v4i *)(q + base + (size_t)((rt + WAVES) * 16 + qi) * 64 + g * 16);
+
+        int mx = max((int)mx2.x, (int)mx2.y);
         mx = max(mx, xor16(mx));
         mx = max(mx, xor32(mx));
-        const uint32_t mu = (uint32_t)min(max(mx, 0), 255);   // saturation is monotone: max of clamped = clamp of max
+        const int m = clamp_i32(mx, -128, 127);   // saturation is monotone: max of clamped = clamp of max
+        const bool any_above = __builtin_amdgcn_ballot_w64(mx > 127) != 0;   // wave-uniform
 
-        // ---- distances, sum of the clamped ones (same identity as the stand-alone kernel) ----
-        const uint32_t mu4 = mu * 0x01010101u;
-        uint32_t acc_d = 0, acc_abs = 0;
+        // ---- window clamp, sum, scores ---------------------------------------------------
+        const short lo = (short)max(m - D, -128);
+        const short2_t lo2 = {lo, lo}, hi2 = {127, 127};
+        const ushort2_t s2 = {(unsigned short)S, (unsigned short)S};
+        const unsigned short cc = (unsigned short)(B - S * m);
+        const ushort2_t c2 = {cc, cc};
+        short2_t sum2 = {0, 0};
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const uint32_t dl = mu4 - xb[t];   // every byte of xb is <= mu: no borrow
-            xb[t] = dl;
-            acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
-            acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                short2_t xc = __builtin_elementwise_max(xp[t][h], lo2);
+                if (any_above) xc = __builtin_elementwise_min(xc, hi2);
+                sum2 += xc;                            // at most 64 values of magnitude <= 128 per half
+                // s = B - S*(m - x'), computed modulo 2^16 (the result is in [0, 32767])
+                xp[t][h] = __builtin_bit_cast(short2_t, __builtin_bit_cast(ushort2_t, xc) * s2 + c2);
+            }
         }
-        int tsum = (int)acc_d - (int)acc_abs;
-        tsum += xor16(tsum);
-        tsum += xor32(tsum);
-        const int sum_clamped = (tsum + L * D) / 2;
-        const uint32_t Z = (uint32_t)(L * B - S * sum_clamped);     // Eq. (3), (5)
-        const RowAffine ra = row_affine(Z, B, S, D);
+        int sx = (int)sum2.x + (int)sum2.y;
+        sx += xor16(sx);
+        sx += xor32(sx);
+        const uint32_t Z = (uint32_t)(L * B - S * (L * m - sx));     // Eq. (3), (5)
+        const uint32_t rho2 = reciprocal_u8(Z) * 2u;                 // <= 65280: fits 16 bits
 
         // ---- P - 128 as the A operand, O = P.V ------------------------------------
         v4i oacc[4];
@@ -174,16 +235,26 @@ __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__res
                 oacc[dt] = (v4i){init, init, init, init};
             }
         }
+        const uint32_t bias = 0x800000u;               // +128 in byte 2: p ^ 0x80 for p <= 255
 #pragma unroll
         for (int T = 0; T < NQ; ++T) {
             v4i pop;
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(xb[T * 4 + tt], ra) ^ 0x80808080u);
+            for (int tt = 0; tt < 4; ++tt) {
+                const uint32_t s01 = __builtin_bit_cast(uint32_t, xp[T * 4 + tt][0]);
+                const uint32_t s23 = __builtin_bit_cast(uint32_t, xp[T * 4 + tt][1]);
+                const uint32_t e0 = mad_u32_u16_lo(s01, rho2, bias), e1 = mad_u32_u16_hi(s01, rho2, bias);
+                const uint32_t e2 = mad_u32_u16_lo(s23, rho2, bias), e3 = mad_u32_u16_hi(s23, rho2, bias);
+                const uint32_t h01 = __builtin_amdgcn_perm(e1, e0, 0x00000602u);
+                const uint32_t h23 = __builtin_amdgcn_perm(e3, e2, 0x00000602u);
+                pop[tt] = (int)__builtin_amdgcn_perm(h23, h01, 0x05040100u);
+            }
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
                 const v4i vop = *(const v4i *)(lds_v + (((T * 4 + dt) * 4 + g) * 16 + qi) * 16);
                 oacc[dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[dt], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
 
         // ---- store: lane (g, qi) holds rows 4g..4g+3 of the tile, columns 4*qi .. 4*qi+3 ----
@@ -197,39 +268,51 @@ __global__ __launch_bounds__(256) void hccs_attention_kernel(const int8_t *__res
 
 template <int NT>
 static hipError_t launch_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int blocks, int H,
-                            const HeadTable &tab, const RequantTable &rq, bool preclamp, hipStream_t st)
+                            const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
 {
-    if (preclamp)
-        hipLaunchKernelGGL((hccs_attention_kernel<NT, true>), dim3(blocks), dim3(256), 0, st, q, k, v, o, H, tab,
-                           rq);
+    // eight waves per block (two per SIMD) when there are at least eight query tiles
+    constexpr int WAVES = NT >= 8 ? 8 : 4;
+    if (kind == kRescaleHigh16)
+        hipLaunchKernelGGL((hccs_attention_kernel<NT, kRescaleHigh16, WAVES>), dim3(blocks), dim3(64 * WAVES), 0, st,
+                           q, k, v, o, H, tab, rq);
+    else if (kind == kRescaleShift)
+        hipLaunchKernelGGL((hccs_attention_kernel<NT, kRescaleShift, WAVES>), dim3(blocks), dim3(64 * WAVES), 0, st,
+                           q, k, v, o, H, tab, rq);
     else
-        hipLaunchKernelGGL((hccs_attention_kernel<NT, false>), dim3(blocks), dim3(256), 0, st, q, k, v, o, H, tab,
-                           rq);
+        hipLaunchKernelGGL((hccs_attention_kernel<NT, kRescalePreclamp, WAVES>), dim3(blocks), dim3(64 * WAVES), 0,
+                           st, q, k, v, o, H, tab, rq);
     return hipGetLastError();
 }
 
 hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
-                            int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st)
+                            int d, const HeadTable &tab, const RequantTable &rq_in, hipStream_t st)
 {
     (void)d;   // 64, checked by the caller
-    // |acc| <= 64*128*128 = 2^20.  If acc*mult + 2^(shift-1) + 128*2^shift can pass 2^31 for
-    // some head, the accumulator is saturated first (same result, a few more instructions).
-    bool preclamp = false;
+    // |acc| <= 64*128*128 = 2^20.  Pick the cheapest rescale form that is exact for every head:
+    //  - if each rule (mult, shift <= 16) can be rewritten as (mult << (16-shift), 16) without
+    //    acc*mult + 2^15 leaving 32 bits, the logit is simply the high half of that word;
+    //  - else multiply-add and shift; if acc*mult + 2^(shift-1) could leave 32 bits for some
+    //    head, the accumulator is saturated first (same result, one more instruction).
+    RequantTable rq = rq_in;
+    bool high16 = true, preclamp = false;
     for (int h = 0; h < H; ++h) {
-        const int64_t worst = ((int64_t)1 << 20) * rq.e[h].x + ((int64_t)1 << (rq.e[h].y - 1)) +
-                              ((int64_t)128 << rq.e[h].y);
-        if (worst > 0x7fffffffll) preclamp = true;
+        const int64_t mult = rq_in.e[h].x, shift = rq_in.e[h].y;
+        if (shift > 16 || (((int64_t)1 << 20) * (mult << (16 - shift)) + (1 << 15)) > 0x7fffffffll) high16 = false;
+        if (((int64_t)1 << 20) * mult + ((int64_t)1 << (shift - 1)) > 0x7fffffffll) preclamp = true;
     }
+    if (high16)
+        for (int h = 0; h < H; ++h) rq.e[h] = make_int2(rq_in.e[h].x << (16 - rq_in.e[h].y), 16);
+    const int kind = high16 ? kRescaleHigh16 : (preclamp ? kRescalePreclamp : kRescaleShift);
     const int blocks = Bt * H;
     switch (L / 16) {
-        case 4: return launch_nt<4>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
-        case 8: return launch_nt<8>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
-        case 12: return launch_nt<12>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
-        case 16: return launch_nt<16>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
-        case 20: return launch_nt<20>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
-        case 24: return launch_nt<24>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
-        case 28: return launch_nt<28>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
-        case 32: return launch_nt<32>(q, k, v, o, blocks, H, tab, rq, preclamp, st);
+        case 4: return launch_nt<4>(q, k, v, o, blocks, H, tab, rq, kind, st);
+        case 8: return launch_nt<8>(q, k, v, o, blocks, H, tab, rq, kind, st);
+        case 12: return launch_nt<12>(q, k, v, o, blocks, H, tab, rq, kind, st);
+        case 16: return launch_nt<16>(q, k, v, o, blocks, H, tab, rq, kind, st);
+        case 20: return launch_nt<20>(q, k, v, o, blocks, H, tab, rq, kind, st);
+        case 24: return launch_nt<24>(q, k, v, o, blocks, H, tab, rq, kind, st);
+        case 28: return launch_nt<28>(q, k, v, o, blocks, H, tab, rq, kind, st);
+        case 32: return launch_nt<32>(q, k, v, o, blocks, H, tab, rq, kind, st);
         default: return hipErrorInvalidValue;
     }
 }
