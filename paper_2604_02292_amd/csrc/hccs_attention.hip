@@ -199,7 +199,6 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
         mx = max(mx, xor16(mx));
         mx = max(mx, xor32(mx));
         const int m = clamp_i32(mx, -128, 127);   // saturation is monotone: max of clamped = clamp of max
-        const bool any_above = __builtin_amdgcn_ballot_w64(mx > 127) != 0;   // wave-uniform
 
         // ---- window clamp, sum, scores ---------------------------------------------------
         const short lo = (short)max(m - D, -128);
@@ -212,8 +211,7 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
         for (int t = 0; t < NT; ++t) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                short2_t xc = __builtin_elementwise_max(xp[t][h], lo2);
-                if (any_above) xc = __builtin_elementwise_min(xc, hi2);
+                const short2_t xc = __builtin_elementwise_min(__builtin_elementwise_max(xp[t][h], lo2), hi2);
                 sum2 += xc;                            // at most 64 values of magnitude <= 128 per half
                 // s = B - S*(m - x'), computed modulo 2^16 (the result is in [0, 32767])
                 xp[t][h] = __builtin_bit_cast(short2_t, __builtin_bit_cast(ushort2_t, xc) * s2 + c2);
