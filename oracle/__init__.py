@@ -23,7 +23,7 @@ MODE_U8, MODE_I16, MODE_CLB_U8, MODE_CLB_I16 = 0, 1, 2, 3
 def build(force=False):
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared",
-                               "-Wall", "-Wextra", "-o", _LIB, _SRC])
+                               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"])
     return _LIB
 
 
@@ -40,6 +40,7 @@ def load():
         lib.hccs_oracle_attention_i8.argtypes = [p, p, p, p, i64, i64, i64, i64, p, p, i32, i32]
         lib.hccs_oracle_requant_logits.argtypes = [p, p, p, i64, i64, i64, i64, p]
         lib.hccs_oracle_reciprocal_u8.argtypes = [p, p, i64]
+        lib.hccs_oracle_calibrate.argtypes = [p, i64, i64, i64, i64, p, p, i64, p, p, i32]
         _lib = lib
     return _lib
 
@@ -106,3 +107,19 @@ def reciprocal_u8(Z):
     rho = np.zeros_like(Z)
     rc = load().hccs_oracle_reciprocal_u8(_ptr(Z), _ptr(rho), Z.shape[0])
     return rho, rc
+
+
+def calibrate(logits, alpha, candidates, threads=1):
+    """Brute-force calibration objective.  logits int8 [B,H,Lq,Lk], alpha float64 [H],
+    candidates int32 [nc,3].  Returns (objective float64 [H,nc], best int32 [H], status)."""
+    logits = np.ascontiguousarray(logits, dtype=np.int8)
+    alpha = np.ascontiguousarray(alpha, dtype=np.float64)
+    candidates = np.ascontiguousarray(candidates, dtype=np.int32)
+    Bt, H, Lq, Lk = logits.shape
+    nc = candidates.shape[0]
+    assert alpha.shape == (H,) and candidates.shape == (nc, 3)
+    obj = np.zeros((H, nc), dtype=np.float64)
+    best = np.zeros(H, dtype=np.int32)
+    rc = load().hccs_oracle_calibrate(_ptr(logits), Bt, H, Lq, Lk, _ptr(alpha), _ptr(candidates), nc,
+                                      _ptr(obj), _ptr(best), int(threads))
+    return obj, best, rc

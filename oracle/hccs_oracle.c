@@ -18,6 +18,8 @@
  *   hccs_oracle_row_clb_*      Sec. III-B "leading-bit detection", Eq. (9)
  *   hccs_oracle_softmax_*      Sec. IV-D: rows are independent, the head of a
  *                              row selects its parameters
+ *   hccs_oracle_calibrate      Sec. III-C, Eq. (10): mean KL(softmax || HCCS) per head and
+ *                              candidate, in the 16-bit output space; arg-min per head
  *   hccs_oracle_attention_i8   int8 Q.K^T -> per-head requantisation -> HCCS
  *                              -> P.V ; the paper only motivates this block
  *                              (Sec. I, Sec. II), the requantisation rule is
@@ -33,6 +35,7 @@
  * exact rational rounding.  Parity for the fused block is therefore pinned to
  * this repository's reading only.
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -350,4 +353,73 @@ int hccs_oracle_reciprocal_u8(const int64_t *Z, int64_t *rho, int64_t count)
         rho[i] = (((int64_t)255) << INV_SHIFT) / Z[i];
     }
     return ORACLE_OK;
+}
+
+/* Offline calibration objective, Sec. III-C Eq. (10), evaluated by brute force.
+ * For head h and candidate c = (B, S, Dmax):
+ *   J[h][c] = mean over the rows r of head h of  KL( softmax(alpha_h * x_r) || q_r ),
+ *   q_r[i]  = phat_r[i] / sum_j phat_r[j],  phat_r the 16-bit HCCS output of row r
+ *             (Alg. 1 as printed: the paper asks for the divergence "in the int16 space").
+ * alpha_h turns an int8 logit into a real one (the paper does not name the dequantisation
+ * scale; it is an input here).  The softmax and the divergence are in double precision,
+ * KL = sum_i P_i (log P_i - log q_i), terms with P_i = 0 contribute nothing.
+ * Candidates that are not admissible under the strict band (Sec. IV-C) get +infinity.
+ * objective: H*nc doubles; best[h] = the first index attaining the minimum, or -1 if no
+ * candidate is admissible. */
+int hccs_oracle_calibrate(const int8_t *logits, int64_t Bt, int64_t H, int64_t Lq, int64_t Lk,
+                          const double *alpha, const int32_t *cand, int64_t nc, double *objective,
+                          int32_t *best, int threads)
+{
+    if (!logits || !alpha || !cand || !objective || !best) return ORACLE_E_ARG;
+    if (Bt < 1 || H < 1 || Lq < 1 || Lk < 1 || nc < 1) return ORACLE_E_ARG;
+    int status = ORACLE_OK;
+    if (threads < 1) threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(dynamic, 1)
+    for (int64_t hc = 0; hc < H * nc; ++hc) {
+        const int64_t h = hc / nc, c = hc % nc;
+        const int64_t B = cand[3 * c], S = cand[3 * c + 1], D = cand[3 * c + 2];
+        if (hccs_oracle_check_params(B, S, D, Lk, 1) != ORACLE_OK) {
+            objective[hc] = INFINITY;
+            continue;
+        }
+        double *P = (double *)malloc((size_t)Lk * sizeof(double));
+        uint16_t *ph = (uint16_t *)malloc((size_t)Lk * sizeof(uint16_t));
+        double total = 0.0;
+        for (int64_t b = 0; b < Bt; ++b)
+            for (int64_t qi = 0; qi < Lq; ++qi) {
+                const int8_t *x = logits + (((b * H + h) * Lq) + qi) * Lk;
+                int64_t m = x[0];
+                for (int64_t i = 1; i < Lk; ++i)
+                    if (x[i] > m) m = x[i];
+                double den = 0.0;
+                for (int64_t i = 0; i < Lk; ++i) {
+                    P[i] = exp(alpha[h] * (double)((int64_t)x[i] - m));
+                    den += P[i];
+                }
+                int rc = hccs_oracle_row_i16(x, Lk, B, S, D, ph, 0, 0);
+                if (rc != ORACLE_OK) {
+#pragma omp critical
+                    status = rc;
+                    continue;
+                }
+                int64_t sum = 0;
+                for (int64_t i = 0; i < Lk; ++i) sum += ph[i];
+                double kl = 0.0;
+                for (int64_t i = 0; i < Lk; ++i) {
+                    const double p = P[i] / den;
+                    if (p > 0.0) kl += p * (log(p) - log((double)ph[i] / (double)sum));
+                }
+                total += kl;
+            }
+        objective[hc] = total / (double)(Bt * Lq);
+        free(P);
+        free(ph);
+    }
+    for (int64_t h = 0; h < H; ++h) {
+        best[h] = -1;
+        for (int64_t c = 0; c < nc; ++c)
+            if (isfinite(objective[h * nc + c]) && (best[h] < 0 || objective[h * nc + c] < objective[h * nc + best[h]]))
+                best[h] = (int32_t)c;
+    }
+    return status;
 }
