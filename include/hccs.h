@@ -130,6 +130,24 @@ HCCS_API int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const i
                       const hccs_head_params *table_host, const hccs_requant *requant_host,
                       int32_t out_scale_T, int32_t band, void *hip_stream);
 
+/* Offline calibration by grid search (Sec. III-C, Eq. (10)).  For every head h and candidate c,
+ *   objective[h*n_candidates + c] = mean over the rows of head h of
+ *       KL( softmax(alpha_h * x) || phat / sum(phat) ),  phat the 16-bit HCCS output of the row
+ *   (the paper minimises the divergence "in the int16 space"), in double precision;
+ *   +infinity for candidates outside HCCS_BAND_STRICT for n = Lk.
+ *   best[h] = first index of the minimum, -1 if no candidate is admissible.
+ * alpha_host: H positive dequantisation scales (real logit = alpha_h * int8 logit; the paper does
+ * not name this scale, it is an input).  candidates_dev: n_candidates (1..65535) entries ON THE
+ * DEVICE.  objective_dev: H*n_candidates doubles, best_dev: H int32, both on the device.
+ * workspace_dev: at least hccs_calibrate_workspace_bytes(...) bytes of device memory, 8-byte
+ * aligned, contents undefined on entry and exit.  B >= 1, Lq >= 1, any Lk.
+ * Sums are taken in a fixed order: two calls with equal inputs give equal bits. */
+HCCS_API int64_t hccs_calibrate_workspace_bytes(int32_t B, int32_t H, int32_t Lq, int32_t Lk);
+HCCS_API int hccs_calibrate_grid(const int8_t *logits_dev, int32_t B, int32_t H, int32_t Lq, int32_t Lk,
+                                 const double *alpha_host, const hccs_head_params *candidates_dev,
+                                 int32_t n_candidates, double *objective_dev, int32_t *best_dev,
+                                 void *workspace_dev, int64_t workspace_bytes, void *hip_stream);
+
 /* Comparison kernel for benchmarks only (never parity-checked): exact-exponential
  * float32 softmax of the same int8 logits, out = rint(255 * softmax(scale_h * x)),
  * same traffic (1 byte in, 1 byte out per element).  scale_host: H floats.

@@ -16,6 +16,7 @@ BAND_U8, BAND_STRICT = 0, 1
 RECIP_EXACT, RECIP_CLB = 0, 1
 
 EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_calibrated_softmax_i8_ex", "hccs_attention_i8",
+           "hccs_calibrate_workspace_bytes", "hccs_calibrate_grid",
            "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_copy_bytes", "hccs_status_string"]
 
 
@@ -51,13 +52,18 @@ def lib():
                                                     i32, vp]
         L.hccs_attention_i8.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, ctypes.POINTER(HeadParams),
                                         ctypes.POINTER(Requant), i32, i32, vp]
+        L.hccs_calibrate_workspace_bytes.argtypes = [i32, i32, i32, i32]
+        L.hccs_calibrate_workspace_bytes.restype = i64
+        L.hccs_calibrate_grid.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_double), vp, i32, vp, vp, vp,
+                                          i64, vp]
         L.hccs_exp_softmax_i8_f32.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_float), vp]
         L.hccs_reciprocal_u8.argtypes = [vp, vp, i64, vp]
         L.hccs_copy_bytes.argtypes = [vp, vp, i64, vp]
         L.hccs_status_string.argtypes = [i32]
         L.hccs_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
-            getattr(L, name).restype = i32
+            if name != "hccs_calibrate_workspace_bytes":
+                getattr(L, name).restype = i32
         _lib = L
     return _lib
 
@@ -199,6 +205,30 @@ def attention_i8(q, k, v, table, requant, band, out=None, out_scale_T=255, strea
                                    ctypes.c_void_p(v.data_ptr()), ctypes.c_void_p(out.data_ptr()),
                                    B, H, L, d, arr, rq, int(out_scale_T), int(band), _stream_handle(stream)))
     return out
+
+
+def calibrate_grid(logits, alpha, candidates, stream=None):
+    """Grid-search calibration.  logits int8 CUDA [B,H,Lq,Lk]; alpha: H floats; candidates: [nc,3] integers
+    (B, S, Dmax).  Returns (objective float64 CUDA [H,nc], best int32 CUDA [H])."""
+    import torch
+    assert logits.is_cuda and logits.dtype == torch.int8 and logits.is_contiguous() and logits.dim() == 4
+    B, H, Lq, Lk = logits.shape
+    cand = np.zeros((len(candidates), 4), dtype=np.int32)
+    cand[:, :3] = np.asarray(candidates, dtype=np.int64).reshape(-1, 3).clip(-2**31, 2**31 - 1)
+    cand_dev = torch.from_numpy(cand).to(logits.device)
+    nc = cand.shape[0]
+    need = lib().hccs_calibrate_workspace_bytes(B, H, Lq, Lk)
+    if need < 0:
+        _check(int(need))
+    work = torch.empty(need // 8 + 1, dtype=torch.float64, device=logits.device)
+    obj = torch.empty((H, nc), dtype=torch.float64, device=logits.device)
+    best = torch.empty(H, dtype=torch.int32, device=logits.device)
+    al = (ctypes.c_double * H)(*[float(a) for a in alpha])
+    _check(lib().hccs_calibrate_grid(ctypes.c_void_p(logits.data_ptr()), B, H, Lq, Lk, al,
+                                     ctypes.c_void_p(cand_dev.data_ptr()), nc, ctypes.c_void_p(obj.data_ptr()),
+                                     ctypes.c_void_p(best.data_ptr()), ctypes.c_void_p(work.data_ptr()),
+                                     work.numel() * 8, _stream_handle(stream)))
+    return obj, best
 
 
 def exp_softmax_i8_f32(logits, scale, out=None, stream=None):

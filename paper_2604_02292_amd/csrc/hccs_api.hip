@@ -11,6 +11,10 @@ hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hi
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
 hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
                             int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st);
+int64_t calibrate_workspace_bytes(int64_t Bt, int64_t H, int64_t Lq);
+hipError_t launch_calibrate(const int8_t *logits, int Bt, int H, int Lq, int Lk, const double *alpha,
+                            const hccs_head_params *cand, int nc, double *objective, int32_t *best, void *workspace,
+                            hipStream_t st);
 hipError_t launch_exp_softmax(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const float *scale,
                               hipStream_t st);
 }  // namespace hccs
@@ -124,6 +128,34 @@ int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_
         rq.e[h] = h < H ? make_int2(requant_host[h].mult, requant_host[h].shift) : make_int2(1, 1);
     const hipError_t e =
         hccs::launch_attention(q_dev, k_dev, v_dev, o_dev, B, H, L, d, tab, rq, (hipStream_t)hip_stream);
+    return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+int64_t hccs_calibrate_workspace_bytes(int32_t B, int32_t H, int32_t Lq, int32_t Lk)
+{
+    if (B < 1 || B > 65535 || H < 1 || H > HCCS_MAX_HEADS || Lq < 1 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH)
+        return HCCS_E_SHAPE;
+    return hccs::calibrate_workspace_bytes(B, H, Lq);
+}
+
+int hccs_calibrate_grid(const int8_t *logits_dev, int32_t B, int32_t H, int32_t Lq, int32_t Lk,
+                        const double *alpha_host, const hccs_head_params *candidates_dev, int32_t n_candidates,
+                        double *objective_dev, int32_t *best_dev, void *workspace_dev, int64_t workspace_bytes,
+                        void *hip_stream)
+{
+    if (!alpha_host) return HCCS_E_NULL;
+    const int64_t need = hccs_calibrate_workspace_bytes(B, H, Lq, Lk);
+    if (need < 0) return HCCS_E_SHAPE;
+    if (n_candidates < 1 || n_candidates > 65535) return HCCS_E_SHAPE;
+    for (int h = 0; h < H; ++h)
+        if (!(alpha_host[h] > 0.0) || !(alpha_host[h] < 1e6)) return HCCS_E_SCALE;
+    if (!logits_dev || !candidates_dev || !objective_dev || !best_dev || !workspace_dev) return HCCS_E_NULL;
+    if (workspace_bytes < need) return HCCS_E_SHAPE;
+    if (((uintptr_t)workspace_dev & 7u) || ((uintptr_t)objective_dev & 7u) || ((uintptr_t)best_dev & 3u) ||
+        ((uintptr_t)candidates_dev & 3u))
+        return HCCS_E_ALIGN;
+    const hipError_t e = hccs::launch_calibrate(logits_dev, B, H, Lq, Lk, alpha_host, candidates_dev, n_candidates,
+                                                objective_dev, best_dev, workspace_dev, (hipStream_t)hip_stream);
     return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
 }
 

@@ -224,6 +224,61 @@ def test_edge_encoder_full_size_i16(oracle):
     assert np.array_equal(got.cpu().numpy().view(np.uint16), want)
 
 
+# ---------------------------------------------------------------- grid-search calibration
+def candidate_grid(n, count, seed):
+    """Mostly admissible triples for row length n, plus a few that are not."""
+    g = np.random.default_rng(seed)
+    bmax = 32767 // n
+    f = -(-256 // n)
+    out = []
+    while len(out) < count:
+        D = int(g.integers(0, 128))
+        B = int(g.integers(f, bmax + 1))
+        S = int(g.integers(0, min(127, (B - f) // max(D, 1)) + 1))
+        out.append((B, S, D))
+    out[3] = (bmax + 1, 0, 1)          # ceiling violated
+    out[7] = (f, 1, 127)               # negative floor
+    out[11] = (bmax, 0, 128)           # Dmax out of range
+    return np.array(out, np.int32)
+
+
+@pytest.mark.parametrize("shape", [(6, 4, 24, 128), (3, 2, 5, 100), (2, 3, 9, 64), (1, 2, 7, 4096), (2, 1, 33, 16)])
+def test_calibration_grid_search(oracle, shape):
+    """Objective in double precision on both sides; sums are ordered differently, so values are
+    compared to 1e-9 relative, and the arg-min is checked for validity against the oracle's table."""
+    H, n = shape[1], shape[3]
+    x = synth.make_workload("edge_encoder", shape=shape)["logits"] if n != 4096 else mixed_logits(shape, 4)
+    alpha = np.linspace(0.04, 0.2, H)
+    cand = candidate_grid(n, 150, seed=n)
+    print(f"calibration case shape={shape}", flush=True)
+    want, want_best, rc = oracle.calibrate(x, alpha, cand, threads=THREADS)
+    assert rc == 0
+    obj, best = binding.calibrate_grid(torch.from_numpy(x).cuda(), alpha, cand)
+    torch.cuda.synchronize()
+    obj, best = obj.cpu().numpy(), best.cpu().numpy()
+    assert np.array_equal(np.isinf(obj), np.isinf(want))
+    fin = np.isfinite(want)
+    assert fin.any()
+    assert np.allclose(obj[fin], want[fin], rtol=1e-9, atol=1e-12)
+    for h in range(H):
+        assert 0 <= best[h] < len(cand) and np.isfinite(want[h, best[h]])
+        assert want[h, best[h]] <= want[h][fin[h]].min() * (1 + 1e-9) + 1e-12
+    # reproducible to the bit
+    obj2, best2 = binding.calibrate_grid(torch.from_numpy(x).cuda(), alpha, cand)
+    torch.cuda.synchronize()
+    assert np.array_equal(obj2.cpu().numpy(), obj) and np.array_equal(best2.cpu().numpy(), best)
+
+
+def test_calibration_finds_the_exact_reproduction():
+    import math
+    x = np.tile(np.array([0, -1, 0, -1], np.int8), (2, 1, 3, 1))
+    cand = [[200, 10, 12], [254, 100, 1], [254, 127, 1], [8192, 0, 0]]
+    obj, best = binding.calibrate_grid(torch.from_numpy(x).cuda(), [math.log(2.0)], cand)
+    torch.cuda.synchronize()
+    assert best.cpu().tolist() == [2]
+    assert abs(float(obj[0, 2])) < 1e-14 and float(obj[0, 0]) > 1e-4 and math.isinf(float(obj[0, 3]))
+
+
 # ---------------------------------------------------------------- the named workloads
 @pytest.mark.parametrize("name,shape", [
     ("pr1_ref", None), ("edge_encoder", (4, 8, 128, 128)), ("stress_rows", (2, 12, 512, 512)),

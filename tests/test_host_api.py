@@ -143,6 +143,24 @@ def test_attention_rejections_launch_nothing(lib):
     assert call(B=0, q=0, k=0, v=0, o=0) == 0
 
 
+def test_calibration_entry_point_rejections(lib):
+    vp = ctypes.c_void_p
+    assert lib.hccs_calibrate_workspace_bytes(2, 3, 4, 64) == 2 * 3 * 4 * (128 * 4 + 8) + 2 * 3 * 2048 + 3 * 2056
+    assert lib.hccs_calibrate_workspace_bytes(0, 3, 4, 64) == -2
+    assert lib.hccs_calibrate_workspace_bytes(2, 65, 4, 64) == -2
+    al = (ctypes.c_double * 2)(0.1, 0.2)
+
+    def call(x=4096, B=1, H=2, Lq=4, Lk=64, alpha=al, cand=8192, nc=5, obj=16384, best=32768, ws=65536, wsb=1 << 20):
+        return lib.hccs_calibrate_grid(vp(x), B, H, Lq, Lk, alpha, vp(cand), nc, vp(obj), vp(best), vp(ws), wsb, None)
+
+    assert call(x=0) == -1 and call(cand=0) == -1 and call(ws=0) == -1
+    assert call(nc=0) == -2 and call(nc=70000) == -2 and call(B=0) == -2
+    assert call(wsb=100) == -2                      # workspace too small
+    assert call(ws=65540) == -3 and call(obj=16388) == -3
+    assert call(alpha=(ctypes.c_double * 2)(0.1, 0.0)) == -4
+    assert call(alpha=(ctypes.c_double * 2)(0.1, float("nan"))) == -4
+
+
 def test_other_entry_points_reject_bad_arguments(lib):
     vp = ctypes.c_void_p
     assert lib.hccs_reciprocal_u8(vp(0), vp(0), 5, None) == -1
