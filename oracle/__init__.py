@@ -37,8 +37,8 @@ def load():
         for name in ("row_u8", "row_i16", "row_clb_u8", "row_clb_i16"):
             getattr(lib, "hccs_oracle_" + name).argtypes = [p, i64, i64, i64, i64, p, p, p]
         lib.hccs_oracle_softmax.argtypes = [p, p, i64, i64, i64, i64, p, i32, i32, i32]
-        lib.hccs_oracle_attention_i8.argtypes = [p, p, p, p, i64, i64, i64, i64, p, p, i32, i32]
-        lib.hccs_oracle_requant_logits.argtypes = [p, p, p, i64, i64, i64, i64, p]
+        lib.hccs_oracle_attention_i8.argtypes = [p, p, p, p, i64, i64, i64, i64, i64, p, p, i32, i32]
+        lib.hccs_oracle_requant_logits.argtypes = [p, p, p, i64, i64, i64, i64, i64, p]
         lib.hccs_oracle_reciprocal_u8.argtypes = [p, p, i64]
         lib.hccs_oracle_calibrate.argtypes = [p, i64, i64, i64, i64, p, p, i64, p, p, i32]
         _lib = lib
@@ -77,17 +77,19 @@ def softmax(logits, table, band, mode=MODE_U8, threads=1):
 
 
 def attention(q, k, v, table, requant, band, threads=1):
-    """q,k,v int8 [B,H,L,d]; table int32 [H,3]; requant int32 [H,2].  Returns (o int32, status)."""
+    """q int8 [B,H,Lq,d]; k,v int8 [B,H,Lk,d]; table int32 [H,3]; requant int32 [H,2].
+    Returns (o int32 [B,H,Lq,d], status)."""
     q = np.ascontiguousarray(q, dtype=np.int8)
     k = np.ascontiguousarray(k, dtype=np.int8)
     v = np.ascontiguousarray(v, dtype=np.int8)
     table = np.ascontiguousarray(table, dtype=np.int32)
     requant = np.ascontiguousarray(requant, dtype=np.int32)
-    Bt, H, L, d = q.shape
-    assert k.shape == q.shape and v.shape == q.shape
+    Bt, H, Lq, d = q.shape
+    Lk = k.shape[2]
+    assert k.shape == (Bt, H, Lk, d) and v.shape == k.shape
     assert table.shape == (H, 3) and requant.shape == (H, 2)
     o = np.zeros(q.shape, dtype=np.int32)
-    rc = load().hccs_oracle_attention_i8(_ptr(q), _ptr(k), _ptr(v), _ptr(o), Bt, H, L, d,
+    rc = load().hccs_oracle_attention_i8(_ptr(q), _ptr(k), _ptr(v), _ptr(o), Bt, H, Lq, Lk, d,
                                          _ptr(table), _ptr(requant), int(band), int(threads))
     return o, rc
 
@@ -96,9 +98,10 @@ def requant_logits(q, k, requant):
     q = np.ascontiguousarray(q, dtype=np.int8)
     k = np.ascontiguousarray(k, dtype=np.int8)
     requant = np.ascontiguousarray(requant, dtype=np.int32)
-    Bt, H, L, d = q.shape
-    x = np.zeros((Bt, H, L, L), dtype=np.int8)
-    rc = load().hccs_oracle_requant_logits(_ptr(q), _ptr(k), _ptr(x), Bt, H, L, d, _ptr(requant))
+    Bt, H, Lq, d = q.shape
+    Lk = k.shape[2]
+    x = np.zeros((Bt, H, Lq, Lk), dtype=np.int8)
+    rc = load().hccs_oracle_requant_logits(_ptr(q), _ptr(k), _ptr(x), Bt, H, Lq, Lk, d, _ptr(requant))
     return x, rc
 
 

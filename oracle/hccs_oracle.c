@@ -247,24 +247,24 @@ int hccs_oracle_softmax(const int8_t *logits, void *out, int64_t Bt, int64_t H, 
     return status;
 }
 
-/* Fused block for one tensor set Q,K,V [Bt,H,L,d] int8 -> O [Bt,H,L,d] int32.
+/* Fused block: Q [Bt,H,Lq,d], K and V [Bt,H,Lk,d] int8 -> O [Bt,H,Lq,d] int32.
  * Per (b,h):
  *   A[i][j] = sum_t Q[i][t]*K[j][t]                      (no 1/sqrt(d): any such
  *                                                         factor lives in mult/shift)
  *   x[i][j] = clamp((A[i][j]*mult_h + 2^(shift_h-1)) >> shift_h, -128, 127)
  *             with a flooring (arithmetic) shift: round half up
- *   p[i][.] = HCCS 8-bit row of x[i][.] with n = L and head h's constants
+ *   p[i][.] = HCCS 8-bit row of x[i][.] with n = Lk and head h's constants
  *   O[i][t] = sum_j p[i][j]*V[j][t]
  * requant holds H pairs (mult, shift), 1 <= mult <= 4096, 1 <= shift <= 23.
  * This requantisation rule is this repository's definition, not the paper's. */
 int hccs_oracle_attention_i8(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o,
-                             int64_t Bt, int64_t H, int64_t L, int64_t d, const int32_t *table,
-                             const int32_t *requant, int band, int threads)
+                             int64_t Bt, int64_t H, int64_t Lq, int64_t Lk, int64_t d,
+                             const int32_t *table, const int32_t *requant, int band, int threads)
 {
     if (!q || !k || !v || !o || !table || !requant) return ORACLE_E_ARG;
-    if (Bt < 0 || H < 1 || L < 1 || d < 1) return ORACLE_E_ARG;
+    if (Bt < 0 || H < 1 || Lq < 0 || Lk < 1 || d < 1) return ORACLE_E_ARG;
     for (int64_t h = 0; h < H; ++h) {
-        int rc = hccs_oracle_check_params(table[3 * h], table[3 * h + 1], table[3 * h + 2], L, band);
+        int rc = hccs_oracle_check_params(table[3 * h], table[3 * h + 1], table[3 * h + 2], Lk, band);
         if (rc != ORACLE_OK) return rc;
         if (requant[2 * h] < 1 || requant[2 * h] > 4096) return ORACLE_E_ARG;
         if (requant[2 * h + 1] < 1 || requant[2 * h + 1] > 23) return ORACLE_E_ARG;
@@ -277,12 +277,12 @@ int hccs_oracle_attention_i8(const int8_t *q, const int8_t *k, const int8_t *v, 
         const int64_t h = bh % H;
         const int64_t B = table[3 * h], S = table[3 * h + 1], D = table[3 * h + 2];
         const int64_t mult = requant[2 * h], shift = requant[2 * h + 1];
-        const int8_t *Q = q + bh * L * d, *K = k + bh * L * d, *V = v + bh * L * d;
-        int32_t *O = o + bh * L * d;
-        int8_t *x = (int8_t *)malloc((size_t)L);
-        uint8_t *p = (uint8_t *)malloc((size_t)L);
-        for (int64_t i = 0; i < L; ++i) {
-            for (int64_t j = 0; j < L; ++j) {
+        const int8_t *Q = q + bh * Lq * d, *K = k + bh * Lk * d, *V = v + bh * Lk * d;
+        int32_t *O = o + bh * Lq * d;
+        int8_t *x = (int8_t *)malloc((size_t)Lk);
+        uint8_t *p = (uint8_t *)malloc((size_t)Lk);
+        for (int64_t i = 0; i < Lq; ++i) {
+            for (int64_t j = 0; j < Lk; ++j) {
                 int64_t acc = 0;
                 for (int64_t t = 0; t < d; ++t) acc += (int64_t)Q[i * d + t] * (int64_t)K[j * d + t];
                 int64_t prod = acc * mult + ((int64_t)1 << (shift - 1));
@@ -295,14 +295,14 @@ int hccs_oracle_attention_i8(const int8_t *q, const int8_t *k, const int8_t *v, 
                 if (y > 127) y = 127;
                 x[j] = (int8_t)y;
             }
-            int rc = hccs_oracle_row_u8(x, L, B, S, D, p, 0, 0);
+            int rc = hccs_oracle_row_u8(x, Lk, B, S, D, p, 0, 0);
             if (rc != ORACLE_OK) {
 #pragma omp critical
                 status = rc;
             }
             for (int64_t t = 0; t < d; ++t) {
                 int64_t acc = 0;
-                for (int64_t j = 0; j < L; ++j) acc += (int64_t)p[j] * (int64_t)V[j * d + t];
+                for (int64_t j = 0; j < Lk; ++j) acc += (int64_t)p[j] * (int64_t)V[j * d + t];
                 if (acc > INT32_MAX || acc < INT32_MIN) {
 #pragma omp critical
                     status = ORACLE_E_INTERNAL;
@@ -317,18 +317,18 @@ int hccs_oracle_attention_i8(const int8_t *q, const int8_t *k, const int8_t *v, 
 }
 
 /* The int8 logits the fused block feeds to HCCS, exposed so that a test can
- * look at the middle of the pipeline: x [Bt,H,L,L]. */
+ * look at the middle of the pipeline: x [Bt,H,Lq,Lk]. */
 int hccs_oracle_requant_logits(const int8_t *q, const int8_t *k, int8_t *x, int64_t Bt, int64_t H,
-                               int64_t L, int64_t d, const int32_t *requant)
+                               int64_t Lq, int64_t Lk, int64_t d, const int32_t *requant)
 {
     if (!q || !k || !x || !requant) return ORACLE_E_ARG;
     for (int64_t bh = 0; bh < Bt * H; ++bh) {
         const int64_t h = bh % H;
         const int64_t mult = requant[2 * h], shift = requant[2 * h + 1];
         if (mult < 1 || mult > 4096 || shift < 1 || shift > 23) return ORACLE_E_ARG;
-        const int8_t *Q = q + bh * L * d, *K = k + bh * L * d;
-        for (int64_t i = 0; i < L; ++i)
-            for (int64_t j = 0; j < L; ++j) {
+        const int8_t *Q = q + bh * Lq * d, *K = k + bh * Lk * d;
+        for (int64_t i = 0; i < Lq; ++i)
+            for (int64_t j = 0; j < Lk; ++j) {
                 int64_t acc = 0;
                 for (int64_t t = 0; t < d; ++t) acc += (int64_t)Q[i * d + t] * (int64_t)K[j * d + t];
                 int64_t prod = acc * mult + ((int64_t)1 << (shift - 1));
@@ -337,7 +337,7 @@ int hccs_oracle_requant_logits(const int8_t *q, const int8_t *k, int8_t *x, int6
                 if (prod % two != 0 && prod < 0) y -= 1;
                 if (y < -128) y = -128;
                 if (y > 127) y = 127;
-                x[(bh * L + i) * L + j] = (int8_t)y;
+                x[(bh * Lq + i) * Lk + j] = (int8_t)y;
             }
     }
     return ORACLE_OK;

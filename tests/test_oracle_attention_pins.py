@@ -119,3 +119,22 @@ def test_offset_identity_for_unsigned_probabilities(oracle):
     signed = p.astype(np.int64) - 128
     want = np.matmul(signed, v.astype(np.int64)) + 128 * v.astype(np.int64).sum(axis=-2, keepdims=True)
     assert np.array_equal(o.astype(np.int64), want)
+
+
+def test_rectangular_blocks_against_library_matmul(oracle):
+    """Lq != Lk: n = Lk for the row function and the band; each query row is independent."""
+    g = np.random.default_rng(8)
+    Bt, H, Lq, Lk, d = 2, 2, 5, 48, 16
+    q = g.integers(-64, 64, size=(Bt, H, Lq, d), dtype=np.int8)
+    k = g.integers(-64, 64, size=(Bt, H, Lk, d), dtype=np.int8)
+    v = g.integers(-64, 64, size=(Bt, H, Lk, d), dtype=np.int8)
+    table = synth.head_params(H, Lk, 1, seed=1)
+    rq = synth.requant_params(H, seed=1, shift=11, mult_lo=20, mult_hi=60)
+    o, rc = oracle.attention(q, k, v, table, rq, 1)
+    x, rc2 = oracle.requant_logits(q, k, rq)
+    assert rc == 0 and rc2 == 0 and x.shape == (Bt, H, Lq, Lk)
+    p, _ = oracle.softmax(x, table, 1)
+    assert np.array_equal(o.astype(np.int64), np.matmul(p.astype(np.int64), v.astype(np.int64)))
+    # dropping query rows does not change the others
+    o2, _ = oracle.attention(q[:, :, :2], k, v, table, rq, 1)
+    assert np.array_equal(o2, o[:, :, :2])
