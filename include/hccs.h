@@ -121,14 +121,27 @@ HCCS_API int hccs_calibrated_softmax_i8_ex(const int8_t *logits_dev, void *out_d
  *   A = Q.K^T (int32)  ->  x = requant_h(A) (int8)  ->  P = HCCS_u8(x) row-wise, n = L
  *   ->  O = P.V (int32).  Logits and probabilities never reach HBM.
  *   q_dev,k_dev,v_dev [B,H,L,d] int8, 16-byte aligned; o_dev [B,H,L,d] int32, 16-byte aligned.
- *   Supported shapes: d = 64; L a multiple of 64, 64 <= L <= 512; 1 <= H <= HCCS_MAX_HEADS.
+ *   Same as hccs_attention_i8_ex with Lq = Lk = L.
  *   table_host H entries validated against `band` with n = L; requant_host H entries.
  * The block is motivated, not defined, by the paper (Sec. I, Sec. II); the
  * rescale rule is the one documented at hccs_requant. */
 HCCS_API int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev,
-                      int32_t B, int32_t H, int32_t L, int32_t d,
-                      const hccs_head_params *table_host, const hccs_requant *requant_host,
-                      int32_t out_scale_T, int32_t band, void *hip_stream);
+                               int32_t B, int32_t H, int32_t L, int32_t d,
+                               const hccs_head_params *table_host, const hccs_requant *requant_host,
+                               int32_t out_scale_T, int32_t band, void *hip_stream);
+
+/* The same block with separate query and key lengths:
+ *   q_dev [B,H,Lq,d], k_dev and v_dev [B,H,Lk,d] int8, o_dev [B,H,Lq,d] int32, all 16-byte aligned.
+ *   d = 64 or 128; Lk a multiple of 16, 16 <= Lk <= HCCS_MAX_ROW_LENGTH; Lq >= 0 (0 is a no-op);
+ *   B*H <= 65535.  The row length of HCCS, and of the band check, is n = Lk.
+ * Square blocks with d = 64 and Lk a multiple of 64 up to 512 keep a query tile's logits in
+ * registers and K, V in LDS; every other shape streams K and V in chunks of 64 keys and
+ * recomputes Q.K^T three times (maximum, sum, output), because the floors of HCCS do not allow
+ * partial results to be rescaled.  Both are bit-exact to the same definition. */
+HCCS_API int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev,
+                                  int32_t B, int32_t H, int32_t Lq, int32_t Lk, int32_t d,
+                                  const hccs_head_params *table_host, const hccs_requant *requant_host,
+                                  int32_t out_scale_T, int32_t band, void *hip_stream);
 
 /* Offline calibration by grid search (Sec. III-C, Eq. (10)).  For every head h and candidate c,
  *   objective[h*n_candidates + c] = mean over the rows of head h of

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libhccs.so")
 BAND_U8, BAND_STRICT = 0, 1
 RECIP_EXACT, RECIP_CLB = 0, 1
 
-EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_calibrated_softmax_i8_ex", "hccs_attention_i8",
+EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_calibrated_softmax_i8_ex", "hccs_attention_i8", "hccs_attention_i8_ex",
            "hccs_calibrate_workspace_bytes", "hccs_calibrate_grid",
            "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_copy_bytes", "hccs_status_string"]
 
@@ -52,6 +52,8 @@ def lib():
                                                     i32, vp]
         L.hccs_attention_i8.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, ctypes.POINTER(HeadParams),
                                         ctypes.POINTER(Requant), i32, i32, vp]
+        L.hccs_attention_i8_ex.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.POINTER(HeadParams),
+                                           ctypes.POINTER(Requant), i32, i32, vp]
         L.hccs_calibrate_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.hccs_calibrate_workspace_bytes.restype = i64
         L.hccs_calibrate_grid.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_double), vp, i32, vp, vp, vp,
@@ -189,21 +191,29 @@ def prepare_attention(q, k, v, out, table, requant, band, out_scale_T=255):
 
 
 def attention_i8(q, k, v, table, requant, band, out=None, out_scale_T=255, stream=None):
-    """q,k,v: int8 CUDA tensors [B,H,L,d].  Returns O int32 [B,H,L,d]."""
+    """q: int8 CUDA [B,H,Lq,d]; k, v: int8 CUDA [B,H,Lk,d].  Returns O int32 [B,H,Lq,d].
+    Square inputs go through hccs_attention_i8, others through hccs_attention_i8_ex."""
     import torch
     for t in (q, k, v):
-        assert t.is_cuda and t.dtype == torch.int8 and t.is_contiguous() and t.dim() == 4 and t.shape == q.shape
+        assert t.is_cuda and t.dtype == torch.int8 and t.is_contiguous() and t.dim() == 4
+    assert k.shape == v.shape and q.shape[:2] == k.shape[:2] and q.shape[3] == k.shape[3]
     if out is None:
         out = torch.empty(q.shape, dtype=torch.int32, device=q.device)
     assert out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and out.shape == q.shape
-    B, H, L, d = q.shape
+    B, H, Lq, d = q.shape
+    Lk = k.shape[2]
     arr, Ht = head_table(table)
     rq, Hr = requant_table(requant)
     if Ht != H or Hr != H:
         raise HccsError(-2, "table and requant must have one entry per head")
-    _check(lib().hccs_attention_i8(ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()),
-                                   ctypes.c_void_p(v.data_ptr()), ctypes.c_void_p(out.data_ptr()),
-                                   B, H, L, d, arr, rq, int(out_scale_T), int(band), _stream_handle(stream)))
+    ptrs = (ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k.data_ptr()), ctypes.c_void_p(v.data_ptr()),
+            ctypes.c_void_p(out.data_ptr()))
+    if Lq == Lk:
+        _check(lib().hccs_attention_i8(*ptrs, B, H, Lk, d, arr, rq, int(out_scale_T), int(band),
+                                       _stream_handle(stream)))
+    else:
+        _check(lib().hccs_attention_i8_ex(*ptrs, B, H, Lq, Lk, d, arr, rq, int(out_scale_T), int(band),
+                                          _stream_handle(stream)))
     return out
 
 

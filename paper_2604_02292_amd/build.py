@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhccs.so")
-SOURCES = ["hccs_api.hip", "hccs_softmax.hip", "hccs_attention.hip", "hccs_calibrate.hip", "exp_softmax.hip"]
+SOURCES = ["hccs_api.hip", "hccs_softmax.hip", "hccs_attention.hip", "hccs_attention_stream.hip", "hccs_calibrate.hip", "exp_softmax.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wextra", "-Wno-unused-parameter"]

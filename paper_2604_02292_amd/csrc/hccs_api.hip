@@ -11,6 +11,9 @@ hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hi
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
 hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
                             int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st);
+hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H,
+                                   int Lq, int Lk, int d, const HeadTable &tab, const RequantTable &rq,
+                                   hipStream_t st);
 int64_t calibrate_workspace_bytes(int64_t Bt, int64_t H, int64_t Lq);
 hipError_t launch_calibrate(const int8_t *logits, int Bt, int H, int Lq, int Lk, const double *alpha,
                             const hccs_head_params *cand, int nc, double *objective, int32_t *best, void *workspace,
@@ -104,21 +107,21 @@ int hccs_calibrated_softmax_i8(const int8_t *logits_dev, uint8_t *probs_dev, int
                                          band, hip_stream);
 }
 
-int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev, int32_t B,
-                      int32_t H, int32_t L, int32_t d, const hccs_head_params *table_host,
-                      const hccs_requant *requant_host, int32_t out_scale_T, int32_t band, void *hip_stream)
+int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev, int32_t B,
+                         int32_t H, int32_t Lq, int32_t Lk, int32_t d, const hccs_head_params *table_host,
+                         const hccs_requant *requant_host, int32_t out_scale_T, int32_t band, void *hip_stream)
 {
     if (!table_host || !requant_host) return HCCS_E_NULL;
-    if (B < 0 || H < 1 || H > HCCS_MAX_HEADS || (int64_t)B * H > 0x7fffffff) return HCCS_E_SHAPE;
-    if (d != 64 || L < 64 || L > 512 || L % 64 != 0) return HCCS_E_SHAPE;
+    if (B < 0 || H < 1 || H > HCCS_MAX_HEADS || (int64_t)B * H > 65535) return HCCS_E_SHAPE;
+    if ((d != 64 && d != 128) || Lq < 0 || Lk < 16 || Lk > HCCS_MAX_ROW_LENGTH || Lk % 16 != 0) return HCCS_E_SHAPE;
     if (out_scale_T != 255) return HCCS_E_SCALE;
-    const int rc = hccs_validate_params(table_host, H, L, band, nullptr);
+    const int rc = hccs_validate_params(table_host, H, Lk, band, nullptr);
     if (rc != HCCS_OK) return rc;
     for (int h = 0; h < H; ++h) {
         if (requant_host[h].mult < 1 || requant_host[h].mult > 4096) return HCCS_E_REQUANT;
         if (requant_host[h].shift < 1 || requant_host[h].shift > 23) return HCCS_E_REQUANT;
     }
-    if (B == 0) return HCCS_OK;
+    if (B == 0 || Lq == 0) return HCCS_OK;
     if (!q_dev || !k_dev || !v_dev || !o_dev) return HCCS_E_NULL;
     if (!aligned16(q_dev) || !aligned16(k_dev) || !aligned16(v_dev) || !aligned16(o_dev)) return HCCS_E_ALIGN;
     hccs::HeadTable tab;
@@ -126,9 +129,21 @@ int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_
     hccs::RequantTable rq;
     for (int h = 0; h < HCCS_MAX_HEADS; ++h)
         rq.e[h] = h < H ? make_int2(requant_host[h].mult, requant_host[h].shift) : make_int2(1, 1);
+    // square blocks whose rows fit the register file go to the resident kernel, everything else streams
+    const bool resident = d == 64 && Lq == Lk && Lk % 64 == 0 && Lk <= 512;
     const hipError_t e =
-        hccs::launch_attention(q_dev, k_dev, v_dev, o_dev, B, H, L, d, tab, rq, (hipStream_t)hip_stream);
+        resident ? hccs::launch_attention(q_dev, k_dev, v_dev, o_dev, B, H, Lk, d, tab, rq, (hipStream_t)hip_stream)
+                 : hccs::launch_attention_stream(q_dev, k_dev, v_dev, o_dev, B, H, Lq, Lk, d, tab, rq,
+                                                 (hipStream_t)hip_stream);
     return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev, int32_t B,
+                      int32_t H, int32_t L, int32_t d, const hccs_head_params *table_host,
+                      const hccs_requant *requant_host, int32_t out_scale_T, int32_t band, void *hip_stream)
+{
+    return hccs_attention_i8_ex(q_dev, k_dev, v_dev, o_dev, B, H, L, L, d, table_host, requant_host, out_scale_T,
+                                band, hip_stream);
 }
 
 int64_t hccs_calibrate_workspace_bytes(int32_t B, int32_t H, int32_t Lq, int32_t Lk)

@@ -23,37 +23,9 @@
 //
 // Every global load of K and V is issued before the first LDS write, and the next
 // tile's Q operand is fetched while the current tile is still in its HCCS stage.
-#include "hccs_device.h"
+#include "hccs_attention_common.h"
 
 namespace hccs {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-
-// min(max(x, lo), hi); the compiler selects v_med3_i32 for it
-__device__ __forceinline__ int clamp_i32(int x, int lo, int hi) { return min(max(x, lo), hi); }
-
-// D = S0.u16 * S1.u16 + S2.u32 on the low (lo) or high (hi) half of the first source.
-__device__ __forceinline__ uint32_t mad_u32_u16_lo(uint32_t a, uint32_t b, uint32_t c)
-{
-    uint32_t d;
-    asm("v_mad_u32_u16 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-    return d;
-}
-__device__ __forceinline__ uint32_t mad_u32_u16_hi(uint32_t a, uint32_t b, uint32_t c)
-{
-    uint32_t d;
-    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-    return d;
-}
-
-constexpr int kKStride = 80;   // bytes per K row in LDS: 64 + 16 of padding against bank conflicts
-
-// How the int32 accumulator becomes a 16-bit logit (before the int8 saturation):
-enum : int {
-    kRescaleHigh16 = 0,   // every head's rule was rewritten to shift 16: the logit is the high half
-    kRescaleShift = 1,    // multiply-add, arithmetic shift, saturating pack
-    kRescalePreclamp = 2  // as kRescaleShift, with the accumulator saturated first
-};
 
 // The HCCS stage runs on 16-bit pairs (two logits per register, v_pk_* instructions):
 //   x' = clamp(y, max(m - D, -128), 127), s = B - S*(m - x')             (Eq. (2), (3))
@@ -127,14 +99,10 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
                 u32x4 w[4];   // w[dt][tt]
 #pragma unroll
                 for (int tt = 0; tt < 4; ++tt) {
-                    const uint32_t a_lo = __builtin_amdgcn_perm(vreg[i][tt][1], vreg[i][tt][0], 0x05010400u);
-                    const uint32_t a_hi = __builtin_amdgcn_perm(vreg[i][tt][1], vreg[i][tt][0], 0x07030602u);
-                    const uint32_t b_lo = __builtin_amdgcn_perm(vreg[i][tt][3], vreg[i][tt][2], 0x05010400u);
-                    const uint32_t b_hi = __builtin_amdgcn_perm(vreg[i][tt][3], vreg[i][tt][2], 0x07030602u);
-                    w[0][tt] = __builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u);
-                    w[1][tt] = __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u);
-                    w[2][tt] = __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u);
-                    w[3][tt] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
+                    uint32_t col[4];
+                    transpose4x4(vreg[i][tt], col);
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt) w[dt][tt] = col[dt];
                 }
 #pragma unroll
                 for (int dt = 0; dt < 4; ++dt) {
@@ -173,21 +141,7 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
                 const v4i kop = *(const v4i *)(lds_k + ((t + 1) * 16 + qi) * kKStride + g * 16);
                 acc_next = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
             }
-            int y[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                int a = acc[r];
-                if constexpr (RQ == kRescalePreclamp) a = clamp_i32(a, -lim, lim);
-                y[r] = __mul24(a, mult) + round_c;
-            }
-            if constexpr (RQ == kRescaleHigh16) {
-                // shift is 16 and |acc*mult + 2^15| < 2^31: the logit is the signed high half
-                xp[t][0] = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x07060302u));
-                xp[t][1] = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x07060302u));
-            } else {
-                xp[t][0] = __builtin_amdgcn_cvt_pk_i16(y[0] >> shift, y[1] >> shift);   // saturating 32 -> 16
-                xp[t][1] = __builtin_amdgcn_cvt_pk_i16(y[2] >> shift, y[3] >> shift);
-            }
+            rescale_tile<RQ>(acc, mult, shift, round_c, lim, xp[t][0], xp[t][1]);
             mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(xp[t][0], xp[t][1]));
             acc = acc_next;
             __builtin_amdgcn_sched_barrier(0);
@@ -233,20 +187,13 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
                 oacc[dt] = (v4i){init, init, init, init};
             }
         }
-        const uint32_t bias = 0x800000u;               // +128 in byte 2: p ^ 0x80 for p <= 255
 #pragma unroll
         for (int T = 0; T < NQ; ++T) {
             v4i pop;
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
-                const uint32_t s01 = __builtin_bit_cast(uint32_t, xp[T * 4 + tt][0]);
-                const uint32_t s23 = __builtin_bit_cast(uint32_t, xp[T * 4 + tt][1]);
-                const uint32_t e0 = mad_u32_u16_lo(s01, rho2, bias), e1 = mad_u32_u16_hi(s01, rho2, bias);
-                const uint32_t e2 = mad_u32_u16_lo(s23, rho2, bias), e3 = mad_u32_u16_hi(s23, rho2, bias);
-                const uint32_t h01 = __builtin_amdgcn_perm(e1, e0, 0x00000602u);
-                const uint32_t h23 = __builtin_amdgcn_perm(e3, e2, 0x00000602u);
-                pop[tt] = (int)__builtin_amdgcn_perm(h23, h01, 0x05040100u);
-            }
+            for (int tt = 0; tt < 4; ++tt)
+                pop[tt] = (int)probabilities_minus_128(__builtin_bit_cast(uint32_t, xp[T * 4 + tt][0]),
+                                                       __builtin_bit_cast(uint32_t, xp[T * 4 + tt][1]), rho2);
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
                 const v4i vop = *(const v4i *)(lds_v + (((T * 4 + dt) * 4 + g) * 16 + qi) * 16);
@@ -286,21 +233,8 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
                             int d, const HeadTable &tab, const RequantTable &rq_in, hipStream_t st)
 {
     (void)d;   // 64, checked by the caller
-    // |acc| <= 64*128*128 = 2^20.  Pick the cheapest rescale form that is exact for every head:
-    //  - if each rule (mult, shift <= 16) can be rewritten as (mult << (16-shift), 16) without
-    //    acc*mult + 2^15 leaving 32 bits, the logit is simply the high half of that word;
-    //  - else multiply-add and shift; if acc*mult + 2^(shift-1) could leave 32 bits for some
-    //    head, the accumulator is saturated first (same result, one more instruction).
-    RequantTable rq = rq_in;
-    bool high16 = true, preclamp = false;
-    for (int h = 0; h < H; ++h) {
-        const int64_t mult = rq_in.e[h].x, shift = rq_in.e[h].y;
-        if (shift > 16 || (((int64_t)1 << 20) * (mult << (16 - shift)) + (1 << 15)) > 0x7fffffffll) high16 = false;
-        if (((int64_t)1 << 20) * mult + ((int64_t)1 << (shift - 1)) > 0x7fffffffll) preclamp = true;
-    }
-    if (high16)
-        for (int h = 0; h < H; ++h) rq.e[h] = make_int2(rq_in.e[h].x << (16 - rq_in.e[h].y), 16);
-    const int kind = high16 ? kRescaleHigh16 : (preclamp ? kRescalePreclamp : kRescaleShift);
+    RequantTable rq;
+    const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
     const int blocks = Bt * H;
     switch (L / 16) {
         case 4: return launch_nt<4>(q, k, v, o, blocks, H, tab, rq, kind, st);

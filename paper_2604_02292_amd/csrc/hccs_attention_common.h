@@ -1,0 +1,101 @@
+// Pieces shared by the two fused-attention kernels (resident and streaming).
+#pragma once
+#include "hccs_device.h"
+
+namespace hccs {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// min(max(x, lo), hi); the compiler selects v_med3_i32 for it
+__device__ __forceinline__ int clamp_i32(int x, int lo, int hi) { return min(max(x, lo), hi); }
+
+// D = S0.u16 * S1.u16 + S2.u32 on the low (lo) or high (hi) half of the first source.
+__device__ __forceinline__ uint32_t mad_u32_u16_lo(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t d;
+    asm("v_mad_u32_u16 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+__device__ __forceinline__ uint32_t mad_u32_u16_hi(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t d;
+    asm("v_mad_u32_u16 %0, %1, %2, %3 op_sel:[1,0,0,0]" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
+constexpr int kKStride = 80;   // bytes per K row in LDS: 64 + 16 of padding against bank conflicts
+
+// How the int32 accumulator becomes a 16-bit logit (before the int8 saturation):
+enum : int {
+    kRescaleHigh16 = 0,   // every head's rule was rewritten to shift 16: the logit is the high half
+    kRescaleShift = 1,    // multiply-add, arithmetic shift, saturating pack
+    kRescalePreclamp = 2  // as kRescaleShift, with the accumulator saturated first
+};
+
+
+// Rescale of four accumulators of one key tile to two 16-bit logit pairs (before the int8
+// saturation): keys r = 0,1 in the first pair, r = 2,3 in the second.
+template <int RQ>
+__device__ __forceinline__ void rescale_tile(const v4i &acc, int mult, int shift, int round_c, int lim,
+                                             short2_t &p01, short2_t &p23)
+{
+    int y[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        int a = acc[r];
+        if constexpr (RQ == kRescalePreclamp) a = clamp_i32(a, -lim, lim);
+        y[r] = __mul24(a, mult) + round_c;
+    }
+    if constexpr (RQ == kRescaleHigh16) {
+        // shift is 16 and |acc*mult + 2^15| < 2^31: the logit is the signed high half
+        p01 = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm((uint32_t)y[1], (uint32_t)y[0], 0x07060302u));
+        p23 = __builtin_bit_cast(short2_t, __builtin_amdgcn_perm((uint32_t)y[3], (uint32_t)y[2], 0x07060302u));
+    } else {
+        p01 = __builtin_amdgcn_cvt_pk_i16(y[0] >> shift, y[1] >> shift);   // saturating 32 -> 16
+        p23 = __builtin_amdgcn_cvt_pk_i16(y[2] >> shift, y[3] >> shift);
+    }
+}
+
+// Four scores (two 16-bit pairs) -> four bytes P - 128: byte 2 of s*(2*rho) + 0x800000 is
+// ((s*rho) >> 15) + 128 modulo 256.
+__device__ __forceinline__ uint32_t probabilities_minus_128(uint32_t s01, uint32_t s23, uint32_t rho2)
+{
+    const uint32_t bias = 0x800000u;
+    const uint32_t e0 = mad_u32_u16_lo(s01, rho2, bias), e1 = mad_u32_u16_hi(s01, rho2, bias);
+    const uint32_t e2 = mad_u32_u16_lo(s23, rho2, bias), e3 = mad_u32_u16_hi(s23, rho2, bias);
+    const uint32_t h01 = __builtin_amdgcn_perm(e1, e0, 0x00000602u);
+    const uint32_t h23 = __builtin_amdgcn_perm(e3, e2, 0x00000602u);
+    return __builtin_amdgcn_perm(h23, h01, 0x05040100u);
+}
+
+// 4x4 byte transpose: r[k] holds 4 columns of key k; w[c] receives the 4 keys of column c.
+__device__ __forceinline__ void transpose4x4(const uint32_t (&r)[4], uint32_t (&w)[4])
+{
+    const uint32_t a_lo = __builtin_amdgcn_perm(r[1], r[0], 0x05010400u);
+    const uint32_t a_hi = __builtin_amdgcn_perm(r[1], r[0], 0x07030602u);
+    const uint32_t b_lo = __builtin_amdgcn_perm(r[3], r[2], 0x05010400u);
+    const uint32_t b_hi = __builtin_amdgcn_perm(r[3], r[2], 0x07030602u);
+    w[0] = __builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u);
+    w[1] = __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u);
+    w[2] = __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u);
+    w[3] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
+}
+
+// Picks the cheapest exact rescale form for a set of heads (|acc| <= acc_bound) and rewrites
+// the table for it: every rule as (mult << (16-shift), 16) if that keeps acc*mult + 2^15 in 32
+// bits, else multiply-add and shift, with the accumulator saturated first if needed.
+inline int choose_rescale(const RequantTable &in, int H, int64_t acc_bound, RequantTable &out)
+{
+    out = in;
+    bool high16 = true, preclamp = false;
+    for (int h = 0; h < H; ++h) {
+        const int64_t mult = in.e[h].x, shift = in.e[h].y;
+        if (shift > 16 || (acc_bound * (mult << (16 - shift)) + (1 << 15)) > 0x7fffffffll) high16 = false;
+        if (acc_bound * mult + ((int64_t)1 << (shift - 1)) > 0x7fffffffll) preclamp = true;
+    }
+    if (high16)
+        for (int h = 0; h < H; ++h) out.e[h] = make_int2(in.e[h].x << (16 - in.e[h].y), 16);
+    return high16 ? kRescaleHigh16 : (preclamp ? kRescalePreclamp : kRescaleShift);
+}
+
+}  // namespace hccs

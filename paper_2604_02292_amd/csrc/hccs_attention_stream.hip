@@ -1,0 +1,249 @@
+// Fused int8 attention block for shapes the resident kernel does not take: any number of
+// queries, any key length that is a multiple of 16, head size 64 or 128.  K and V stream
+// through LDS in chunks of 64 keys, so neither the logits of a row nor K and V have to fit
+// anywhere.  HCCS needs the row maximum before the clamped sum and the sum before the first
+// output, and its floors rule out rescaling partial results, so Q.K^T is recomputed three
+// times: pass A finds the maximum, pass B the sum Z, pass C the probabilities and O = P.V.
+// Same arithmetic per element as the resident kernel (hccs_attention_common.h).
+//
+// Grid (query tiles of 64, batch*head); a wave owns 16 queries.  A chunk is double-buffered:
+// the global loads of chunk c+1 are issued before chunk c is computed and written to the
+// other LDS buffer afterwards, one barrier per chunk.
+#include "hccs_attention_common.h"
+
+namespace hccs {
+
+template <int ND, int RQ>   // head size d = 64*ND
+__global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t *__restrict__ q,
+                                                                    const int8_t *__restrict__ k,
+                                                                    const int8_t *__restrict__ v,
+                                                                    int32_t *__restrict__ o, int H, int Lq, int Lk,
+                                                                    HeadTable table, RequantTable requant)
+{
+    constexpr int DH = 64 * ND;          // head size
+    constexpr int KSTR = DH + 16;        // padded K row in LDS (bank spread)
+    constexpr int KPARTS = DH / 16;      // 16-byte parts of a K row
+    __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][64 * KSTR];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_v[2][64 * DH];
+    __shared__ __attribute__((aligned(16))) int32_t lds_colsum[DH];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qi = lane & 15, g = lane >> 4;
+    const int item = blockIdx.y;
+    const int head = item % H;
+    const int4 hp = table.e[head];
+    const int B = hp.x, S = hp.y, D = hp.z;
+    const int mult = requant.e[head].x, shift = requant.e[head].y;
+    const int round_c = 1 << (shift - 1);
+    const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 21);
+    const int8_t *kb = k + (size_t)item * Lk * DH;
+    const int8_t *vb = v + (size_t)item * Lk * DH;
+    const int tile = blockIdx.x * 4 + wave;
+    const bool active = tile * 16 < Lq;      // a wave without queries still stages and synchronises
+    const int nchunks = (Lk + 63) / 64;
+
+    for (int c = tid; c < DH; c += 256) lds_colsum[c] = 0;
+
+    // Q operand: row clamped into range for the tail tile (those rows are never stored)
+    v4i qop[ND];
+    {
+        const int row = min(tile * 16 + qi, Lq - 1);
+#pragma unroll
+        for (int kd = 0; kd < ND; ++kd)
+            qop[kd] = *(const v4i *)(q + ((size_t)item * Lq + row) * DH + 64 * kd + 16 * g);
+    }
+
+    // ---- chunk staging -------------------------------------------------------------------
+    u32x4 kreg[ND];
+    uint32_t vreg[ND][4];
+    auto load_chunk = [&](int chunk, bool with_v) {
+        const int key0 = chunk * 64;
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            const int c = tid + i * 256;
+            const int key = key0 + c / KPARTS;
+            kreg[i] = key < Lk ? *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16) : (u32x4){0, 0, 0, 0};
+            if (with_v) {
+                // unit (cg = i, gg, nn, tt): keys key0 + 16*tt + 4*gg + r, columns 64*cg + 4*nn .. +3
+                const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int kk = key0 + 16 * tt + 4 * gg + r;
+                    vreg[i][r] = kk < Lk ? *(const uint32_t *)(vb + (size_t)kk * DH + 64 * i + 4 * nn) : 0u;
+                }
+            }
+        }
+    };
+    auto store_chunk = [&](int buf, bool with_v) {
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            const int c = tid + i * 256;
+            *(u32x4 *)(lds_k[buf] + (c / KPARTS) * KSTR + (c % KPARTS) * 16) = kreg[i];
+            if (with_v) {
+                const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
+                uint32_t w[4];
+                transpose4x4(vreg[i], w);
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    *(uint32_t *)(lds_v[buf] + (((i * 4 + dt) * 4 + gg) * 16 + nn) * 16 + tt * 4) = w[dt];
+                    atomicAdd(&lds_colsum[64 * i + 4 * nn + dt], __builtin_amdgcn_sdot4((int)w[dt], 0x01010101, 0, false));
+                }
+            }
+        }
+    };
+
+    // logits of key tile tt of the chunk in `buf`, as two 16-bit pairs
+    auto tile_logits = [&](int buf, int tt, short2_t &p01, short2_t &p23) {
+        v4i acc = {0, 0, 0, 0};
+#pragma unroll
+        for (int kd = 0; kd < ND; ++kd) {
+            const v4i kop = *(const v4i *)(lds_k[buf] + (16 * tt + qi) * KSTR + 64 * kd + 16 * g);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop[kd], acc, 0, 0, 0);
+        }
+        rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
+    };
+
+    __syncthreads();   // colsum zeroed before any atomic
+
+    // ---- pass A: row maximum -------------------------------------------------------------
+    short2_t mx2 = {-32768, -32768};
+    load_chunk(0, false);
+    store_chunk(0, false);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        if (c + 1 < nchunks) load_chunk(c + 1, false);
+        if (active) {
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt)
+                if (c * 64 + 16 * tt < Lk) {
+                    short2_t p01, p23;
+                    tile_logits(c & 1, tt, p01, p23);
+                    mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(p01, p23));
+                }
+        }
+        if (c + 1 < nchunks) store_chunk((c + 1) & 1, false);
+        __syncthreads();
+    }
+    int mx = max((int)mx2.x, (int)mx2.y);
+    mx = max(mx, xor16(mx));
+    mx = max(mx, xor32(mx));
+    const int m = clamp_i32(mx, -128, 127);
+    const short lo = (short)max(m - D, -128);
+    const short2_t lo2 = {lo, lo}, hi2 = {127, 127};
+
+    // ---- pass B: sum of the window-clamped logits -> Z, reciprocal ----------------------------
+    int sx = 0;
+    load_chunk(0, false);
+    store_chunk(0, false);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        if (c + 1 < nchunks) load_chunk(c + 1, false);
+        if (active) {
+            short2_t sum2 = {0, 0};
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt)
+                if (c * 64 + 16 * tt < Lk) {
+                    short2_t p01, p23;
+                    tile_logits(c & 1, tt, p01, p23);
+                    sum2 += __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
+                    sum2 += __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
+                }
+            sx += (int)sum2.x + (int)sum2.y;     // at most 8 values of magnitude <= 128 per half and chunk
+        }
+        if (c + 1 < nchunks) store_chunk((c + 1) & 1, false);
+        __syncthreads();
+    }
+    sx += xor16(sx);
+    sx += xor32(sx);
+    // Z = sum (B - S*(m - x')) = Lk*B - S*(Lk*m - sum x')      (Eq. (3), (5))
+    const uint32_t Z = (uint32_t)(Lk * B - S * (Lk * m - sx));
+    const uint32_t rho2 = (active ? reciprocal_u8(Z) : 1u) * 2u;
+    const ushort2_t s2 = {(unsigned short)S, (unsigned short)S};
+    const unsigned short cc = (unsigned short)(B - S * m);
+    const ushort2_t c2 = {cc, cc};
+
+    // ---- pass C: probabilities and O = P.V ---------------------------------------------------
+    v4i oacc[ND][4];
+#pragma unroll
+    for (int cg = 0; cg < ND; ++cg)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) oacc[cg][dt] = (v4i){0, 0, 0, 0};
+    load_chunk(0, true);
+    store_chunk(0, true);
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        if (c + 1 < nchunks) load_chunk(c + 1, true);
+        if (active) {
+            v4i pop;
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) {
+                pop[tt] = (int)0x80808080u;      // P = 0 for keys past the end (their V rows are staged as zero)
+                if (c * 64 + 16 * tt < Lk) {
+                    short2_t p01, p23;
+                    tile_logits(c & 1, tt, p01, p23);
+                    const short2_t x01 = __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
+                    const short2_t x23 = __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
+                    const uint32_t s01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x01) * s2 + c2);
+                    const uint32_t s23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x23) * s2 + c2);
+                    pop[tt] = (int)probabilities_minus_128(s01, s23, rho2);
+                }
+            }
+#pragma unroll
+            for (int cg = 0; cg < ND; ++cg)
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    const v4i vop = *(const v4i *)(lds_v[c & 1] + (((cg * 4 + dt) * 4 + g) * 16 + qi) * 16);
+                    oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[cg][dt], 0, 0, 0);
+                }
+        }
+        if (c + 1 < nchunks) store_chunk((c + 1) & 1, true);
+        __syncthreads();
+    }
+
+    // ---- O = (P - 128).V + 128 * column sums of V ---------------------------------------------
+    if (active) {
+#pragma unroll
+        for (int cg = 0; cg < ND; ++cg) {
+            const v4i cs = *(const v4i *)(lds_colsum + 64 * cg + 4 * qi);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = tile * 16 + 4 * g + r;
+                const v4i out = {oacc[cg][0][r] + 128 * cs[0], oacc[cg][1][r] + 128 * cs[1],
+                                 oacc[cg][2][r] + 128 * cs[2], oacc[cg][3][r] + 128 * cs[3]};
+                if (row < Lq)
+                    __builtin_nontemporal_store(out, (v4i *)(o + ((size_t)item * Lq + row) * DH + 64 * cg + 4 * qi));
+            }
+        }
+    }
+}
+
+template <int ND>
+static hipError_t launch_stream_nd(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int items, int H,
+                                   int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
+                                   hipStream_t st)
+{
+    const dim3 grid((Lq + 63) / 64, items), block(256);
+    if (kind == kRescaleHigh16)
+        hipLaunchKernelGGL((hccs_attention_stream_kernel<ND, kRescaleHigh16>), grid, block, 0, st, q, k, v, o, H, Lq,
+                           Lk, tab, rq);
+    else if (kind == kRescaleShift)
+        hipLaunchKernelGGL((hccs_attention_stream_kernel<ND, kRescaleShift>), grid, block, 0, st, q, k, v, o, H, Lq,
+                           Lk, tab, rq);
+    else
+        hipLaunchKernelGGL((hccs_attention_stream_kernel<ND, kRescalePreclamp>), grid, block, 0, st, q, k, v, o, H,
+                           Lq, Lk, tab, rq);
+    return hipGetLastError();
+}
+
+hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H,
+                                   int Lq, int Lk, int d, const HeadTable &tab, const RequantTable &rq_in,
+                                   hipStream_t st)
+{
+    RequantTable rq;
+    const int kind = choose_rescale(rq_in, H, (int64_t)d << 14, rq);   // |acc| <= d*128*128
+    if (d == 64) return launch_stream_nd<1>(q, k, v, o, Bt * H, H, Lq, Lk, tab, rq, kind, st);
+    if (d == 128) return launch_stream_nd<2>(q, k, v, o, Bt * H, H, Lq, Lk, tab, rq, kind, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace hccs

@@ -352,6 +352,58 @@ def test_attention_full_range_inputs_and_large_multiplier(oracle):
     check_attention(q, k, v, table, rq, 0, oracle, "extremes")
 
 
+def rect_qkv(seed, Bt, H, Lq, Lk, d, lo=-64, hi=63):
+    g = np.random.default_rng(seed)
+    return (g.integers(lo, hi + 1, size=(Bt, H, Lq, d), dtype=np.int8),
+            g.integers(lo, hi + 1, size=(Bt, H, Lk, d), dtype=np.int8),
+            g.integers(lo, hi + 1, size=(Bt, H, Lk, d), dtype=np.int8))
+
+
+# streaming kernel: rectangular blocks, key lengths beyond the resident kernel, ragged tails, d = 128
+STREAM_SHAPES = [  # (Bt, H, Lq, Lk, d, band)
+    (1, 2, 64, 128, 64, 1), (2, 3, 40, 256, 64, 1), (1, 2, 7, 48, 64, 1), (1, 1, 130, 80, 64, 1),
+    (1, 2, 33, 1024, 64, 1), (1, 1, 20, 2064, 64, 0), (1, 2, 64, 64, 128, 1), (2, 2, 50, 272, 128, 1),
+    (1, 1, 16, 4096, 128, 0), (1, 2, 100, 576, 64, 0), (3, 1, 1, 16, 64, 1), (1, 1, 70, 1040, 128, 0),
+]
+
+
+@pytest.mark.parametrize("Bt,H,Lq,Lk,d,band", STREAM_SHAPES)
+def test_attention_streaming_shapes(oracle, Bt, H, Lq, Lk, d, band):
+    q, k, v = rect_qkv(Lq + Lk + d, Bt, H, Lq, Lk, d)
+    table = synth.head_params(H, Lk, band, seed=Lk + d)
+    rq = synth.requant_params(H, seed=Lk, shift=16, mult_lo=60, mult_hi=200)
+    check_attention(q, k, v, table, rq, band, oracle, "streaming")
+
+
+def test_attention_streaming_rescale_kinds_and_extremes(oracle):
+    """Every rescale form of the streaming kernel, full-range inputs, d = 128 (|acc| up to 2^21)."""
+    g = np.random.default_rng(12)
+    Bt, H, Lq, Lk, d = 1, 3, 24, 144, 128
+    q = g.integers(-128, 128, size=(Bt, H, Lq, d), dtype=np.int8)
+    k = g.integers(-128, 128, size=(Bt, H, Lk, d), dtype=np.int8)
+    v = g.integers(-128, 128, size=(Bt, H, Lk, d), dtype=np.int8)
+    q[0, 0, :3] = -128
+    k[0, 0, :3] = -128
+    table = np.array([[30000, 127, 127], [32767, 127, 100], [227, 1, 127]], np.int32)
+    assert binding.validate_params(table, Lk, 0) == (0, -1)
+    for rq in ([[100, 16], [7, 12], [255, 16]],          # high-half form
+               [[100, 17], [900, 20], [3, 2]],           # shift form
+               [[4096, 23], [4096, 12], [2047, 16]]):    # accumulator saturation needed
+        check_attention(q, k, v, table, np.array(rq, np.int32), 0, oracle, f"rescale {rq}")
+
+
+def test_attention_streaming_equals_resident_definition(oracle):
+    """A square shape that the resident kernel takes, pushed through the streaming kernel by
+    giving it one extra query row: the first L rows must equal the resident result."""
+    w = synth.make_workload("fused_attention", shape=(1, 2, 128, 64))
+    q1 = np.concatenate([w["q"], w["q"][:, :, :1]], axis=2)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    o_res = binding.attention_i8(dev(w["q"]), dev(w["k"]), dev(w["v"]), w["table"], w["requant"], w["band"])
+    o_str = binding.attention_i8(dev(q1), dev(w["k"]), dev(w["v"]), w["table"], w["requant"], w["band"])
+    torch.cuda.synchronize()
+    assert torch.equal(o_str[:, :, :128], o_res) and torch.equal(o_str[:, :, 128], o_res[:, :, 0])
+
+
 def test_attention_full_size(oracle):
     w = synth.make_workload("fused_attention")
     check_attention(w["q"], w["k"], w["v"], w["table"], w["requant"], w["band"], oracle, "full")
