@@ -38,6 +38,39 @@ __device__ __forceinline__ uint32_t normalise4_clb_u8(uint32_t delta4, int B, in
     return p0 | (p1 << 8) | (p2 << 16) | (p3 << 24);
 }
 
+// Stages 3-5 for one row once Z is known: the reciprocal of the row and the 16 output
+// bytes of one vector of distances (4 dwords in the 8-bit modes, 2 in the 16-bit modes).
+template <int MODE>
+struct RowOutput {
+    int B, S, D;
+    uint32_t rho;
+    RowAffine ra;
+    __device__ __forceinline__ RowOutput(uint32_t Z, int B_, int S_, int D_) : B(B_), S(S_), D(D_)
+    {
+        if constexpr (MODE == kModeU8)
+            ra = row_affine(Z, B, S, D), rho = 0;
+        else
+            rho = reciprocal_for_mode<MODE>(Z);
+    }
+    __device__ __forceinline__ u32x4 vector(const uint32_t *dl) const
+    {
+        u32x4 o;
+        if constexpr (MODE == kModeU8) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] = normalise4(dl[c], ra);
+        } else if constexpr (MODE == kModeClbU8) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] = normalise4_clb_u8(dl[c], B, S, D, rho);
+        } else {
+            uint32_t w[4];
+#pragma unroll
+            for (int c = 0; c < 2; ++c) normalise4_wide<MODE>(dl[c], B, S, D, rho, w[2 * c], w[2 * c + 1]);
+            o = (u32x4){w[0], w[1], w[2], w[3]};
+        }
+        return o;
+    }
+};
+
 // ---------------------------------------------------------------------------
 // Register-resident kernel for rows whose length is a multiple of 16.
 //
@@ -142,37 +175,97 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
         const int row = row0 + j * kRowsPerBatch;
         uint8_t *dst = out + (slab + row) * (size_t)n * kOutBytes;
 
-        if constexpr (MODE == kModeU8) {
-            const RowAffine ra = row_affine(Z, B, S, D);
+        const RowOutput<MODE> ro(Z, B, S, D);
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const int vi = v * G + sub;
-                u32x4 o;
+        for (int v = 0; v < V; ++v) {
+            const int vi = v * G + sub;
+            const u32x4 o = ro.vector(d[j][v]);
+            if (row < Lq && vi < nvec) store_stream(dst + vi * 16, o);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// One block (four waves) per row, for rows beyond a wave's registers (16384 < Lk <= 65536):
+// thread t holds vectors t, t + 256, ...; the maximum and the sum cross waves through LDS.
+// Same arithmetic and the same padding rule as the kernel above.
+// ---------------------------------------------------------------------------
+template <int V, int MODE>
+__global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__restrict__ logits,
+                                                             uint8_t *__restrict__ out, int Lq, int nvec,
+                                                             HeadTable table)
+{
+    constexpr int kOutBytes = (MODE & 1) ? 2 : 1;
+    constexpr int DW = 4 / kOutBytes;
+    constexpr int kVecBytes = DW * 4;
+    constexpr int kPaddedLen = 256 * V * kVecBytes;
+    __shared__ int red[2][4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int head = blockIdx.y;
+    const int4 hp = table.e[head];
+    const int B = hp.x, S = hp.y, D = hp.z;
+    const int n = nvec * kVecBytes;
+    const size_t row = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq + blockIdx.x;
+    const int8_t *src = logits + row * (size_t)n;
+    uint8_t *dst = out + row * (size_t)n * kOutBytes;
+
+    uint32_t d[V][DW];
 #pragma unroll
-                for (int c = 0; c < 4; ++c) o[c] = normalise4(d[j][v][c], ra);
-                if (row < Lq && vi < nvec) store_stream(dst + vi * 16, o);
-            }
-        } else if constexpr (MODE == kModeClbU8) {
-            const uint32_t rho = reciprocal_for_mode<MODE>(Z);
-#pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const int vi = v * G + sub;
-                u32x4 o;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) o[c] = normalise4_clb_u8(d[j][v][c], B, S, D, rho);
-                if (row < Lq && vi < nvec) store_stream(dst + vi * 16, o);
+    for (int v = 0; v < V; ++v) {
+        const int vi = v * 256 + tid;
+        if (vi < nvec) {
+            if constexpr (DW == 4) {
+                const u32x4 t = load_stream(src + vi * 16);
+                d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
+            } else {
+                const u32x2 t = load_stream8(src + vi * 8);
+                d[v][0] = t[0], d[v][1] = t[1];
             }
         } else {
-            const uint32_t rho = reciprocal_for_mode<MODE>(Z);
 #pragma unroll
-            for (int v = 0; v < V; ++v) {
-                const int vi = v * G + sub;
-                uint32_t w[4];
-#pragma unroll
-                for (int c = 0; c < 2; ++c) normalise4_wide<MODE>(d[j][v][c], B, S, D, rho, w[2 * c], w[2 * c + 1]);
-                if (row < Lq && vi < nvec) store_stream(dst + vi * 16, (u32x4){w[0], w[1], w[2], w[3]});
-            }
+            for (int c = 0; c < DW; ++c) d[v][c] = kPadWord;
         }
+    }
+    ByteMax bm;
+    bm.init(d[0][0]);
+#pragma unroll
+    for (int c = 1; c < DW; ++c) bm.add(d[0][c]);
+#pragma unroll
+    for (int v = 1; v < V; ++v)
+#pragma unroll
+        for (int c = 0; c < DW; ++c) bm.add(d[v][c]);
+    int m = group_max<64>(bm.result());
+    if (lane == 0) red[0][wave] = m;
+    __syncthreads();
+    m = max(max(red[0][0], red[0][1]), max(red[0][2], red[0][3]));
+    const uint32_t mu = (uint32_t)(m + 128);
+
+    const uint32_t D4 = (uint32_t)D * 0x01010101u;
+    const uint32_t neg_base4 = 0u - (uint32_t)(127 - m) * 0x01010101u;
+    uint32_t acc_d = 0, acc_abs = 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int c = 0; c < DW; ++c) {
+            const uint32_t dl = distance4(d[v][c], neg_base4);
+            d[v][c] = dl;
+            acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
+            acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
+        }
+    int t = group_sum<64>((int)acc_d - (int)acc_abs);
+    if (lane == 0) red[1][wave] = t;
+    __syncthreads();
+    t = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    const int npad = kPaddedLen - n;
+    const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu, (uint32_t)D);
+    const uint32_t Z = (uint32_t)(n * B - S * sum_clamped);
+    const RowOutput<MODE> ro(Z, B, S, D);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int vi = v * 256 + tid;
+        const u32x4 o = ro.vector(d[v]);
+        if (vi < nvec) store_stream(dst + vi * 16, o);
     }
 }
 
@@ -273,9 +366,17 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
         if (nvec <= 256) return launch_rows<64, 4, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         if (nvec <= 512) return launch_rows<64, 8, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         if (nvec <= 1024) return launch_rows<64, 16, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        return launch_rows<64, 32, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // 16-bit modes, Lk > 8192
+        return launch_rows<64, 32, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // 16-bit modes, 8192 < Lk <= 16384
     }
     dim3 grid(Lq, H, Bt);
+    if (vector_ok && Lk % 16 == 0) {   // 16384 < Lk <= 65536: one block per row, the row in the block's registers
+        const int nvec = Lk / ((MODE & 1) ? 8 : 16);
+        if (nvec <= 2048)
+            hipLaunchKernelGGL((hccs_row_block_kernel<8, MODE>), grid, dim3(256), 0, st, x, p, Lq, nvec, tab);
+        else   // at most 4096: Lk <= 65536 in the 8-bit modes, and the 16-bit modes need Lk*B <= 32767
+            hipLaunchKernelGGL((hccs_row_block_kernel<16, MODE>), grid, dim3(256), 0, st, x, p, Lq, nvec, tab);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(hccs_row_bytes_kernel<MODE>, grid, dim3(256), 0, st, x, p, Lq, Lk, tab);
     return hipGetLastError();
 }

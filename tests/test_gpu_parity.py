@@ -57,6 +57,8 @@ SHAPES = [
     # byte kernel: lengths that are not multiples of 16, or beyond the register kernel
     ((1, 2, 5, 100), 1), ((1, 2, 3, 1), 1), ((1, 1, 4, 17), 1), ((1, 1, 3, 255), 0), ((1, 1, 2, 20000), 0),
     ((1, 1, 1, 65536), 0), ((1, 2, 2, 16400), 0),
+    # one block per row: multiples of 16 beyond 16384
+    ((1, 2, 3, 32768), 0), ((2, 1, 2, 40000), 0), ((1, 1, 5, 65520), 0),
 ]
 
 
@@ -149,6 +151,7 @@ MODE_SHAPES = [
     ((2, 12, 40, 512), 1), ((1, 2, 3, 4096), 1), ((1, 1, 2, 16384), 1), ((1, 2, 7, 208), 1), ((1, 2, 6, 880), 1),
     ((1, 2, 5, 100), 1), ((1, 1, 4, 17), 1), ((1, 2, 3, 1), 1), ((1, 1, 2, 20000), 1),
     ((1, 2, 5, 1024), 0), ((1, 2, 3, 4096), 0), ((1, 1, 3, 255), 0),
+    ((1, 2, 2, 32752), 1), ((1, 1, 3, 16400), 1), ((1, 1, 2, 40000), 0),
 ]
 
 
