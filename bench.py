@@ -184,7 +184,7 @@ def main():
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": counter_traffic(),
-                "kernel": "hccs_rows_kernel<8,1,2,4>", "algorithmic_bytes_per_launch": alg_bytes,
+                "kernel": "hccs_rows_kernel<8,1,2,4,0>", "algorithmic_bytes_per_launch": alg_bytes,
                 "avg_launch_ms": round(kern_ms, 5), "median_launch_ms": round(median(ev), 5),
                 "launches_timed": replays * per if replays else tail,
                 "how": f"HIP events around each graph replay of {per} launches, divided by {per}"}

@@ -52,6 +52,20 @@ struct RowOutput {
         else
             rho = reciprocal_for_mode<MODE>(Z);
     }
+    // The same constants as held by lane J of each quad (quad_perm broadcast).
+    template <int J>
+    __device__ __forceinline__ RowOutput from_quad_lane() const
+    {
+        RowOutput r = *this;
+        if constexpr (MODE == kModeU8) {
+            r.ra.slope = __builtin_bit_cast(float, dpp<J * 0x55>(__builtin_bit_cast(int, ra.slope)));
+            r.ra.offset = __builtin_bit_cast(float, dpp<J * 0x55>(__builtin_bit_cast(int, ra.offset)));
+            r.ra.pmin4 = (uint32_t)dpp<J * 0x55>((int)ra.pmin4);
+        } else {
+            r.rho = (uint32_t)dpp<J * 0x55>((int)rho);
+        }
+        return r;
+    }
     __device__ __forceinline__ u32x4 vector(const uint32_t *dl) const
     {
         u32x4 o;
@@ -137,6 +151,9 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
     }
 
     const uint32_t D4 = (uint32_t)D * 0x01010101u;
+    const int npad = kPaddedLen - n;   // padding bytes sit at distance m+128
+    int tsum[R];                       // sum delta - sum |delta - D| of each batch's row
+    uint32_t mu[R];                    // row maximum in offset-binary form
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         // stage 1: row maximum (Alg. 1, first step)
@@ -150,7 +167,7 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
             for (int c = 0; c < DW; ++c) bm.add(d[j][v][c]);
         }
         const int m = group_max<G>(bm.result());
-        const uint32_t mu = (uint32_t)(m + 128);
+        mu[j] = (uint32_t)(m + 128);
 
         // stage 2: unclamped distances; sum of the clamped ones from two byte-SAD
         // accumulations: sum min(delta, D) = (sum delta + count*D - sum |delta - D|) / 2
@@ -166,22 +183,44 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
                 acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
             }
         }
-        const int t = group_sum<G>((int)acc_d - (int)acc_abs);
-        const int npad = kPaddedLen - n;   // padding bytes sit at distance m+128
-        const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu, (uint32_t)D);
+        tsum[j] = group_sum<G>((int)acc_d - (int)acc_abs);
+    }
 
-        // stages 3-5: Z = n*B - S*sum min(delta, D)  (Eq. (3), (5)), reciprocal, normalise
-        const uint32_t Z = (uint32_t)(n * B - S * sum_clamped);
+    // stages 3-5: Z = n*B - S*sum min(delta, D)  (Eq. (3), (5)), reciprocal, normalise.
+    // Every lane of a group holds the sums of all R rows the group works on.  With R = 2 or 4
+    // lane i of each quad takes row i % R, so the reciprocal and the row constants are computed
+    // once per R rows instead of R times, and come back through quad broadcasts.
+    auto row_output = [&](int t, uint32_t mu_) {
+        const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu_, (uint32_t)D);
+        return RowOutput<MODE>((uint32_t)(n * B - S * sum_clamped), B, S, D);
+    };
+    auto emit = [&](int j, const RowOutput<MODE> &ro) {
         const int row = row0 + j * kRowsPerBatch;
         uint8_t *dst = out + (slab + row) * (size_t)n * kOutBytes;
-
-        const RowOutput<MODE> ro(Z, B, S, D);
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             const int vi = v * G + sub;
             const u32x4 o = ro.vector(d[j][v]);
             if (row < Lq && vi < nvec) store_stream(dst + vi * 16, o);
         }
+    };
+    if constexpr (R == 2) {
+        const bool odd = lane & 1;
+        const RowOutput<MODE> mine = row_output(odd ? tsum[1] : tsum[0], odd ? mu[1] : mu[0]);
+        emit(0, mine.template from_quad_lane<0>());
+        emit(1, mine.template from_quad_lane<1>());
+    } else if constexpr (R == 4) {
+        const int w = lane & 3;
+        const int t = w == 0 ? tsum[0] : (w == 1 ? tsum[1] : (w == 2 ? tsum[2] : tsum[3]));
+        const uint32_t u = w == 0 ? mu[0] : (w == 1 ? mu[1] : (w == 2 ? mu[2] : mu[3]));
+        const RowOutput<MODE> mine = row_output(t, u);
+        emit(0, mine.template from_quad_lane<0>());
+        emit(1, mine.template from_quad_lane<1>());
+        emit(2, mine.template from_quad_lane<2>());
+        emit(3, mine.template from_quad_lane<3>());
+    } else {
+#pragma unroll
+        for (int j = 0; j < R; ++j) emit(j, row_output(tsum[j], mu[j]));
     }
 }
 
