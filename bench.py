@@ -212,9 +212,13 @@ def main():
         c1 = time.perf_counter()
         assert rc == 0
         same = bool(np.array_equal(outs[0].cpu().numpy(), want))
+        s0 = time.perf_counter()
+        oracle.softmax(x_host[:16], table, band, threads=1)            # 1/16 of the batch on one thread
+        s1 = time.perf_counter()
         result["cpu_baseline"] = {"value": round(rows / (c1 - c0), 1), "unit": "rows/s", "cores": ncpu,
                                   "kind": "oracle",
                                   "sample": f"the whole {name} batch once ({rows} rows, {c1 - c0:.2f} s)",
+                                  "single_thread_rows_per_s": round(rows / 16 / (s1 - s0), 1),
                                   "gpu_output_equals_oracle": same}
 
     if not args.no_extras:
