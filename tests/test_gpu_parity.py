@@ -109,6 +109,27 @@ def test_softmax_in_place_and_unaligned(oracle):
     assert int(buf_out[:3].sum()) == 0 and int(buf_out[3 + x.size:].sum()) == 0
 
 
+def test_empty_tensors_and_size_limits(oracle):
+    """Zero-sized tensors are a no-op; the largest head table (64) and the largest batch extent
+    (65535, the grid's z limit) go through; one more is rejected before any launch."""
+    for shape in [(0, 4, 8, 64), (3, 4, 0, 64)]:
+        x = torch.empty(shape, dtype=torch.int8, device="cuda")
+        out = binding.calibrated_softmax_i8(x, synth.head_params(4, 64, 1, seed=1), 1)
+        torch.cuda.synchronize()
+        assert out.shape == x.shape
+    table = synth.head_params(64, 32, 1, seed=64)
+    check(mixed_logits((2, 64, 3, 32), 64), table, 1, oracle, "64 heads")
+    table = synth.head_params(1, 16, 1, seed=2)
+    check(mixed_logits((65535, 1, 1, 16), 65535), table, 1, oracle, "65535 batches")
+    with pytest.raises(binding.HccsError) as e:
+        binding.calibrated_softmax_i8(torch.zeros((65536, 1, 1, 16), dtype=torch.int8, device="cuda"), table, 1)
+    assert e.value.status == -2
+    q = torch.empty((0, 2, 64, 64), dtype=torch.int8, device="cuda")
+    o = binding.attention_i8(q, q, q, synth.head_params(2, 64, 1, seed=1), synth.requant_params(2, seed=1), 1)
+    torch.cuda.synchronize()
+    assert o.shape == q.shape
+
+
 def test_rejected_call_leaves_output_untouched():
     x = torch.zeros((1, 1, 4, 64), dtype=torch.int8, device="cuda")
     out = torch.full((1, 1, 4, 64), 77, dtype=torch.uint8, device="cuda")
