@@ -132,7 +132,7 @@ HCCS_API int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const i
 
 /* The same block with separate query and key lengths:
  *   q_dev [B,H,Lq,d], k_dev and v_dev [B,H,Lk,d] int8, o_dev [B,H,Lq,d] int32, all 16-byte aligned.
- *   d = 64 or 128; Lk a multiple of 16, 16 <= Lk <= HCCS_MAX_ROW_LENGTH; Lq >= 0 (0 is a no-op);
+ *   d = 64 or 128; 1 <= Lk <= HCCS_MAX_ROW_LENGTH; Lq >= 0 (0 is a no-op);
  *   B*H <= 65535.  The row length of HCCS, and of the band check, is n = Lk.
  * Square blocks with d = 64 and Lk a multiple of 64 up to 512 keep a query tile's logits in
  * registers and K, V in LDS; every other shape streams K and V in chunks of 64 keys and

@@ -113,7 +113,7 @@ int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t 
 {
     if (!table_host || !requant_host) return HCCS_E_NULL;
     if (B < 0 || H < 1 || H > HCCS_MAX_HEADS || (int64_t)B * H > 65535) return HCCS_E_SHAPE;
-    if ((d != 64 && d != 128) || Lq < 0 || Lk < 16 || Lk > HCCS_MAX_ROW_LENGTH || Lk % 16 != 0) return HCCS_E_SHAPE;
+    if ((d != 64 && d != 128) || Lq < 0 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH) return HCCS_E_SHAPE;
     if (out_scale_T != 255) return HCCS_E_SCALE;
     const int rc = hccs_validate_params(table_host, H, Lk, band, nullptr);
     if (rc != HCCS_OK) return rc;

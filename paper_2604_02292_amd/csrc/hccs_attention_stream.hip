@@ -1,5 +1,5 @@
 // Fused int8 attention block for shapes the resident kernel does not take: any number of
-// queries, any key length that is a multiple of 16, head size 64 or 128.  K and V stream
+// queries, any key length, head size 64 or 128.  K and V stream
 // through LDS in chunks of 64 keys, so neither the logits of a row nor K and V have to fit
 // anywhere.  HCCS needs the row maximum before the clamped sum and the sum before the first
 // output, and its floors rule out rescaling partial results, so Q.K^T is recomputed three
@@ -92,6 +92,17 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
         }
     };
 
+    // 16-bit lane masks of the keys key0 + 4g + {0,1} and {2,3} that exist (all ones except in
+    // the last, partial tile)
+    auto pair_masks = [&](int key0, uint32_t &m01, uint32_t &m23) {
+        const int kbase = key0 + 4 * g;
+        m01 = (kbase < Lk ? 0x0000ffffu : 0u) | (kbase + 1 < Lk ? 0xffff0000u : 0u);
+        m23 = (kbase + 2 < Lk ? 0x0000ffffu : 0u) | (kbase + 3 < Lk ? 0xffff0000u : 0u);
+    };
+    auto masked = [](short2_t p, uint32_t mask, uint32_t fill) {
+        return __builtin_bit_cast(short2_t, (__builtin_bit_cast(uint32_t, p) & mask) | (fill & ~mask));
+    };
+
     // logits of key tile tt of the chunk in `buf`, as two 16-bit pairs
     auto tile_logits = [&](int buf, int tt, short2_t &p01, short2_t &p23) {
         v4i acc = {0, 0, 0, 0};
@@ -118,6 +129,12 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
                 if (c * 64 + 16 * tt < Lk) {
                     short2_t p01, p23;
                     tile_logits(c & 1, tt, p01, p23);
+                    if (c * 64 + 16 * tt + 16 > Lk) {      // partial tile: missing keys cannot win the maximum
+                        uint32_t m01, m23;
+                        pair_masks(c * 64 + 16 * tt, m01, m23);
+                        p01 = masked(p01, m01, 0x80008000u);
+                        p23 = masked(p23, m23, 0x80008000u);
+                    }
                     mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(p01, p23));
                 }
         }
@@ -145,8 +162,16 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
                 if (c * 64 + 16 * tt < Lk) {
                     short2_t p01, p23;
                     tile_logits(c & 1, tt, p01, p23);
-                    sum2 += __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
-                    sum2 += __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
+                    short2_t x01 = __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
+                    short2_t x23 = __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
+                    if (c * 64 + 16 * tt + 16 > Lk) {      // missing keys add nothing to the sum
+                        uint32_t m01, m23;
+                        pair_masks(c * 64 + 16 * tt, m01, m23);
+                        x01 = masked(x01, m01, 0u);
+                        x23 = masked(x23, m23, 0u);
+                    }
+                    sum2 += x01;
+                    sum2 += x23;
                 }
             sx += (int)sum2.x + (int)sum2.y;     // at most 8 values of magnitude <= 128 per half and chunk
         }
@@ -183,8 +208,14 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
                     tile_logits(c & 1, tt, p01, p23);
                     const short2_t x01 = __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
                     const short2_t x23 = __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
-                    const uint32_t s01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x01) * s2 + c2);
-                    const uint32_t s23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x23) * s2 + c2);
+                    uint32_t s01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x01) * s2 + c2);
+                    uint32_t s23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x23) * s2 + c2);
+                    if (c * 64 + 16 * tt + 16 > Lk) {      // a zero score gives P = 0
+                        uint32_t m01, m23;
+                        pair_masks(c * 64 + 16 * tt, m01, m23);
+                        s01 &= m01;
+                        s23 &= m23;
+                    }
                     pop[tt] = (int)probabilities_minus_128(s01, s23, rho2);
                 }
             }

@@ -133,7 +133,7 @@ def test_attention_rejections_launch_nothing(lib):
         return lib.hccs_attention_i8(vp(q), vp(k), vp(v), vp(o), B, H, L, d, tab, rq_, T, band, None)
 
     assert call(q=0) == -1
-    assert call(d=32) == -2 and call(L=100) == -2 and call(L=8) == -2 and call(H=0) == -2
+    assert call(d=32) == -2 and call(L=0) == -2 and call(L=70000) == -2 and call(H=0) == -2
     assert call(L=1024) == -7                         # a valid shape now; this table is outside the band at n = 1024
     assert call(q=4100) == -3
     assert call(T=32767) == -4
@@ -146,7 +146,7 @@ def test_attention_rejections_launch_nothing(lib):
     def call_ex(q=4096, k=8192, v=12288, o=16384, B=1, H=1, Lq=40, Lk=256, d=64, band=1):
         return lib.hccs_attention_i8_ex(vp(q), vp(k), vp(v), vp(o), B, H, Lq, Lk, d, arr, rq, 255, band, None)
 
-    assert call_ex(Lk=250) == -2 and call_ex(d=96) == -2 and call_ex(Lq=-1) == -2 and call_ex(B=70000) == -2
+    assert call_ex(Lk=0) == -2 and call_ex(d=96) == -2 and call_ex(Lq=-1) == -2 and call_ex(B=70000) == -2
     assert call_ex(Lq=0, q=0, o=0) == 0               # no queries: nothing to do
     assert call_ex(k=0) == -1 and call_ex(o=16388) == -3
     assert call_ex(Lk=512) == -7                      # band is checked with n = Lk
