@@ -23,6 +23,14 @@ __device__ __forceinline__ uint32_t mad_u32_u16_hi(uint32_t a, uint32_t b, uint3
     return d;
 }
 
+// Two signed 16-bit values -> two unsigned bytes, saturated to [0,255], in the low half.
+__device__ __forceinline__ uint32_t sat_pk_u8_i16(uint32_t v)
+{
+    uint32_t d;
+    asm("v_sat_pk_u8_i16 %0, %1" : "=v"(d) : "v"(v));
+    return d;
+}
+
 constexpr int kKStride = 80;   // bytes per K row in LDS: 64 + 16 of padding against bank conflicts
 
 // How the int32 accumulator becomes a 16-bit logit (before the int8 saturation):
@@ -54,6 +62,18 @@ __device__ __forceinline__ void rescale_tile(const v4i &acc, int mult, int shift
         p01 = __builtin_amdgcn_cvt_pk_i16(y[0] >> shift, y[1] >> shift);   // saturating 32 -> 16
         p23 = __builtin_amdgcn_cvt_pk_i16(y[2] >> shift, y[3] >> shift);
     }
+}
+
+// 16-bit lane masks of the keys kbase + {0,1} and kbase + {2,3} that exist (key < Lk): all ones
+// except in the last, partial key tile.
+__device__ __forceinline__ void key_pair_masks(int kbase, int Lk, uint32_t &m01, uint32_t &m23)
+{
+    m01 = (kbase < Lk ? 0x0000ffffu : 0u) | (kbase + 1 < Lk ? 0xffff0000u : 0u);
+    m23 = (kbase + 2 < Lk ? 0x0000ffffu : 0u) | (kbase + 3 < Lk ? 0xffff0000u : 0u);
+}
+__device__ __forceinline__ short2_t mask_pair(short2_t p, uint32_t mask, uint32_t fill)
+{
+    return __builtin_bit_cast(short2_t, (__builtin_bit_cast(uint32_t, p) & mask) | (fill & ~mask));
 }
 
 // Four scores (two 16-bit pairs) -> four bytes P - 128: byte 2 of s*(2*rho) + 0x800000 is

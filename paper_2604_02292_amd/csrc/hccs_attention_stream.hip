@@ -92,16 +92,8 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
         }
     };
 
-    // 16-bit lane masks of the keys key0 + 4g + {0,1} and {2,3} that exist (all ones except in
-    // the last, partial tile)
-    auto pair_masks = [&](int key0, uint32_t &m01, uint32_t &m23) {
-        const int kbase = key0 + 4 * g;
-        m01 = (kbase < Lk ? 0x0000ffffu : 0u) | (kbase + 1 < Lk ? 0xffff0000u : 0u);
-        m23 = (kbase + 2 < Lk ? 0x0000ffffu : 0u) | (kbase + 3 < Lk ? 0xffff0000u : 0u);
-    };
-    auto masked = [](short2_t p, uint32_t mask, uint32_t fill) {
-        return __builtin_bit_cast(short2_t, (__builtin_bit_cast(uint32_t, p) & mask) | (fill & ~mask));
-    };
+    auto pair_masks = [&](int key0, uint32_t &m01, uint32_t &m23) { key_pair_masks(key0 + 4 * g, Lk, m01, m23); };
+    auto masked = [](short2_t p, uint32_t mask, uint32_t fill) { return mask_pair(p, mask, fill); };
 
     // logits of key tile tt of the chunk in `buf`, as two 16-bit pairs
     auto tile_logits = [&](int buf, int tt, short2_t &p01, short2_t &p23) {
@@ -248,6 +240,226 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     }
 }
 
+// ---------------------------------------------------------------------------
+// Two-pass form for key lengths up to 64*NCMAX: the logits of a query tile are kept in
+// registers as offset-binary bytes (u = x + 128, four keys per register), so Q.K^T is computed
+// once.  Pass 1 streams K and fills the bytes; the HCCS stage then runs on them with the
+// byte-parallel steps of the stand-alone kernel (distances by one subtraction per four keys,
+// the clamped sum from two byte-SADs, one exact fma and a saturating pack per probability);
+// pass 2 streams V for O = P.V.  Key slots that do not exist hold u = 0: that is the identity
+// of the maximum, their distance to it is m + 128 -- a known amount taken out of the sum -- and
+// their V rows are staged as zero, so whatever P they get multiplies nothing.
+// ---------------------------------------------------------------------------
+template <int NCMAX, int ND, int RQ>
+__global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_stream2_kernel(
+    const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v,
+    int32_t *__restrict__ o, int H, int Lq, int Lk, HeadTable table, RequantTable requant)
+{
+    constexpr int DH = 64 * ND;
+    constexpr int KSTR = DH + 16;
+    constexpr int KPARTS = DH / 16;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][64 * KSTR];   // pass 1: K chunks; pass 2: V chunks
+    __shared__ __attribute__((aligned(16))) int32_t lds_colsum[DH];
+    static_assert(64 * KSTR >= 64 * DH, "the V chunk reuses the K buffers");
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qi = lane & 15, g = lane >> 4;
+    const int item = blockIdx.y;
+    const int head = item % H;
+    const int4 hp = table.e[head];
+    const int B = hp.x, S = hp.y, D = hp.z;
+    const int mult = requant.e[head].x, shift = requant.e[head].y;
+    const int round_c = 1 << (shift - 1);
+    const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 21);
+    const int8_t *kb = k + (size_t)item * Lk * DH;
+    const int8_t *vb = v + (size_t)item * Lk * DH;
+    const int tile = blockIdx.x * 4 + wave;
+    const bool active = tile * 16 < Lq;
+    const int nchunks = (Lk + 63) / 64;
+
+    for (int c = tid; c < DH; c += 256) lds_colsum[c] = 0;
+
+    v4i qop[ND];
+    {
+        const int row = min(tile * 16 + qi, Lq - 1);
+#pragma unroll
+        for (int kd = 0; kd < ND; ++kd)
+            qop[kd] = *(const v4i *)(q + ((size_t)item * Lq + row) * DH + 64 * kd + 16 * g);
+    }
+
+    u32x4 kreg[ND];
+    uint32_t vreg[ND][4];
+    auto load_k = [&](int chunk) {
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            const int c = tid + i * 256;
+            const int key = chunk * 64 + c / KPARTS;
+            kreg[i] = key < Lk ? *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16) : (u32x4){0, 0, 0, 0};
+        }
+    };
+    auto store_k = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            const int c = tid + i * 256;
+            *(u32x4 *)(lds_k[buf] + (c / KPARTS) * KSTR + (c % KPARTS) * 16) = kreg[i];
+        }
+    };
+    auto load_v = [&](int chunk) {
+        const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
+#pragma unroll
+        for (int i = 0; i < ND; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int kk = chunk * 64 + 16 * tt + 4 * gg + r;
+                vreg[i][r] = kk < Lk ? *(const uint32_t *)(vb + (size_t)kk * DH + 64 * i + 4 * nn) : 0u;
+            }
+    };
+    auto store_v = [&](int buf) {
+        const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            uint32_t w[4];
+            transpose4x4(vreg[i], w);
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                *(uint32_t *)(lds_k[buf] + (((i * 4 + dt) * 4 + gg) * 16 + nn) * 16 + tt * 4) = w[dt];
+                atomicAdd(&lds_colsum[64 * i + 4 * nn + dt], __builtin_amdgcn_sdot4((int)w[dt], 0x01010101, 0, false));
+            }
+        }
+    };
+
+    // ---- pass 1: logits as offset-binary bytes, running maximum --------------------------------
+    uint32_t xb[NCMAX * 4];
+#pragma unroll
+    for (int i = 0; i < NCMAX * 4; ++i) xb[i] = 0;
+    short2_t mx2 = {-32768, -32768};
+    load_k(0);
+    store_k(0);
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < NCMAX; ++c) {
+        if (c < nchunks) {
+            if (c + 1 < nchunks) load_k(c + 1);
+            if (active) {
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt)
+                    if (c * 64 + 16 * tt < Lk) {
+                        v4i acc = {0, 0, 0, 0};
+#pragma unroll
+                        for (int kd = 0; kd < ND; ++kd) {
+                            const v4i kop = *(const v4i *)(lds_k[c & 1] + (16 * tt + qi) * KSTR + 64 * kd + 16 * g);
+                            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop[kd], acc, 0, 0, 0);
+                        }
+                        short2_t p01, p23;
+                        rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
+                        if (c * 64 + 16 * tt + 16 > Lk) {
+                            // partial tile: key slots that do not exist get the lowest 16-bit value, so they
+                            // cannot win the maximum and saturate to u = 0 below
+                            uint32_t m01, m23;
+                            key_pair_masks(c * 64 + 16 * tt + 4 * g, Lk, m01, m23);
+                            p01 = mask_pair(p01, m01, 0x80008000u);
+                            p23 = mask_pair(p23, m23, 0x80008000u);
+                        }
+                        mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(p01, p23));
+                        const short2_t c128 = {128, 128};
+                        const uint32_t lo8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(p01, c128)));
+                        const uint32_t hi8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(p23, c128)));
+                        xb[c * 4 + tt] = __builtin_amdgcn_perm(hi8, lo8, 0x05040100u);
+                    }
+            }
+            if (c + 1 < nchunks) store_k((c + 1) & 1);
+            __syncthreads();
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the unrolled chunks in order: registers, not latency, are scarce
+    }
+    int mx = max((int)mx2.x, (int)mx2.y);
+    mx = max(mx, xor16(mx));
+    mx = max(mx, xor32(mx));
+    const uint32_t mu = (uint32_t)(clamp_i32(mx, -128, 127) + 128);   // saturation is monotone
+
+    // ---- HCCS on the bytes: distances, clamped sum, row constants -------------------------------
+    const uint32_t mu4 = mu * 0x01010101u, D4 = (uint32_t)D * 0x01010101u;
+    uint32_t acc_d = 0, acc_abs = 0;
+#pragma unroll
+    for (int i = 0; i < NCMAX * 4; ++i) {
+        const uint32_t dl = mu4 - xb[i];       // every byte is <= mu: no borrow
+        xb[i] = dl;
+        acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
+        acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
+    }
+    int tsum = (int)acc_d - (int)acc_abs;
+    tsum += xor16(tsum);
+    tsum += xor32(tsum);
+    constexpr int kSlots = NCMAX * 64;
+    const int sum_clamped = (tsum + kSlots * D) / 2 - (kSlots - Lk) * (int)min(mu, (uint32_t)D);
+    const uint32_t Z = active ? (uint32_t)(Lk * B - S * sum_clamped) : 256u;
+    const RowAffine ra = row_affine(Z, B, S, D);
+
+    // ---- pass 2: O = P.V -----------------------------------------------------------------------
+    v4i oacc[ND][4];
+#pragma unroll
+    for (int cg = 0; cg < ND; ++cg)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) oacc[cg][dt] = (v4i){0, 0, 0, 0};
+    load_v(0);
+    store_v(0);
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < NCMAX; ++c) {
+        if (c < nchunks) {
+            if (c + 1 < nchunks) load_v(c + 1);
+            if (active) {
+                v4i pop;
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(xb[c * 4 + tt], ra) ^ 0x80808080u);
+#pragma unroll
+                for (int cg = 0; cg < ND; ++cg)
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt) {
+                        const v4i vop = *(const v4i *)(lds_k[c & 1] + (((cg * 4 + dt) * 4 + g) * 16 + qi) * 16);
+                        oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[cg][dt], 0, 0, 0);
+                    }
+            }
+            if (c + 1 < nchunks) store_v((c + 1) & 1);
+            __syncthreads();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+
+    if (active) {
+#pragma unroll
+        for (int cg = 0; cg < ND; ++cg) {
+            const v4i cs = *(const v4i *)(lds_colsum + 64 * cg + 4 * qi);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = tile * 16 + 4 * g + r;
+                const v4i out = {oacc[cg][0][r] + 128 * cs[0], oacc[cg][1][r] + 128 * cs[1],
+                                 oacc[cg][2][r] + 128 * cs[2], oacc[cg][3][r] + 128 * cs[3]};
+                if (row < Lq)
+                    __builtin_nontemporal_store(out, (v4i *)(o + ((size_t)item * Lq + row) * DH + 64 * cg + 4 * qi));
+            }
+        }
+    }
+}
+
+template <int NCMAX, int ND>
+static hipError_t launch_stream2(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int items, int H,
+                                 int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
+                                 hipStream_t st)
+{
+    const dim3 grid((Lq + 63) / 64, items), block(256);
+    if (kind == kRescaleHigh16)
+        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16>), grid, block, 0, st, q, k, v, o,
+                           H, Lq, Lk, tab, rq);
+    else if (kind == kRescaleShift)
+        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift>), grid, block, 0, st, q, k, v, o,
+                           H, Lq, Lk, tab, rq);
+    else
+        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp>), grid, block, 0, st, q, k, v,
+                           o, H, Lq, Lk, tab, rq);
+    return hipGetLastError();
+}
+
 template <int ND>
 static hipError_t launch_stream_nd(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int items, int H,
                                    int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
@@ -272,9 +484,17 @@ hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_
 {
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)d << 14, rq);   // |acc| <= d*128*128
-    if (d == 64) return launch_stream_nd<1>(q, k, v, o, Bt * H, H, Lq, Lk, tab, rq, kind, st);
-    if (d == 128) return launch_stream_nd<2>(q, k, v, o, Bt * H, H, Lq, Lk, tab, rq, kind, st);
-    return hipErrorInvalidValue;
+    const int items = Bt * H;
+    if (d != 64 && d != 128) return hipErrorInvalidValue;
+    // up to 2048 keys a query tile's logits fit its registers as bytes: Q.K^T once, two passes
+    if (Lk <= 1024)
+        return d == 64 ? launch_stream2<16, 1>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                       : launch_stream2<16, 2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    if (Lk <= 2048)
+        return d == 64 ? launch_stream2<32, 1>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                       : launch_stream2<32, 2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    return d == 64 ? launch_stream_nd<1>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                   : launch_stream_nd<2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
 }
 
 }  // namespace hccs
