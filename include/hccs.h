@@ -174,6 +174,13 @@ HCCS_API int hccs_exp_softmax_i8_f32(const int8_t *logits_dev, uint8_t *probs_de
  * the exhaustive check of Eq. (8) reach the GPU code. */
 HCCS_API int hccs_reciprocal_u8(const uint32_t *z_dev, uint32_t *rho_dev, int64_t count, void *hip_stream);
 
+/* Test hook: the kernels' normalise stage alone.  bsdz_dev: count quadruples (B, S, Dmax, Z) of
+ * int32 on the device (16-byte aligned), each with 0 <= S*Dmax <= B <= Z and 256 <= Z <= 255*2^15,
+ * which is what a row under either band produces.  out_dev: count*256 bytes, entry i holding
+ * ((B - S*min(delta, Dmax)) * floor(255*2^15 / Z)) >> 15 for delta = 0..255.  Lets a sweep over the
+ * constants reach the exact-float arithmetic of the 8-bit path directly. */
+HCCS_API int hccs_normalise_table_u8(const int32_t *bsdz_dev, uint8_t *out_dev, int64_t count, void *hip_stream);
+
 /* Plain device-to-device copy kernel (uint4 per lane), used to scale hardware
  * byte counters and as the streaming reference point in benchmarks.
  * bytes must be a multiple of 16; pointers 16-byte aligned. */

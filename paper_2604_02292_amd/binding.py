@@ -17,7 +17,7 @@ RECIP_EXACT, RECIP_CLB = 0, 1
 
 EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_calibrated_softmax_i8_ex", "hccs_attention_i8", "hccs_attention_i8_ex",
            "hccs_calibrate_workspace_bytes", "hccs_calibrate_grid",
-           "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_copy_bytes", "hccs_status_string"]
+           "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_normalise_table_u8", "hccs_copy_bytes", "hccs_status_string"]
 
 
 class HccsError(RuntimeError):
@@ -61,6 +61,7 @@ def lib():
         L.hccs_exp_softmax_i8_f32.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_float), vp]
         L.hccs_reciprocal_u8.argtypes = [vp, vp, i64, vp]
         L.hccs_copy_bytes.argtypes = [vp, vp, i64, vp]
+        L.hccs_normalise_table_u8.argtypes = [vp, vp, i64, vp]
         L.hccs_status_string.argtypes = [i32]
         L.hccs_status_string.restype = ctypes.c_char_p
         for name in EXPORTS[:-1]:
@@ -262,6 +263,16 @@ def reciprocal_u8(z, out=None, stream=None):
         out = torch.empty_like(z)
     _check(lib().hccs_reciprocal_u8(ctypes.c_void_p(z.data_ptr()), ctypes.c_void_p(out.data_ptr()),
                                     z.numel(), _stream_handle(stream)))
+    return out
+
+
+def normalise_table_u8(bsdz, stream=None):
+    """bsdz: int32 CUDA tensor [count,4] of (B, S, Dmax, Z).  Returns uint8 [count,256]: p(delta)."""
+    import torch
+    assert bsdz.is_cuda and bsdz.dtype == torch.int32 and bsdz.is_contiguous() and bsdz.shape[1] == 4
+    out = torch.empty((bsdz.shape[0], 256), dtype=torch.uint8, device=bsdz.device)
+    _check(lib().hccs_normalise_table_u8(ctypes.c_void_p(bsdz.data_ptr()), ctypes.c_void_p(out.data_ptr()),
+                                         bsdz.shape[0], _stream_handle(stream)))
     return out
 
 

@@ -9,6 +9,7 @@ hipError_t launch_softmax(const int8_t *x, void *out, int Bt, int H, int Lq, int
                           int mode, bool vector_ok, hipStream_t st);
 hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hipStream_t st);
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
+hipError_t launch_normalise_table(const int32_t *bsdz, uint8_t *out, int64_t count, hipStream_t st);
 hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
                             int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st);
 hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H,
@@ -194,6 +195,16 @@ int hccs_reciprocal_u8(const uint32_t *z_dev, uint32_t *rho_dev, int64_t count, 
     if (count == 0) return HCCS_OK;
     if (!z_dev || !rho_dev) return HCCS_E_NULL;
     const hipError_t e = hccs::launch_reciprocal(z_dev, rho_dev, count, (hipStream_t)hip_stream);
+    return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
+}
+
+int hccs_normalise_table_u8(const int32_t *bsdz_dev, uint8_t *out_dev, int64_t count, void *hip_stream)
+{
+    if (count < 0 || count > 0x7fffffff) return HCCS_E_SHAPE;
+    if (count == 0) return HCCS_OK;
+    if (!bsdz_dev || !out_dev) return HCCS_E_NULL;
+    if (!aligned16(bsdz_dev) || ((uintptr_t)out_dev & 3u)) return HCCS_E_ALIGN;
+    const hipError_t e = hccs::launch_normalise_table(bsdz_dev, out_dev, count, (hipStream_t)hip_stream);
     return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
 }
 

@@ -359,6 +359,20 @@ __global__ void reciprocal_kernel(const uint32_t *z, uint32_t *rho, int64_t coun
     if (i < count) rho[i] = reciprocal_u8(z[i]);
 }
 
+// Test hook: the normalise stage alone.  Entry i has constants (B, S, Dmax) and a row sum Z; the
+// 256 output bytes are p(delta) for delta = 0..255 through the same row_affine / normalise4 path
+// as the row kernel.
+__global__ __launch_bounds__(64) void normalise_table_kernel(const int4 *__restrict__ bsdz, uint32_t *__restrict__ out,
+                                                             int64_t count)
+{
+    const int64_t i = blockIdx.x;
+    if (i >= count) return;
+    const int4 e = bsdz[i];
+    const RowAffine ra = row_affine((uint32_t)e.w, e.x, e.y, e.z);
+    const uint32_t d0 = threadIdx.x * 4u;
+    out[i * 64 + threadIdx.x] = normalise4(d0 | ((d0 + 1) << 8) | ((d0 + 2) << 16) | ((d0 + 3) << 24), ra);
+}
+
 __global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
                                                    int64_t count)
 {
@@ -439,6 +453,14 @@ hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hi
     if (count == 0) return hipSuccess;
     hipLaunchKernelGGL(reciprocal_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, z, rho,
                        count);
+    return hipGetLastError();
+}
+
+hipError_t launch_normalise_table(const int32_t *bsdz, uint8_t *out, int64_t count, hipStream_t st)
+{
+    if (count == 0) return hipSuccess;
+    hipLaunchKernelGGL(normalise_table_kernel, dim3((unsigned)count), dim3(64), 0, st, (const int4 *)bsdz,
+                       (uint32_t *)out, count);
     return hipGetLastError();
 }
 

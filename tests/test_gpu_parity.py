@@ -151,6 +151,39 @@ def test_reciprocal_exhaustive(oracle):
     assert np.array_equal(got.cpu().numpy().astype(np.int64), want)
 
 
+def test_normalise_stage_sweep(oracle):
+    """The exact-float normalise stage against integers, over constants and row sums that random rows
+    rarely produce: Z = B (one element carries everything), Z at the ends of its range, reciprocals
+    next to powers of two, and 300k random admissible combinations."""
+    N = 255 << 15
+    g = np.random.default_rng(42)
+    count = 300_000
+    B = g.integers(1, 32768, count)
+    D = g.integers(0, 128, count)
+    S = np.minimum(g.integers(0, 128, count), B // np.maximum(D, 1))
+    Z = (np.maximum(B, 256) + (g.random(count) ** 3 * (N - np.maximum(B, 256)))).astype(np.int64)
+    edge = []
+    for b in (1, 2, 255, 256, 257, 4095, 16383, 32767):
+        for s_, d_ in ((0, 0), (1, min(b, 127)), (min(127, b // 127), 127), (min(b, 127), 1)):
+            for z in {max(b, 256), max(b, 256) + 1, 32767, 32768, 65535, 65536, N - 1, N, 8355, 261120, 522241}:
+                if z >= max(b, 256) and s_ * d_ <= b:
+                    edge.append((b, s_, d_, z))
+    edge = np.array(edge, np.int64)
+    B, S, D, Z = (np.concatenate([a, edge[:, i]]) for i, a in enumerate((B, S, D, Z)))
+    assert np.all(S * D <= B) and np.all(B <= Z) and np.all(Z >= 256) and np.all(Z <= N)
+    rho, rc = oracle.reciprocal_u8(Z)
+    assert rc == 0
+    delta = np.arange(256, dtype=np.int64)[None, :]
+    want = ((B[:, None] - S[:, None] * np.minimum(delta, D[:, None])) * rho[:, None]) >> 15
+    assert want.min() >= 0 and want.max() <= 255
+    bsdz = torch.from_numpy(np.stack([B, S, D, Z], 1).astype(np.int32)).cuda()
+    got = binding.normalise_table_u8(bsdz)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy().astype(np.int64)
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"{bad.shape[0]} mismatches, first (B,S,D,Z)={B[bad[0,0]],S[bad[0,0]],D[bad[0,0]],Z[bad[0,0]]} delta={bad[0,1]}"
+
+
 def test_other_stream(oracle):
     shape = (2, 8, 64, 128)
     x = mixed_logits(shape, 9)

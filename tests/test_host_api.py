@@ -175,6 +175,9 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.hccs_reciprocal_u8(vp(0), vp(0), 5, None) == -1
     assert lib.hccs_reciprocal_u8(vp(0), vp(0), -1, None) == -2
     assert lib.hccs_reciprocal_u8(vp(0), vp(0), 0, None) == 0
+    assert lib.hccs_normalise_table_u8(vp(0), vp(0), 3, None) == -1
+    assert lib.hccs_normalise_table_u8(vp(4100), vp(8192), 3, None) == -3
+    assert lib.hccs_normalise_table_u8(vp(4096), vp(8192), -1, None) == -2
     assert lib.hccs_copy_bytes(vp(4096), vp(8192), 17, None) == -2
     assert lib.hccs_copy_bytes(vp(4097), vp(8192), 16, None) == -3
     sc = (ctypes.c_float * 1)(0.1)
