@@ -309,6 +309,125 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
 }
 
 // ---------------------------------------------------------------------------
+// Rows of any length (8-bit modes, 16-byte aligned tensors): row r starts at byte r*n, which
+// is 16-byte aligned only when n is a multiple of 16.  A lane group loads the ALIGNED vectors
+// that cover the row; bytes of the first and last vector that belong to the neighbouring rows
+// are overwritten with -128 before use, i.e. they become padding (identity of the maximum,
+// known distance, taken out of the sum like every other pad).  Interior vectors are stored
+// whole; the two boundary vectors of a row are stored byte by byte, so neighbouring rows, which
+// share those 16-byte lines, never write each other's bytes.  Input and output rows have the
+// same byte offsets, so one set of masks serves both.
+// ---------------------------------------------------------------------------
+template <int G, int V, int MODE>
+__global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__restrict__ logits,
+                                                               uint8_t *__restrict__ out, int Lq, int n,
+                                                               size_t total, HeadTable table)
+{
+    static_assert((MODE & 1) == 0, "8-bit modes only");
+    constexpr int kRowsPerWave = 64 / G;
+    constexpr int kPaddedLen = G * V * 16;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane % G, grp = lane / G;
+    const int head = blockIdx.y;
+    const int4 hp = table.e[head];
+    const int B = hp.x, S = hp.y, D = hp.z;
+    const int q = ((int)blockIdx.x * 4 + wave) * kRowsPerWave + grp;
+    const bool live = q < Lq;
+    const size_t row = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq + (live ? q : 0);
+    const size_t begin = row * (size_t)n;                 // first byte of the row in the tensor
+    const size_t base = begin & ~(size_t)15;              // aligned start of the covering vectors
+    const int lo = (int)(begin - base), hi = lo + n;      // the row is bytes [lo, hi) relative to base
+    const int nspan = (hi + 15) >> 4;                     // vectors that touch the row
+
+    // valid-byte mask of dword c of vector vi: bytes whose offset k = 16*vi + 4*c + b lies in [lo, hi)
+    auto dword_mask = [&](int k0) -> uint32_t {
+        const int nlow = min(max(lo - k0, 0), 4), nhigh = min(max(k0 + 4 - hi, 0), 4);
+        const uint32_t mlow = nlow >= 4 ? 0u : (0xffffffffu << (8 * nlow));
+        const uint32_t mhigh = nhigh >= 4 ? 0u : (0xffffffffu >> (8 * nhigh));
+        return mlow & mhigh;
+    };
+
+    uint32_t d[V][4];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int vi = v * G + sub;
+        if (live && vi < nspan) {
+            const size_t at = base + (size_t)vi * 16;
+            if (at + 16 <= total) {
+                const u32x4 t = load_stream(logits + at);
+                d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
+            } else {                                      // the tensor ends inside this vector: no read past it
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const size_t k = at + 4 * c + b;
+                        w |= (uint32_t)(k < total ? (uint8_t)logits[k] : 0x80u) << (8 * b);
+                    }
+                    d[v][c] = w;
+                }
+            }
+            if (vi == 0 || vi == nspan - 1) {             // boundary vectors: foreign bytes become padding
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t mk = dword_mask(16 * vi + 4 * c);
+                    d[v][c] = (d[v][c] & mk) | (kPadWord & ~mk);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) d[v][c] = kPadWord;
+        }
+    }
+
+    ByteMax bm;
+    bm.init(d[0][0]);
+#pragma unroll
+    for (int c = 1; c < 4; ++c) bm.add(d[0][c]);
+#pragma unroll
+    for (int v = 1; v < V; ++v)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) bm.add(d[v][c]);
+    const int m = group_max<G>(bm.result());
+    const uint32_t mu = (uint32_t)(m + 128);
+    const uint32_t D4 = (uint32_t)D * 0x01010101u;
+    const uint32_t neg_base4 = 0u - (uint32_t)(127 - m) * 0x01010101u;
+    uint32_t acc_d = 0, acc_abs = 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t dl = distance4(d[v][c], neg_base4);
+            d[v][c] = dl;
+            acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
+            acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
+        }
+    const int t = group_sum<G>((int)acc_d - (int)acc_abs);
+    const int npad = kPaddedLen - n;
+    const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu, (uint32_t)D);
+    const RowOutput<MODE> ro((uint32_t)(n * B - S * sum_clamped), B, S, D);
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int vi = v * G + sub;
+        if (!live || vi >= nspan) continue;
+        const u32x4 o = ro.vector(d[v]);
+        uint8_t *dst = out + base + (size_t)vi * 16;
+        if (16 * vi >= lo && 16 * vi + 16 <= hi) {
+            store_stream(dst, o);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int kk = 16 * vi + 4 * c + b;
+                    if (kk >= lo && kk < hi) dst[4 * c + b] = (uint8_t)(o[c] >> (8 * b));
+                }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // One block per row, any length and alignment: the plain integer form of
 // Alg. 1 with byte accesses.  Slow; it exists so that every admissible shape
 // has a path.  Three passes over the row (the second and third re-read it
@@ -420,6 +539,29 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
         if (nvec <= 512) return launch_rows<64, 8, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         if (nvec <= 1024) return launch_rows<64, 16, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         return launch_rows<64, 32, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // 16-bit modes, 8192 < Lk <= 16384
+    }
+    if constexpr ((MODE & 1) == 0) {
+        // 8-bit modes, aligned tensors, ragged row length: aligned vectors over the row's span, masked ends
+        if (vector_ok && Lk % 16 != 0 && Lk <= 16384 - 32) {
+            const int nspan = (Lk + 15 + 15) / 16;   // widest span of a row over aligned 16-byte vectors
+#define HCCS_LAUNCH_RAGGED(G_, V_)                                                                          \
+    {                                                                                                     \
+        dim3 grid_r((Lq + 4 * (64 / G_) - 1) / (4 * (64 / G_)), H, Bt);                                     \
+        hipLaunchKernelGGL((hccs_rows_ragged_kernel<G_, V_, MODE>), grid_r, dim3(256), 0, st, x, p, Lq, Lk, \
+                           (size_t)Bt * H * Lq * Lk, tab);                                                  \
+        return hipGetLastError();                                                                         \
+    }
+            if (nspan <= 4) HCCS_LAUNCH_RAGGED(4, 1)
+            if (nspan <= 8) HCCS_LAUNCH_RAGGED(8, 1)
+            if (nspan <= 16) HCCS_LAUNCH_RAGGED(16, 1)
+            if (nspan <= 32) HCCS_LAUNCH_RAGGED(32, 1)
+            if (nspan <= 64) HCCS_LAUNCH_RAGGED(64, 1)
+            if (nspan <= 128) HCCS_LAUNCH_RAGGED(64, 2)
+            if (nspan <= 256) HCCS_LAUNCH_RAGGED(64, 4)
+            if (nspan <= 512) HCCS_LAUNCH_RAGGED(64, 8)
+            HCCS_LAUNCH_RAGGED(64, 16)
+#undef HCCS_LAUNCH_RAGGED
+        }
     }
     dim3 grid(Lq, H, Bt);
     if (vector_ok && Lk % 16 == 0) {   // 16384 < Lk <= 65536: one block per row, the row in the block's registers

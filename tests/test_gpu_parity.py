@@ -54,7 +54,7 @@ SHAPES = [
     ((1, 2, 130, 400), 1), ((1, 2, 5, 1024), 0), ((1, 2, 6, 880), 0), ((1, 2, 5, 2048), 0), ((1, 2, 9, 1536), 0),
     ((1, 2, 3, 4096), 0), ((1, 1, 5, 3216), 0), ((1, 1, 3, 8192), 0), ((1, 1, 2, 5008), 0), ((1, 1, 2, 16384), 0),
     ((1, 1, 2, 12304), 0), ((2, 1, 1, 64), 1), ((1, 1, 257, 64), 1), ((1, 1, 513, 128), 1),
-    # byte kernel: lengths that are not multiples of 16, or beyond the register kernel
+    # lengths that are not multiples of 16, or beyond the register kernel
     ((1, 2, 5, 100), 1), ((1, 2, 3, 1), 1), ((1, 1, 4, 17), 1), ((1, 1, 3, 255), 0), ((1, 1, 2, 20000), 0),
     ((1, 1, 1, 65536), 0), ((1, 2, 2, 16400), 0),
     # one block per row: multiples of 16 beyond 16384
@@ -98,7 +98,7 @@ def test_softmax_in_place_and_unaligned(oracle):
     out = binding.calibrated_softmax_i8(t, table, 1, out=t.view(torch.uint8))
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), want)
-    # misaligned base pointers take the byte kernel
+    # misaligned base pointers take the byte-granular kernel
     buf_in = torch.zeros(x.size + 16, dtype=torch.int8, device="cuda")
     buf_out = torch.zeros(x.size + 16, dtype=torch.uint8, device="cuda")
     buf_in[1:1 + x.size] = torch.from_numpy(x).cuda().view(-1)
@@ -107,6 +107,47 @@ def test_softmax_in_place_and_unaligned(oracle):
     torch.cuda.synchronize()
     assert np.array_equal(got.cpu().numpy(), want)
     assert int(buf_out[:3].sum()) == 0 and int(buf_out[3 + x.size:].sum()) == 0
+
+
+# ragged row lengths on aligned tensors: every lane-group shape of the masked-ends kernel, rows
+# that start at every offset inside a 16-byte line, its longest length and the first one past it
+RAGGED_SHAPES = [
+    ((2, 3, 40, 1), 1), ((1, 2, 33, 7), 1), ((1, 2, 70, 33), 1), ((2, 2, 50, 49), 1), ((1, 3, 37, 50), 1),
+    ((1, 2, 19, 100), 1), ((2, 2, 33, 113), 1), ((1, 2, 21, 127), 1), ((1, 2, 35, 129), 1), ((1, 2, 18, 225), 1),
+    ((1, 2, 17, 241), 1), ((1, 1, 9, 500), 0), ((1, 2, 11, 1001), 0), ((1, 1, 7, 1009), 0), ((1, 2, 5, 2047), 0),
+    ((1, 1, 5, 3000), 0), ((1, 1, 3, 4099), 0), ((1, 1, 3, 8100), 0), ((1, 1, 3, 16351), 0), ((1, 1, 2, 16353), 0),
+]
+
+
+@pytest.mark.parametrize("shape,band", RAGGED_SHAPES)
+def test_softmax_u8_ragged_lengths(oracle, shape, band):
+    """The output tensor sits inside a larger buffer filled with a canary value: bytes before
+    and after it stay untouched, also when the tensor's last byte is not at the end of a 16-byte line."""
+    H, n = shape[1], shape[3]
+    table = synth.head_params(H, n, band, seed=n + 7 * H)
+    x = mixed_logits(shape, seed=sum(shape))
+    print(f"case ragged shape={shape} band={band}", flush=True)
+    want, rc = oracle.softmax(x, table, band, threads=THREADS)
+    assert rc == 0
+    buf = torch.full((x.size + 96,), 0xA5, dtype=torch.uint8, device="cuda")
+    out = buf[32:32 + x.size].view(shape)
+    binding.calibrated_softmax_i8(torch.from_numpy(x).cuda(), table, band, out=out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        i = tuple(bad[0])
+        raise AssertionError(f"{bad.shape[0]} mismatches, first at {i}: got {got[i]} want {want[i]}")
+    assert bool((buf[:32] == 0xA5).all()) and bool((buf[32 + x.size:] == 0xA5).all())
+    # in place, and with the leading-bit reciprocal
+    t = torch.from_numpy(x).cuda()
+    binding.calibrated_softmax_i8(t, table, band, out=t.view(torch.uint8))
+    torch.cuda.synchronize()
+    assert np.array_equal(t.view(torch.uint8).cpu().numpy(), want)
+    want_clb, _ = oracle.softmax(x, table, band, mode=2, threads=THREADS)
+    got_clb = binding.calibrated_softmax_i8_ex(torch.from_numpy(x).cuda(), table, band, reciprocal=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(got_clb.cpu().numpy(), want_clb)
 
 
 def test_empty_tensors_and_size_limits(oracle):
