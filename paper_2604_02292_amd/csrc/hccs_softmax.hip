@@ -308,43 +308,89 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
     }
 }
 
+// Division of a number below 2^31 by a fixed divisor: floor(x / d) = (x * magic) >> (31 + l)
+// with l = ceil(log2 d) and magic = floor(2^(31+l) / d) + 1 < 2^32 (round-up method for 31-bit
+// dividends).
+struct FastDiv {
+    uint32_t divisor, magic, shift;
+    __device__ __forceinline__ uint32_t quotient(uint32_t x) const
+    {
+        return (uint32_t)(((uint64_t)x * magic) >> 31) >> shift;
+    }
+};
+inline FastDiv make_fast_div(uint32_t d)
+{
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    FastDiv f;
+    f.divisor = d, f.shift = l;
+    f.magic = (uint32_t)((((uint64_t)1 << (31 + l)) / d) + 1);
+    return f;
+}
+
 // ---------------------------------------------------------------------------
 // Rows of any length (8-bit modes, 16-byte aligned tensors): row r starts at byte r*n, which
 // is 16-byte aligned only when n is a multiple of 16.  A lane group loads the ALIGNED vectors
 // that cover the row; bytes of the first and last vector that belong to the neighbouring rows
 // are overwritten with -128 before use, i.e. they become padding (identity of the maximum,
-// known distance, taken out of the sum like every other pad).  Interior vectors are stored
-// whole; the two boundary vectors of a row are stored byte by byte, so neighbouring rows, which
-// share those 16-byte lines, never write each other's bytes.  Input and output rows have the
-// same byte offsets, so one set of masks serves both.
+// known distance, taken out of the sum like every other pad).  Input and output rows have the
+// same byte offsets, so a lane's result vector is an aligned vector of the output as well, and
+// one set of masks serves both.
+//
+// Interior vectors are stored whole.  The vector in which one row ends and the next begins is
+// put together inside the block: the upper row leaves its bytes of it in LDS, the lower row's
+// first lane adds its own and stores the whole vector.  Rows are numbered through the whole
+// tensor (the head comes from the row number), a block owns 4*(64/G) consecutive rows, and
+// that is a multiple of 16 rows whenever G <= 16: then every block begins and ends on a vector
+// boundary.  Only where it does not (longer rows of odd length, the end of the tensor) the
+// first and last vector of a block are stored byte by byte, in branches that whole waves skip.
+// With LEN16 = false (rows shorter than 16 bytes, where a vector can hold several rows) every
+// boundary vector is stored byte by byte instead.
 // ---------------------------------------------------------------------------
-template <int G, int V, int MODE>
+template <int G, int V, int MODE, bool LEN16>
 __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__restrict__ logits,
-                                                               uint8_t *__restrict__ out, int Lq, int n,
-                                                               size_t total, HeadTable table)
+                                                               uint8_t *__restrict__ out, uint32_t rows,
+                                                               FastDiv by_Lq, FastDiv by_H, int n, HeadTable table)
 {
     static_assert((MODE & 1) == 0, "8-bit modes only");
     constexpr int kRowsPerWave = 64 / G;
+    constexpr int kRowsPerBlock = 4 * kRowsPerWave;
     constexpr int kPaddedLen = G * V * 16;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __shared__ int4 lds_table[64];
+    __shared__ __attribute__((aligned(16))) u32x4 lds_tail[kRowsPerBlock];
+    __shared__ __attribute__((aligned(16))) u32x4 lds_low[17];   // entry c: the low c bytes of a vector set
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane % G, grp = lane / G;
-    const int head = blockIdx.y;
-    const int4 hp = table.e[head];
+    if (tid < 64) lds_table[tid] = table.e[tid];
+    if (tid >= 64 && tid < 64 + 17) {
+        const int c = tid - 64;
+        u32x4 mk;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int cj = c - 4 * j;
+            mk[j] = cj >= 4 ? 0xffffffffu : (cj <= 0 ? 0u : ((1u << (8 * cj)) - 1u));
+        }
+        lds_low[c] = mk;
+    }
+    __syncthreads();
+
+    const int rib = wave * kRowsPerWave + grp;                  // row inside the block
+    const uint32_t row_raw = blockIdx.x * (uint32_t)kRowsPerBlock + (uint32_t)rib;
+    const bool live = row_raw < rows;
+    const uint32_t row = live ? row_raw : 0;
+    const uint32_t slab = by_Lq.quotient(row);
+    const int4 hp = lds_table[slab - by_H.quotient(slab) * by_H.divisor];
     const int B = hp.x, S = hp.y, D = hp.z;
-    const int q = ((int)blockIdx.x * 4 + wave) * kRowsPerWave + grp;
-    const bool live = q < Lq;
-    const size_t row = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq + (live ? q : 0);
-    const size_t begin = row * (size_t)n;                 // first byte of the row in the tensor
+    const size_t total = (size_t)rows * (size_t)n;
+    const size_t begin = (size_t)row * (size_t)n;         // first byte of the row in the tensor
     const size_t base = begin & ~(size_t)15;              // aligned start of the covering vectors
     const int lo = (int)(begin - base), hi = lo + n;      // the row is bytes [lo, hi) relative to base
     const int nspan = (hi + 15) >> 4;                     // vectors that touch the row
 
-    // valid-byte mask of dword c of vector vi: bytes whose offset k = 16*vi + 4*c + b lies in [lo, hi)
-    auto dword_mask = [&](int k0) -> uint32_t {
-        const int nlow = min(max(lo - k0, 0), 4), nhigh = min(max(k0 + 4 - hi, 0), 4);
-        const uint32_t mlow = nlow >= 4 ? 0u : (0xffffffffu << (8 * nlow));
-        const uint32_t mhigh = nhigh >= 4 ? 0u : (0xffffffffu >> (8 * nhigh));
-        return mlow & mhigh;
+    // bytes of vector vi that belong to the row: offsets k of the span with lo <= k < hi
+    auto own_bytes = [&](int vi) -> u32x4 {
+        const u32x4 below = lds_low[min(max(lo - 16 * vi, 0), 16)], upto = lds_low[min(max(hi - 16 * vi, 0), 16)];
+        return (u32x4){upto[0] & ~below[0], upto[1] & ~below[1], upto[2] & ~below[2], upto[3] & ~below[3]};
     };
 
     uint32_t d[V][4];
@@ -369,11 +415,9 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
                 }
             }
             if (vi == 0 || vi == nspan - 1) {             // boundary vectors: foreign bytes become padding
+                const u32x4 mk = own_bytes(vi);
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const uint32_t mk = dword_mask(16 * vi + 4 * c);
-                    d[v][c] = (d[v][c] & mk) | (kPadWord & ~mk);
-                }
+                for (int c = 0; c < 4; ++c) d[v][c] = (d[v][c] & mk[c]) | (kPadWord & ~mk[c]);
             }
         } else {
 #pragma unroll
@@ -407,22 +451,50 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
     const int npad = kPaddedLen - n;
     const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu, (uint32_t)D);
     const RowOutput<MODE> ro((uint32_t)(n * B - S * sum_clamped), B, S, D);
+
+    // own bytes of a boundary vector, one at a time
+    auto store_bytes = [&](uint8_t *dst, const u32x4 &o, int vi) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int kk = 16 * vi + 4 * c + b;
+                if (kk >= lo && kk < hi) dst[4 * c + b] = (uint8_t)(o[c] >> (8 * b));
+            }
+    };
+    // the row's last vector is shared with the next row, which is in this block and exists
+    const bool tail_shared = (hi & 15) != 0;
+    const bool tail_to_lds = LEN16 && live && tail_shared && rib + 1 < kRowsPerBlock && row_raw + 1 < rows;
+    const bool head_shared = lo != 0;
+    const bool head_from_lds = LEN16 && live && head_shared && rib > 0;
+    u32x4 head_o = {0, 0, 0, 0};
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int vi = v * G + sub;
         if (!live || vi >= nspan) continue;
-        const u32x4 o = ro.vector(d[v]);
+        u32x4 o = ro.vector(d[v]);
         uint8_t *dst = out + base + (size_t)vi * 16;
         if (16 * vi >= lo && 16 * vi + 16 <= hi) {
             store_stream(dst, o);
+        } else if (v == 0 && vi == 0 && head_from_lds) {
+            const u32x4 mk = own_bytes(0);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) head_o[c] = o[c] & mk[c];   // finished after the barrier
+        } else if (vi == nspan - 1 && tail_to_lds) {
+            const u32x4 mk = own_bytes(vi);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] &= mk[c];
+            lds_tail[rib] = o;
         } else {
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int kk = 16 * vi + 4 * c + b;
-                    if (kk >= lo && kk < hi) dst[4 * c + b] = (uint8_t)(o[c] >> (8 * b));
-                }
+            store_bytes(dst, o, vi);
+        }
+    }
+    if constexpr (LEN16) {
+        __syncthreads();
+        if (sub == 0 && head_from_lds) {
+            const u32x4 above = lds_tail[rib - 1];
+            store_stream(out + base, (u32x4){head_o[0] | above[0], head_o[1] | above[1], head_o[2] | above[2],
+                                             head_o[3] | above[3]});
         }
     }
 }
@@ -541,25 +613,30 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
         return launch_rows<64, 32, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // 16-bit modes, 8192 < Lk <= 16384
     }
     if constexpr ((MODE & 1) == 0) {
-        // 8-bit modes, aligned tensors, ragged row length: aligned vectors over the row's span, masked ends
-        if (vector_ok && Lk % 16 != 0 && Lk <= 16384 - 32) {
-            const int nspan = (Lk + 15 + 15) / 16;   // widest span of a row over aligned 16-byte vectors
-#define HCCS_LAUNCH_RAGGED(G_, V_)                                                                          \
-    {                                                                                                     \
-        dim3 grid_r((Lq + 4 * (64 / G_) - 1) / (4 * (64 / G_)), H, Bt);                                     \
-        hipLaunchKernelGGL((hccs_rows_ragged_kernel<G_, V_, MODE>), grid_r, dim3(256), 0, st, x, p, Lq, Lk, \
-                           (size_t)Bt * H * Lq * Lk, tab);                                                  \
-        return hipGetLastError();                                                                         \
+        // 8-bit modes, aligned tensors, ragged row length: aligned vectors over the row's span
+        const int64_t rows = (int64_t)Bt * H * Lq;
+        if (vector_ok && Lk % 16 != 0 && Lk <= 16384 - 32 && rows < ((int64_t)1 << 31)) {
+            // widest span of a row over aligned 16-byte vectors: rows start at multiples of gcd(Lk, 16)
+            const int step = Lk & -Lk & 15 ? (Lk & -Lk & 15) : 16;
+            const int nspan = (16 - step + Lk + 15) / 16;
+#define HCCS_LAUNCH_RAGGED(G_, V_, LEN16_)                                                                   \
+    {                                                                                                      \
+        const int64_t per_block = 4 * (64 / G_);                                                           \
+        hipLaunchKernelGGL((hccs_rows_ragged_kernel<G_, V_, MODE, LEN16_>),                                 \
+                           dim3((uint32_t)((rows + per_block - 1) / per_block)), dim3(256), 0, st, x, p,    \
+                           (uint32_t)rows, make_fast_div((uint32_t)Lq), make_fast_div((uint32_t)H), Lk, tab);  \
+        return hipGetLastError();                                                                          \
     }
-            if (nspan <= 4) HCCS_LAUNCH_RAGGED(4, 1)
-            if (nspan <= 8) HCCS_LAUNCH_RAGGED(8, 1)
-            if (nspan <= 16) HCCS_LAUNCH_RAGGED(16, 1)
-            if (nspan <= 32) HCCS_LAUNCH_RAGGED(32, 1)
-            if (nspan <= 64) HCCS_LAUNCH_RAGGED(64, 1)
-            if (nspan <= 128) HCCS_LAUNCH_RAGGED(64, 2)
-            if (nspan <= 256) HCCS_LAUNCH_RAGGED(64, 4)
-            if (nspan <= 512) HCCS_LAUNCH_RAGGED(64, 8)
-            HCCS_LAUNCH_RAGGED(64, 16)
+            if (Lk < 16) HCCS_LAUNCH_RAGGED(4, 1, false)
+            if (nspan <= 4) HCCS_LAUNCH_RAGGED(4, 1, true)
+            if (nspan <= 8) HCCS_LAUNCH_RAGGED(8, 1, true)
+            if (nspan <= 16) HCCS_LAUNCH_RAGGED(16, 1, true)
+            if (nspan <= 32) HCCS_LAUNCH_RAGGED(32, 1, true)
+            if (nspan <= 64) HCCS_LAUNCH_RAGGED(64, 1, true)
+            if (nspan <= 128) HCCS_LAUNCH_RAGGED(64, 2, true)
+            if (nspan <= 256) HCCS_LAUNCH_RAGGED(64, 4, true)
+            if (nspan <= 512) HCCS_LAUNCH_RAGGED(64, 8, true)
+            HCCS_LAUNCH_RAGGED(64, 16, true)
 #undef HCCS_LAUNCH_RAGGED
         }
     }

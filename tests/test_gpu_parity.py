@@ -116,6 +116,8 @@ RAGGED_SHAPES = [
     ((1, 2, 19, 100), 1), ((2, 2, 33, 113), 1), ((1, 2, 21, 127), 1), ((1, 2, 35, 129), 1), ((1, 2, 18, 225), 1),
     ((1, 2, 17, 241), 1), ((1, 1, 9, 500), 0), ((1, 2, 11, 1001), 0), ((1, 1, 7, 1009), 0), ((1, 2, 5, 2047), 0),
     ((1, 1, 5, 3000), 0), ((1, 1, 3, 4099), 0), ((1, 1, 3, 8100), 0), ((1, 1, 3, 16351), 0), ((1, 1, 2, 16353), 0),
+    ((2, 3, 197, 197), 0), ((1, 5, 77, 77), 1), ((3, 2, 61, 250), 1), ((1, 2, 130, 999), 0), ((1, 64, 5, 21), 1),
+    ((1, 2, 40, 500), 0), ((1, 2, 9, 1000), 0), ((1, 3, 33, 104), 1), ((1, 2, 21, 2040), 0), ((1, 2, 19, 252), 1),
 ]
 
 
