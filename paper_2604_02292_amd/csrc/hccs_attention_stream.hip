@@ -10,6 +10,7 @@
 // the global loads of chunk c+1 are issued before chunk c is computed and written to the
 // other LDS buffer afterwards, one barrier per chunk.
 #include "hccs_attention_common.h"
+#include <type_traits>
 
 namespace hccs {
 
@@ -92,9 +93,6 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
         }
     };
 
-    auto pair_masks = [&](int key0, uint32_t &m01, uint32_t &m23) { key_pair_masks(key0 + 4 * g, Lk, m01, m23); };
-    auto masked = [](short2_t p, uint32_t mask, uint32_t fill) { return mask_pair(p, mask, fill); };
-
     // logits of key tile tt of the chunk in `buf`, as two 16-bit pairs
     auto tile_logits = [&](int buf, int tt, short2_t &p01, short2_t &p23) {
         v4i acc = {0, 0, 0, 0};
@@ -106,33 +104,45 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
         rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
     };
 
+    // Chunks of 64 whole keys take a branch-free body (the four tiles of a chunk overlap); the one
+    // chunk that may be partial runs the masked body, once per pass.  `body(buf, key0, masked)`
+    // computes one chunk; `with_v` says whether V is staged along with K.
+    const int nfull = Lk >> 6;
+    const bool tail = (Lk & 63) != 0;
+    auto sweep = [&](bool with_v, auto body) {
+        load_chunk(0, with_v);
+        store_chunk(0, with_v);
+        __syncthreads();
+        for (int c = 0; c < nfull; ++c) {
+            if (c + 1 < nchunks) load_chunk(c + 1, with_v);
+            if (active) body(c & 1, c * 64, std::false_type{});
+            if (c + 1 < nchunks) store_chunk((c + 1) & 1, with_v);
+            __syncthreads();
+        }
+        if (tail) {
+            if (active) body(nfull & 1, nfull * 64, std::true_type{});
+            __syncthreads();
+        }
+    };
+
     __syncthreads();   // colsum zeroed before any atomic
 
     // ---- pass A: row maximum -------------------------------------------------------------
     short2_t mx2 = {-32768, -32768};
-    load_chunk(0, false);
-    store_chunk(0, false);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        if (c + 1 < nchunks) load_chunk(c + 1, false);
-        if (active) {
+    sweep(false, [&](int buf, int key0, auto masked) {
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
-                if (c * 64 + 16 * tt < Lk) {
-                    short2_t p01, p23;
-                    tile_logits(c & 1, tt, p01, p23);
-                    if (c * 64 + 16 * tt + 16 > Lk) {      // partial tile: missing keys cannot win the maximum
-                        uint32_t m01, m23;
-                        pair_masks(c * 64 + 16 * tt, m01, m23);
-                        p01 = masked(p01, m01, 0x80008000u);
-                        p23 = masked(p23, m23, 0x80008000u);
-                    }
-                    mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(p01, p23));
-                }
+        for (int tt = 0; tt < 4; ++tt) {
+            short2_t p01, p23;
+            tile_logits(buf, tt, p01, p23);
+            if constexpr (decltype(masked)::value) {   // missing keys cannot win the maximum
+                uint32_t m01, m23;
+                key_pair_masks(key0 + 16 * tt + 4 * g, Lk, m01, m23);
+                p01 = mask_pair(p01, m01, 0x80008000u);
+                p23 = mask_pair(p23, m23, 0x80008000u);
+            }
+            mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(p01, p23));
         }
-        if (c + 1 < nchunks) store_chunk((c + 1) & 1, false);
-        __syncthreads();
-    }
+    });
     int mx = max((int)mx2.x, (int)mx2.y);
     mx = max(mx, xor16(mx));
     mx = max(mx, xor32(mx));
@@ -142,34 +152,25 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 
     // ---- pass B: sum of the window-clamped logits -> Z, reciprocal ----------------------------
     int sx = 0;
-    load_chunk(0, false);
-    store_chunk(0, false);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        if (c + 1 < nchunks) load_chunk(c + 1, false);
-        if (active) {
-            short2_t sum2 = {0, 0};
+    sweep(false, [&](int buf, int key0, auto masked) {
+        short2_t sum2 = {0, 0};
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt)
-                if (c * 64 + 16 * tt < Lk) {
-                    short2_t p01, p23;
-                    tile_logits(c & 1, tt, p01, p23);
-                    short2_t x01 = __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
-                    short2_t x23 = __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
-                    if (c * 64 + 16 * tt + 16 > Lk) {      // missing keys add nothing to the sum
-                        uint32_t m01, m23;
-                        pair_masks(c * 64 + 16 * tt, m01, m23);
-                        x01 = masked(x01, m01, 0u);
-                        x23 = masked(x23, m23, 0u);
-                    }
-                    sum2 += x01;
-                    sum2 += x23;
-                }
-            sx += (int)sum2.x + (int)sum2.y;     // at most 8 values of magnitude <= 128 per half and chunk
+        for (int tt = 0; tt < 4; ++tt) {
+            short2_t p01, p23;
+            tile_logits(buf, tt, p01, p23);
+            short2_t x01 = __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
+            short2_t x23 = __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
+            if constexpr (decltype(masked)::value) {   // missing keys add nothing to the sum
+                uint32_t m01, m23;
+                key_pair_masks(key0 + 16 * tt + 4 * g, Lk, m01, m23);
+                x01 = mask_pair(x01, m01, 0u);
+                x23 = mask_pair(x23, m23, 0u);
+            }
+            sum2 += x01;
+            sum2 += x23;
         }
-        if (c + 1 < nchunks) store_chunk((c + 1) & 1, false);
-        __syncthreads();
-    }
+        sx += (int)sum2.x + (int)sum2.y;     // at most 8 values of magnitude <= 128 per half and chunk
+    });
     sx += xor16(sx);
     sx += xor32(sx);
     // Z = sum (B - S*(m - x')) = Lk*B - S*(Lk*m - sum x')      (Eq. (3), (5))
@@ -185,43 +186,32 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     for (int cg = 0; cg < ND; ++cg)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) oacc[cg][dt] = (v4i){0, 0, 0, 0};
-    load_chunk(0, true);
-    store_chunk(0, true);
-    __syncthreads();
-    for (int c = 0; c < nchunks; ++c) {
-        if (c + 1 < nchunks) load_chunk(c + 1, true);
-        if (active) {
-            v4i pop;
+    sweep(true, [&](int buf, int key0, auto masked) {
+        v4i pop;
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) {
-                pop[tt] = (int)0x80808080u;      // P = 0 for keys past the end (their V rows are staged as zero)
-                if (c * 64 + 16 * tt < Lk) {
-                    short2_t p01, p23;
-                    tile_logits(c & 1, tt, p01, p23);
-                    const short2_t x01 = __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
-                    const short2_t x23 = __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
-                    uint32_t s01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x01) * s2 + c2);
-                    uint32_t s23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x23) * s2 + c2);
-                    if (c * 64 + 16 * tt + 16 > Lk) {      // a zero score gives P = 0
-                        uint32_t m01, m23;
-                        pair_masks(c * 64 + 16 * tt, m01, m23);
-                        s01 &= m01;
-                        s23 &= m23;
-                    }
-                    pop[tt] = (int)probabilities_minus_128(s01, s23, rho2);
-                }
+        for (int tt = 0; tt < 4; ++tt) {
+            short2_t p01, p23;
+            tile_logits(buf, tt, p01, p23);
+            const short2_t x01 = __builtin_elementwise_min(__builtin_elementwise_max(p01, lo2), hi2);
+            const short2_t x23 = __builtin_elementwise_min(__builtin_elementwise_max(p23, lo2), hi2);
+            uint32_t s01 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x01) * s2 + c2);
+            uint32_t s23 = __builtin_bit_cast(uint32_t, __builtin_bit_cast(ushort2_t, x23) * s2 + c2);
+            if constexpr (decltype(masked)::value) {   // a zero score gives P = 0; those V rows are staged as zero too
+                uint32_t m01, m23;
+                key_pair_masks(key0 + 16 * tt + 4 * g, Lk, m01, m23);
+                s01 &= m01;
+                s23 &= m23;
             }
-#pragma unroll
-            for (int cg = 0; cg < ND; ++cg)
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    const v4i vop = *(const v4i *)(lds_v[c & 1] + (((cg * 4 + dt) * 4 + g) * 16 + qi) * 16);
-                    oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[cg][dt], 0, 0, 0);
-                }
+            pop[tt] = (int)probabilities_minus_128(s01, s23, rho2);
         }
-        if (c + 1 < nchunks) store_chunk((c + 1) & 1, true);
-        __syncthreads();
-    }
+#pragma unroll
+        for (int cg = 0; cg < ND; ++cg)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const v4i vop = *(const v4i *)(lds_v[buf] + (((cg * 4 + dt) * 4 + g) * 16 + qi) * 16);
+                oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[cg][dt], 0, 0, 0);
+            }
+    });
 
     // ---- O = (P - 128).V + 128 * column sums of V ---------------------------------------------
     if (active) {
@@ -328,49 +318,64 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
         }
     };
 
+    // Chunks of 64 whole keys take a branch-free path, so that the four tiles of a chunk overlap
+    // (operand reads, contractions and rescales of different tiles interleave); the one chunk
+    // that may be partial is handled once, after them, with its own four registers.
+    const int nfull = Lk >> 6;
+    const bool tail = (Lk & 63) != 0;
+    const int tail_buf = nfull & 1;      // the chunk after the full ones was staged by their last iteration
+
     // ---- pass 1: logits as offset-binary bytes, running maximum --------------------------------
-    uint32_t xb[NCMAX * 4];
+    uint32_t xb[NCMAX * 4], xt[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int i = 0; i < NCMAX * 4; ++i) xb[i] = 0;
     short2_t mx2 = {-32768, -32768};
+    // tile tt of the chunk in `buf`: logits -> running maximum, bytes u = clamp(x, -128, 127) + 128
+    auto tile_bytes = [&](const uint8_t *buf, int tt, auto masked, int key0) -> uint32_t {
+        v4i acc = {0, 0, 0, 0};
+#pragma unroll
+        for (int kd = 0; kd < ND; ++kd) {
+            const v4i kop = *(const v4i *)(buf + (16 * tt + qi) * KSTR + 64 * kd + 16 * g);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop[kd], acc, 0, 0, 0);
+        }
+        short2_t p01, p23;
+        rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
+        if constexpr (decltype(masked)::value) {
+            // key slots that do not exist get the lowest 16-bit value: they cannot win the
+            // maximum and saturate to u = 0 below
+            uint32_t m01, m23;
+            key_pair_masks(key0 + 16 * tt + 4 * g, Lk, m01, m23);
+            p01 = mask_pair(p01, m01, 0x80008000u);
+            p23 = mask_pair(p23, m23, 0x80008000u);
+        }
+        mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(p01, p23));
+        const short2_t c128 = {128, 128};
+        const uint32_t lo8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(p01, c128)));
+        const uint32_t hi8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(p23, c128)));
+        return __builtin_amdgcn_perm(hi8, lo8, 0x05040100u);
+    };
     load_k(0);
     store_k(0);
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < NCMAX; ++c) {
-        if (c < nchunks) {
+        if (c < nfull) {
             if (c + 1 < nchunks) load_k(c + 1);
             if (active) {
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt)
-                    if (c * 64 + 16 * tt < Lk) {
-                        v4i acc = {0, 0, 0, 0};
-#pragma unroll
-                        for (int kd = 0; kd < ND; ++kd) {
-                            const v4i kop = *(const v4i *)(lds_k[c & 1] + (16 * tt + qi) * KSTR + 64 * kd + 16 * g);
-                            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop[kd], acc, 0, 0, 0);
-                        }
-                        short2_t p01, p23;
-                        rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
-                        if (c * 64 + 16 * tt + 16 > Lk) {
-                            // partial tile: key slots that do not exist get the lowest 16-bit value, so they
-                            // cannot win the maximum and saturate to u = 0 below
-                            uint32_t m01, m23;
-                            key_pair_masks(c * 64 + 16 * tt + 4 * g, Lk, m01, m23);
-                            p01 = mask_pair(p01, m01, 0x80008000u);
-                            p23 = mask_pair(p23, m23, 0x80008000u);
-                        }
-                        mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(p01, p23));
-                        const short2_t c128 = {128, 128};
-                        const uint32_t lo8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(p01, c128)));
-                        const uint32_t hi8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(p23, c128)));
-                        xb[c * 4 + tt] = __builtin_amdgcn_perm(hi8, lo8, 0x05040100u);
-                    }
+                for (int tt = 0; tt < 4; ++tt) xb[c * 4 + tt] = tile_bytes(lds_k[c & 1], tt, std::false_type{}, 0);
             }
             if (c + 1 < nchunks) store_k((c + 1) & 1);
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);   // keep the unrolled chunks in order: registers, not latency, are scarce
+    }
+    if (tail) {
+        if (active) {
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) xt[tt] = tile_bytes(lds_k[tail_buf], tt, std::true_type{}, nfull * 64);
+        }
+        __syncthreads();                     // the buffers are refilled with V next
     }
     int mx = max((int)mx2.x, (int)mx2.y);
     mx = max(mx, xor16(mx));
@@ -387,10 +392,17 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
         acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
         acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t dl = mu4 - xt[i];
+        xt[i] = dl;
+        acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
+        acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
+    }
     int tsum = (int)acc_d - (int)acc_abs;
     tsum += xor16(tsum);
     tsum += xor32(tsum);
-    constexpr int kSlots = NCMAX * 64;
+    constexpr int kSlots = NCMAX * 64 + 64;    // every slot that is not a key holds u = 0
     const int sum_clamped = (tsum + kSlots * D) / 2 - (kSlots - Lk) * (int)min(mu, (uint32_t)D);
     const uint32_t Z = active ? (uint32_t)(Lk * B - S * sum_clamped) : 256u;
     const RowAffine ra = row_affine(Z, B, S, D);
@@ -401,30 +413,32 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     for (int cg = 0; cg < ND; ++cg)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) oacc[cg][dt] = (v4i){0, 0, 0, 0};
+    auto chunk_pv = [&](const uint8_t *buf, const uint32_t *dist) {
+        v4i pop;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(dist[tt], ra) ^ 0x80808080u);
+#pragma unroll
+        for (int cg = 0; cg < ND; ++cg)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const v4i vop = *(const v4i *)(buf + (((cg * 4 + dt) * 4 + g) * 16 + qi) * 16);
+                oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[cg][dt], 0, 0, 0);
+            }
+    };
     load_v(0);
     store_v(0);
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < NCMAX; ++c) {
-        if (c < nchunks) {
+        if (c < nfull) {
             if (c + 1 < nchunks) load_v(c + 1);
-            if (active) {
-                v4i pop;
-#pragma unroll
-                for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(xb[c * 4 + tt], ra) ^ 0x80808080u);
-#pragma unroll
-                for (int cg = 0; cg < ND; ++cg)
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt) {
-                        const v4i vop = *(const v4i *)(lds_k[c & 1] + (((cg * 4 + dt) * 4 + g) * 16 + qi) * 16);
-                        oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[cg][dt], 0, 0, 0);
-                    }
-            }
+            if (active) chunk_pv(lds_k[c & 1], &xb[c * 4]);
             if (c + 1 < nchunks) store_v((c + 1) & 1);
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);
     }
+    if (tail && active) chunk_pv(lds_k[tail_buf], xt);   // V rows past the end were staged as zero
 
     if (active) {
 #pragma unroll

@@ -466,7 +466,8 @@ STREAM_SHAPES = [  # (Bt, H, Lq, Lk, d, band)
     (1, 1, 16, 4096, 128, 0), (1, 2, 100, 576, 64, 0), (3, 1, 1, 16, 64, 1), (1, 1, 70, 1040, 128, 0),
     # key lengths that are not a multiple of 16 (masked tail tile)
     (1, 2, 19, 100, 64, 1), (2, 1, 33, 1, 64, 1), (1, 2, 5, 17, 128, 1), (1, 1, 40, 255, 64, 1),
-    (1, 2, 16, 1031, 64, 0), (1, 1, 9, 63, 128, 1), (1, 1, 3, 65, 64, 1),
+    (1, 2, 16, 1031, 64, 0), (1, 1, 9, 63, 128, 1), (1, 1, 3, 65, 64, 1), (1, 1, 5, 2049, 64, 0),
+    (1, 1, 18, 2111, 128, 0), (1, 2, 17, 1999, 64, 0), (1, 1, 70, 2047, 128, 0),
 ]
 
 
