@@ -102,15 +102,16 @@ __device__ __forceinline__ void transpose4x4(const uint32_t (&r)[4], uint32_t (&
 }
 
 // Picks the cheapest exact rescale form for a set of heads (|acc| <= acc_bound) and rewrites
-// the table for it: every rule as (mult << (16-shift), 16) if that keeps acc*mult + 2^15 in 32
-// bits, else multiply-add and shift, with the accumulator saturated first if needed.
-inline int choose_rescale(const RequantTable &in, int H, int64_t acc_bound, RequantTable &out)
+// the table for it: every rule as (mult << (16-shift), 16) if that keeps acc*mult + 2^15 (plus
+// `headroom`, for a kernel that adds an offset to the rounding constant) in 32 bits, else
+// multiply-add and shift, with the accumulator saturated first if needed.
+inline int choose_rescale(const RequantTable &in, int H, int64_t acc_bound, RequantTable &out, int64_t headroom = 0)
 {
     out = in;
     bool high16 = true, preclamp = false;
     for (int h = 0; h < H; ++h) {
         const int64_t mult = in.e[h].x, shift = in.e[h].y;
-        if (shift > 16 || (acc_bound * (mult << (16 - shift)) + (1 << 15)) > 0x7fffffffll) high16 = false;
+        if (shift > 16 || (acc_bound * (mult << (16 - shift)) + (1 << 15) + headroom) > 0x7fffffffll) high16 = false;
         if (acc_bound * mult + ((int64_t)1 << (shift - 1)) > 0x7fffffffll) preclamp = true;
     }
     if (high16)

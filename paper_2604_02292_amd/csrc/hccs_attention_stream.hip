@@ -57,20 +57,28 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     // ---- chunk staging -------------------------------------------------------------------
     u32x4 kreg[ND];
     uint32_t vreg[ND][4];
+    // K rows past the end are read from the last row instead (their logits are masked anyway);
+    // V rows past the end must be zero, which only the last, partial chunk has to check.
     auto load_chunk = [&](int chunk, bool with_v) {
         const int key0 = chunk * 64;
+        const bool whole = key0 + 64 <= Lk;
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
             const int c = tid + i * 256;
-            const int key = key0 + c / KPARTS;
-            kreg[i] = key < Lk ? *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16) : (u32x4){0, 0, 0, 0};
+            const int key = min(key0 + c / KPARTS, Lk - 1);
+            kreg[i] = *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16);
             if (with_v) {
                 // unit (cg = i, gg, nn, tt): keys key0 + 16*tt + 4*gg + r, columns 64*cg + 4*nn .. +3
                 const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
+                const int kk0 = key0 + 16 * tt + 4 * gg;
+                if (whole) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int kk = key0 + 16 * tt + 4 * gg + r;
-                    vreg[i][r] = kk < Lk ? *(const uint32_t *)(vb + (size_t)kk * DH + 64 * i + 4 * nn) : 0u;
+                    for (int r = 0; r < 4; ++r)
+                        vreg[i][r] = *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * i + 4 * nn);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        vreg[i][r] = kk0 + r < Lk ? *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * i + 4 * nn) : 0u;
                 }
             }
         }
@@ -279,12 +287,13 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
 
     u32x4 kreg[ND];
     uint32_t vreg[ND][4];
+    // K rows past the end are read from the last row instead: their logits are masked anyway
     auto load_k = [&](int chunk) {
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
             const int c = tid + i * 256;
-            const int key = chunk * 64 + c / KPARTS;
-            kreg[i] = key < Lk ? *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16) : (u32x4){0, 0, 0, 0};
+            const int key = min(chunk * 64 + c / KPARTS, Lk - 1);
+            kreg[i] = *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16);
         }
     };
     auto store_k = [&](int buf) {
@@ -294,15 +303,23 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
             *(u32x4 *)(lds_k[buf] + (c / KPARTS) * KSTR + (c % KPARTS) * 16) = kreg[i];
         }
     };
+    // V rows past the end must be zero, which only the last, partial chunk has to check
     auto load_v = [&](int chunk) {
         const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
+        const int kk0 = chunk * 64 + 16 * tt + 4 * gg;
+        if (chunk * 64 + 64 <= Lk) {
 #pragma unroll
-        for (int i = 0; i < ND; ++i)
+            for (int i = 0; i < ND; ++i)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int kk = chunk * 64 + 16 * tt + 4 * gg + r;
-                vreg[i][r] = kk < Lk ? *(const uint32_t *)(vb + (size_t)kk * DH + 64 * i + 4 * nn) : 0u;
-            }
+                for (int r = 0; r < 4; ++r)
+                    vreg[i][r] = *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * i + 4 * nn);
+        } else {
+#pragma unroll
+            for (int i = 0; i < ND; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    vreg[i][r] = kk0 + r < Lk ? *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * i + 4 * nn) : 0u;
+        }
     };
     auto store_v = [&](int buf) {
         const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
@@ -338,8 +355,17 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
             const v4i kop = *(const v4i *)(buf + (16 * tt + qi) * KSTR + 64 * kd + 16 * g);
             acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop[kd], acc, 0, 0, 0);
         }
+        // logits + 128 (the maximum is tracked with the same offset); in the high-half form the
+        // offset rides on the rounding constant (the host has checked the headroom for it)
         short2_t p01, p23;
-        rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
+        if constexpr (RQ == kRescaleHigh16) {
+            rescale_tile<RQ>(acc, mult, shift, round_c + (128 << 16), lim, p01, p23);
+        } else {
+            rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
+            const short2_t c128 = {128, 128};
+            p01 = __builtin_elementwise_add_sat(p01, c128);
+            p23 = __builtin_elementwise_add_sat(p23, c128);
+        }
         if constexpr (decltype(masked)::value) {
             // key slots that do not exist get the lowest 16-bit value: they cannot win the
             // maximum and saturate to u = 0 below
@@ -349,9 +375,8 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
             p23 = mask_pair(p23, m23, 0x80008000u);
         }
         mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(p01, p23));
-        const short2_t c128 = {128, 128};
-        const uint32_t lo8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(p01, c128)));
-        const uint32_t hi8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, __builtin_elementwise_add_sat(p23, c128)));
+        const uint32_t lo8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, p01));
+        const uint32_t hi8 = sat_pk_u8_i16(__builtin_bit_cast(uint32_t, p23));
         return __builtin_amdgcn_perm(hi8, lo8, 0x05040100u);
     };
     load_k(0);
@@ -380,7 +405,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     int mx = max((int)mx2.x, (int)mx2.y);
     mx = max(mx, xor16(mx));
     mx = max(mx, xor32(mx));
-    const uint32_t mu = (uint32_t)(clamp_i32(mx, -128, 127) + 128);   // saturation is monotone
+    const uint32_t mu = (uint32_t)clamp_i32(mx, 0, 255);   // saturation is monotone; mx carries the +128
 
     // ---- HCCS on the bytes: distances, clamped sum, row constants -------------------------------
     const uint32_t mu4 = mu * 0x01010101u, D4 = (uint32_t)D * 0x01010101u;
@@ -497,7 +522,8 @@ hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_
                                    hipStream_t st)
 {
     RequantTable rq;
-    const int kind = choose_rescale(rq_in, H, (int64_t)d << 14, rq);   // |acc| <= d*128*128
+    // |acc| <= d*128*128; the two-pass kernel adds 128 << 16 to the rounding constant
+    const int kind = choose_rescale(rq_in, H, (int64_t)d << 14, rq, Lk <= 2048 ? (int64_t)128 << 16 : 0);
     const int items = Bt * H;
     if (d != 64 && d != 128) return hipErrorInvalidValue;
     // up to 2048 keys a query tile's logits fit its registers as bytes: Q.K^T once, two passes
