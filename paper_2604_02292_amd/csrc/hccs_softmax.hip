@@ -329,44 +329,47 @@ inline FastDiv make_fast_div(uint32_t d)
 }
 
 // ---------------------------------------------------------------------------
-// Rows of any length (8-bit modes, 16-byte aligned tensors): row r starts at byte r*n, which
-// is 16-byte aligned only when n is a multiple of 16.  A lane group loads the ALIGNED vectors
-// that cover the row; bytes of the first and last vector that belong to the neighbouring rows
-// are overwritten with -128 before use, i.e. they become padding (identity of the maximum,
-// known distance, taken out of the sum like every other pad).  Input and output rows have the
-// same byte offsets, so a lane's result vector is an aligned vector of the output as well, and
-// one set of masks serves both.
+// Rows of any length on 16-byte aligned tensors: row r starts at byte r*n of the input, which
+// is aligned to an input vector only when n is a multiple of the vector size VB (16 bytes in the
+// 8-bit modes, 8 bytes in the 16-bit modes, so that an output vector is 16 bytes in both).  A
+// lane group loads the ALIGNED vectors that cover the row; bytes of the first and last vector
+// that belong to the neighbouring rows are overwritten with -128 before use, i.e. they become
+// padding (identity of the maximum, known distance, taken out of the sum like every other pad).
+// Element positions are kept, so a lane's result is an aligned 16-byte vector of the output as
+// well, and one set of masks serves both.
 //
 // Interior vectors are stored whole.  The vector in which one row ends and the next begins is
-// put together inside the block: the upper row leaves its bytes of it in LDS, the lower row's
+// put together inside the block: the upper row leaves its part of it in LDS, the lower row's
 // first lane adds its own and stores the whole vector.  Rows are numbered through the whole
 // tensor (the head comes from the row number), a block owns 4*(64/G) consecutive rows, and
 // that is a multiple of 16 rows whenever G <= 16: then every block begins and ends on a vector
 // boundary.  Only where it does not (longer rows of odd length, the end of the tensor) the
-// first and last vector of a block are stored byte by byte, in branches that whole waves skip.
-// With LEN16 = false (rows shorter than 16 bytes, where a vector can hold several rows) every
-// boundary vector is stored byte by byte instead.
+// first and last vector of a block are stored element by element, in branches that whole waves
+// skip.  With LONG = false (rows shorter than a vector, which can then hold several rows) every
+// boundary vector is stored element by element instead.
 // ---------------------------------------------------------------------------
-template <int G, int V, int MODE, bool LEN16>
+template <int G, int V, int MODE, bool LONG>
 __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__restrict__ logits,
                                                                uint8_t *__restrict__ out, uint32_t rows,
                                                                FastDiv by_Lq, FastDiv by_H, int n, HeadTable table)
 {
-    static_assert((MODE & 1) == 0, "8-bit modes only");
+    constexpr int kOutBytes = (MODE & 1) ? 2 : 1;   // bytes per output element
+    constexpr int DW = 4 / kOutBytes;               // dwords per input vector
+    constexpr int VB = DW * 4;                      // bytes per input vector
     constexpr int kRowsPerWave = 64 / G;
     constexpr int kRowsPerBlock = 4 * kRowsPerWave;
-    constexpr int kPaddedLen = G * V * 16;
+    constexpr int kPaddedLen = G * V * VB;
     __shared__ int4 lds_table[64];
     __shared__ __attribute__((aligned(16))) u32x4 lds_tail[kRowsPerBlock];
-    __shared__ __attribute__((aligned(16))) u32x4 lds_low[17];   // entry c: the low c bytes of a vector set
+    __shared__ __attribute__((aligned(16))) u32x4 lds_low[VB + 1];   // entry c: the low c input bytes of a vector set
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane % G, grp = lane / G;
     if (tid < 64) lds_table[tid] = table.e[tid];
-    if (tid >= 64 && tid < 64 + 17) {
+    if (tid >= 64 && tid < 64 + VB + 1) {
         const int c = tid - 64;
-        u32x4 mk;
+        u32x4 mk = {0, 0, 0, 0};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < DW; ++j) {
             const int cj = c - 4 * j;
             mk[j] = cj >= 4 ? 0xffffffffu : (cj <= 0 ? 0u : ((1u << (8 * cj)) - 1u));
         }
@@ -382,29 +385,52 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
     const int4 hp = lds_table[slab - by_H.quotient(slab) * by_H.divisor];
     const int B = hp.x, S = hp.y, D = hp.z;
     const size_t total = (size_t)rows * (size_t)n;
-    const size_t begin = (size_t)row * (size_t)n;         // first byte of the row in the tensor
-    const size_t base = begin & ~(size_t)15;              // aligned start of the covering vectors
+    const size_t begin = (size_t)row * (size_t)n;         // first byte of the row in the input
+    const size_t base = begin & ~(size_t)(VB - 1);        // aligned start of the covering vectors
     const int lo = (int)(begin - base), hi = lo + n;      // the row is bytes [lo, hi) relative to base
-    const int nspan = (hi + 15) >> 4;                     // vectors that touch the row
+    const int nspan = (hi + VB - 1) / VB;                 // vectors that touch the row
 
-    // bytes of vector vi that belong to the row: offsets k of the span with lo <= k < hi
-    auto own_bytes = [&](int vi) -> u32x4 {
-        const u32x4 below = lds_low[min(max(lo - 16 * vi, 0), 16)], upto = lds_low[min(max(hi - 16 * vi, 0), 16)];
-        return (u32x4){upto[0] & ~below[0], upto[1] & ~below[1], upto[2] & ~below[2], upto[3] & ~below[3]};
+    // input bytes of vector vi that belong to the row: offsets k of the span with lo <= k < hi
+    struct Mask {
+        uint32_t w[DW];
+    };
+    auto own_bytes = [&](int vi) -> Mask {
+        const u32x4 below = lds_low[min(max(lo - VB * vi, 0), VB)], upto = lds_low[min(max(hi - VB * vi, 0), VB)];
+        Mask mk;
+#pragma unroll
+        for (int c = 0; c < DW; ++c) mk.w[c] = upto[c] & ~below[c];
+        return mk;
+    };
+    // the same as a mask over the 16 output bytes of the vector
+    auto own_out = [&](int vi) -> u32x4 {
+        const Mask mk = own_bytes(vi);
+        if constexpr (DW == 4) {
+            return (u32x4){mk.w[0], mk.w[1], mk.w[2], mk.w[3]};
+        } else {
+            return (u32x4){__builtin_amdgcn_perm(mk.w[0], mk.w[0], 0x01010000u),
+                           __builtin_amdgcn_perm(mk.w[0], mk.w[0], 0x03030202u),
+                           __builtin_amdgcn_perm(mk.w[1], mk.w[1], 0x01010000u),
+                           __builtin_amdgcn_perm(mk.w[1], mk.w[1], 0x03030202u)};
+        }
     };
 
-    uint32_t d[V][4];
+    uint32_t d[V][DW];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int vi = v * G + sub;
         if (live && vi < nspan) {
-            const size_t at = base + (size_t)vi * 16;
-            if (at + 16 <= total) {
-                const u32x4 t = load_stream(logits + at);
-                d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
+            const size_t at = base + (size_t)vi * VB;
+            if (at + VB <= total) {
+                if constexpr (DW == 4) {
+                    const u32x4 t = load_stream(logits + at);
+                    d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
+                } else {
+                    const u32x2 t = load_stream8(logits + at);
+                    d[v][0] = t[0], d[v][1] = t[1];
+                }
             } else {                                      // the tensor ends inside this vector: no read past it
 #pragma unroll
-                for (int c = 0; c < 4; ++c) {
+                for (int c = 0; c < DW; ++c) {
                     uint32_t w = 0;
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
@@ -415,24 +441,24 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
                 }
             }
             if (vi == 0 || vi == nspan - 1) {             // boundary vectors: foreign bytes become padding
-                const u32x4 mk = own_bytes(vi);
+                const Mask mk = own_bytes(vi);
 #pragma unroll
-                for (int c = 0; c < 4; ++c) d[v][c] = (d[v][c] & mk[c]) | (kPadWord & ~mk[c]);
+                for (int c = 0; c < DW; ++c) d[v][c] = (d[v][c] & mk.w[c]) | (kPadWord & ~mk.w[c]);
             }
         } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) d[v][c] = kPadWord;
+            for (int c = 0; c < DW; ++c) d[v][c] = kPadWord;
         }
     }
 
     ByteMax bm;
     bm.init(d[0][0]);
 #pragma unroll
-    for (int c = 1; c < 4; ++c) bm.add(d[0][c]);
+    for (int c = 1; c < DW; ++c) bm.add(d[0][c]);
 #pragma unroll
     for (int v = 1; v < V; ++v)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) bm.add(d[v][c]);
+        for (int c = 0; c < DW; ++c) bm.add(d[v][c]);
     const int m = group_max<G>(bm.result());
     const uint32_t mu = (uint32_t)(m + 128);
     const uint32_t D4 = (uint32_t)D * 0x01010101u;
@@ -441,7 +467,7 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
 #pragma unroll
     for (int v = 0; v < V; ++v)
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < DW; ++c) {
             const uint32_t dl = distance4(d[v][c], neg_base4);
             d[v][c] = dl;
             acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
@@ -452,49 +478,53 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
     const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu, (uint32_t)D);
     const RowOutput<MODE> ro((uint32_t)(n * B - S * sum_clamped), B, S, D);
 
-    // own bytes of a boundary vector, one at a time
-    auto store_bytes = [&](uint8_t *dst, const u32x4 &o, int vi) {
+    // own elements of a boundary vector, one at a time
+    auto store_elements = [&](uint8_t *dst, const u32x4 &o, int vi) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const int kk = 16 * vi + 4 * c + b;
-                if (kk >= lo && kk < hi) dst[4 * c + b] = (uint8_t)(o[c] >> (8 * b));
+        for (int e = 0; e < VB; ++e) {
+            const int kk = VB * vi + e;                   // input byte = element number
+            if (kk >= lo && kk < hi) {
+                if constexpr (kOutBytes == 1)
+                    dst[e] = (uint8_t)(o[e >> 2] >> (8 * (e & 3)));
+                else
+                    ((uint16_t *)dst)[e] = (uint16_t)(o[e >> 1] >> (16 * (e & 1)));
             }
+        }
     };
     // the row's last vector is shared with the next row, which is in this block and exists
-    const bool tail_shared = (hi & 15) != 0;
-    const bool tail_to_lds = LEN16 && live && tail_shared && rib + 1 < kRowsPerBlock && row_raw + 1 < rows;
+    const bool tail_shared = (hi % VB) != 0;
+    const bool tail_to_lds = LONG && live && tail_shared && rib + 1 < kRowsPerBlock && row_raw + 1 < rows;
     const bool head_shared = lo != 0;
-    const bool head_from_lds = LEN16 && live && head_shared && rib > 0;
+    const bool head_from_lds = LONG && live && head_shared && rib > 0;
     u32x4 head_o = {0, 0, 0, 0};
+    uint8_t *out_base = out + base * kOutBytes;
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int vi = v * G + sub;
         if (!live || vi >= nspan) continue;
         u32x4 o = ro.vector(d[v]);
-        uint8_t *dst = out + base + (size_t)vi * 16;
-        if (16 * vi >= lo && 16 * vi + 16 <= hi) {
+        uint8_t *dst = out_base + (size_t)vi * 16;
+        if (VB * vi >= lo && VB * vi + VB <= hi) {
             store_stream(dst, o);
         } else if (v == 0 && vi == 0 && head_from_lds) {
-            const u32x4 mk = own_bytes(0);
+            const u32x4 mk = own_out(0);
 #pragma unroll
             for (int c = 0; c < 4; ++c) head_o[c] = o[c] & mk[c];   // finished after the barrier
         } else if (vi == nspan - 1 && tail_to_lds) {
-            const u32x4 mk = own_bytes(vi);
+            const u32x4 mk = own_out(vi);
 #pragma unroll
             for (int c = 0; c < 4; ++c) o[c] &= mk[c];
             lds_tail[rib] = o;
         } else {
-            store_bytes(dst, o, vi);
+            store_elements(dst, o, vi);
         }
     }
-    if constexpr (LEN16) {
+    if constexpr (LONG) {
         __syncthreads();
         if (sub == 0 && head_from_lds) {
             const u32x4 above = lds_tail[rib - 1];
-            store_stream(out + base, (u32x4){head_o[0] | above[0], head_o[1] | above[1], head_o[2] | above[2],
-                                             head_o[3] | above[3]});
+            store_stream(out_base, (u32x4){head_o[0] | above[0], head_o[1] | above[1], head_o[2] | above[2],
+                                           head_o[3] | above[3]});
         }
     }
 }
@@ -595,7 +625,7 @@ template <int MODE>
 static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
                               bool vector_ok, hipStream_t st)
 {
-    if (vector_ok && Lk % 16 == 0 && Lk <= 16384) {
+    if (vector_ok && Lk % ((MODE & 1) ? 8 : 16) == 0 && Lk <= 16384) {
         // Lane-group width G = the smallest power of two that covers the row with one
         // vector per lane, so that each load/store instruction touches G contiguous
         // vectors of a row; beyond 64 lanes the row takes V vectors per lane.  Few rows in
@@ -612,22 +642,23 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
         if (nvec <= 1024) return launch_rows<64, 16, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         return launch_rows<64, 32, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // 16-bit modes, 8192 < Lk <= 16384
     }
-    if constexpr ((MODE & 1) == 0) {
-        // 8-bit modes, aligned tensors, ragged row length: aligned vectors over the row's span
+    {
+        // aligned tensors, ragged row length: aligned vectors over the row's span
+        constexpr int VB = (MODE & 1) ? 8 : 16;   // input bytes per vector
         const int64_t rows = (int64_t)Bt * H * Lq;
-        if (vector_ok && Lk % 16 != 0 && Lk <= 16384 - 32 && rows < ((int64_t)1 << 31)) {
-            // widest span of a row over aligned 16-byte vectors: rows start at multiples of gcd(Lk, 16)
-            const int step = Lk & -Lk & 15 ? (Lk & -Lk & 15) : 16;
-            const int nspan = (16 - step + Lk + 15) / 16;
-#define HCCS_LAUNCH_RAGGED(G_, V_, LEN16_)                                                                   \
+        if (vector_ok && Lk % VB != 0 && Lk <= 16384 - 32 && rows < ((int64_t)1 << 31)) {
+            // widest span of a row over aligned vectors: rows start at multiples of gcd(Lk, VB)
+            const int step = (Lk & -Lk & (VB - 1)) ? (Lk & -Lk & (VB - 1)) : VB;
+            const int nspan = (VB - step + Lk + VB - 1) / VB;
+#define HCCS_LAUNCH_RAGGED(G_, V_, LONG_)                                                                    \
     {                                                                                                      \
         const int64_t per_block = 4 * (64 / G_);                                                           \
-        hipLaunchKernelGGL((hccs_rows_ragged_kernel<G_, V_, MODE, LEN16_>),                                 \
+        hipLaunchKernelGGL((hccs_rows_ragged_kernel<G_, V_, MODE, LONG_>),                                  \
                            dim3((uint32_t)((rows + per_block - 1) / per_block)), dim3(256), 0, st, x, p,    \
                            (uint32_t)rows, make_fast_div((uint32_t)Lq), make_fast_div((uint32_t)H), Lk, tab);  \
         return hipGetLastError();                                                                          \
     }
-            if (Lk < 16) HCCS_LAUNCH_RAGGED(4, 1, false)
+            if (Lk < VB) HCCS_LAUNCH_RAGGED(4, 1, false)
             if (nspan <= 4) HCCS_LAUNCH_RAGGED(4, 1, true)
             if (nspan <= 8) HCCS_LAUNCH_RAGGED(8, 1, true)
             if (nspan <= 16) HCCS_LAUNCH_RAGGED(16, 1, true)
@@ -636,7 +667,8 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
             if (nspan <= 128) HCCS_LAUNCH_RAGGED(64, 2, true)
             if (nspan <= 256) HCCS_LAUNCH_RAGGED(64, 4, true)
             if (nspan <= 512) HCCS_LAUNCH_RAGGED(64, 8, true)
-            HCCS_LAUNCH_RAGGED(64, 16, true)
+            if (nspan <= 1024) HCCS_LAUNCH_RAGGED(64, 16, true)
+            HCCS_LAUNCH_RAGGED(64, 32, true)
 #undef HCCS_LAUNCH_RAGGED
         }
     }

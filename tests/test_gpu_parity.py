@@ -249,6 +249,10 @@ MODE_SHAPES = [
     ((1, 2, 5, 100), 1), ((1, 1, 4, 17), 1), ((1, 2, 3, 1), 1), ((1, 1, 2, 20000), 1),
     ((1, 2, 5, 1024), 0), ((1, 2, 3, 4096), 0), ((1, 1, 3, 255), 0),
     ((1, 2, 2, 32752), 1), ((1, 1, 3, 16400), 1), ((1, 1, 2, 40000), 0),
+    # ragged lengths: masked-ends kernel in every mode (8-byte input vectors in the 16-bit modes)
+    ((2, 3, 197, 197), 1), ((1, 2, 40, 500), 1), ((1, 2, 33, 24), 1), ((1, 2, 9, 1000), 1), ((1, 2, 7, 8200), 1),
+    ((1, 3, 70, 7), 1), ((1, 2, 21, 127), 1), ((1, 2, 50, 9), 1), ((1, 1, 3, 16351), 1), ((1, 2, 5, 2047), 1),
+    ((1, 2, 130, 129), 0), ((1, 2, 19, 72), 1), ((1, 1, 5, 16376), 1),
 ]
 
 
