@@ -90,9 +90,10 @@ HCCS_API int hccs_validate_params(const hccs_head_params *table_host, int32_t H,
  *               logits_dev (in place) but must not partially overlap it.
  *   B,H,Lq      >= 0 for B and Lq (an empty tensor is a no-op), 1 <= H <= HCCS_MAX_HEADS,
  *               B <= 65535.
- *   Lk          1..HCCS_MAX_ROW_LENGTH.  Rows whose length is a multiple of 16 with
- *               16-byte aligned base pointers take the vectorised kernels; any other
- *               length or alignment takes a slower byte-wise kernel.
+ *   Lk          1..HCCS_MAX_ROW_LENGTH.  With 16-byte aligned base pointers every length up
+ *               to 16352 (and multiples of 16 beyond) takes the vectorised kernels, fastest
+ *               for multiples of 16; misaligned pointers and other lengths beyond 16352 take
+ *               a slower byte-wise kernel.
  *   table_host  H entries, validated against `band` with n = Lk.
  *   out_scale_T must be 255.
  * Errors: NULL pointers, bad shapes, out_scale_T != 255, inadmissible table. */
