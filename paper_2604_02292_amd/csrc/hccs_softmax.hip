@@ -661,10 +661,13 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
             if (Lk < VB) HCCS_LAUNCH_RAGGED(4, 1, false)
             if (nspan <= 4) HCCS_LAUNCH_RAGGED(4, 1, true)
             if (nspan <= 8) HCCS_LAUNCH_RAGGED(8, 1, true)
+            // measured: two vectors per lane in a narrower group beat one per lane in a wide,
+            // half-empty one (the per-row index and mask work is shared by more payload)
+            if (nspan <= 12) HCCS_LAUNCH_RAGGED(8, 2, true)
             if (nspan <= 16) HCCS_LAUNCH_RAGGED(16, 1, true)
-            if (nspan <= 32) HCCS_LAUNCH_RAGGED(32, 1, true)
-            if (nspan <= 64) HCCS_LAUNCH_RAGGED(64, 1, true)
-            if (nspan <= 128) HCCS_LAUNCH_RAGGED(64, 2, true)
+            if (nspan <= 32) HCCS_LAUNCH_RAGGED(16, 2, true)
+            if (nspan <= 64) HCCS_LAUNCH_RAGGED(32, 2, true)
+            if (nspan <= 128) HCCS_LAUNCH_RAGGED(32, 4, true)
             if (nspan <= 256) HCCS_LAUNCH_RAGGED(64, 4, true)
             if (nspan <= 512) HCCS_LAUNCH_RAGGED(64, 8, true)
             if (nspan <= 1024) HCCS_LAUNCH_RAGGED(64, 16, true)
