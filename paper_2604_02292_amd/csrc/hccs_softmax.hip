@@ -626,16 +626,16 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
                               bool vector_ok, hipStream_t st)
 {
     if (vector_ok && Lk % ((MODE & 1) ? 8 : 16) == 0 && Lk <= 16384) {
-        // Lane-group width G = the smallest power of two that covers the row with one
-        // vector per lane, so that each load/store instruction touches G contiguous
-        // vectors of a row; beyond 64 lanes the row takes V vectors per lane.  Few rows in
-        // flight per wave (R) and many waves measured faster than the reverse.
+        // Lane-group width G: a power of two that covers the row with one or two vectors
+        // per lane, so that each load/store instruction touches G contiguous vectors of a
+        // row; beyond 128 vectors the row takes V vectors per lane of a whole wave.  Few rows
+        // in flight per wave (R) and many waves measured faster than the reverse.
         const int nvec = Lk / ((MODE & 1) ? 8 : 16);
         if (nvec <= 4) return launch_rows<4, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         if (nvec <= 8) return launch_rows<8, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         if (nvec <= 16) return launch_rows<16, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         if (nvec <= 32) return launch_rows<16, 2, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        if (nvec <= 64) return launch_rows<64, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
+        if (nvec <= 64) return launch_rows<32, 2, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // measured against <64,1,2>: up to 20 % faster below 48 vectors, equal at 64
         if (nvec <= 128) return launch_rows<64, 2, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         if (nvec <= 256) return launch_rows<64, 4, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
         if (nvec <= 512) return launch_rows<64, 8, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
