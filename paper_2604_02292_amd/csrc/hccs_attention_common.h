@@ -101,6 +101,18 @@ __device__ __forceinline__ void transpose4x4(const uint32_t (&r)[4], uint32_t (&
     w[3] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
 }
 
+// Workgroups are handed to the chip's 8 accelerator dies round-robin in linear order, and each
+// die has its own L2.  This maps a block's linear number so that consecutive logical numbers
+// (the query tiles of one (batch, head), which all stream the same K and V) run on one die:
+// die x = linear % 8 gets the logical range [start_x, start_x + count_x).
+constexpr uint32_t kDies = 8;
+__device__ __forceinline__ uint32_t die_major_block(uint32_t linear, uint32_t total)
+{
+    const uint32_t die = linear % kDies, slot = linear / kDies;
+    const uint32_t per = total / kDies, extra = total % kDies;
+    return die * per + min(die, extra) + slot;
+}
+
 // Picks the cheapest exact rescale form for a set of heads (|acc| <= acc_bound) and rewrites
 // the table for it: every rule as (mult << (16-shift), 16) if that keeps acc*mult + 2^15 (plus
 // `headroom`, for a kernel that adds an offset to the rounding constant) in 32 bits, else

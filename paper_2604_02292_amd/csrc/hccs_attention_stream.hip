@@ -30,7 +30,9 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
-    const int item = blockIdx.y;
+    // logical block number: all query tiles of an item on one die, so its K and V stay in that L2
+    const uint32_t logical = die_major_block(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+    const int item = (int)(logical / gridDim.x);
     const int head = item % H;
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
@@ -39,7 +41,7 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 21);
     const int8_t *kb = k + (size_t)item * Lk * DH;
     const int8_t *vb = v + (size_t)item * Lk * DH;
-    const int tile = blockIdx.x * 4 + wave;
+    const int tile = (int)(logical % gridDim.x) * 4 + wave;
     const bool active = tile * 16 < Lq;      // a wave without queries still stages and synchronises
     const int nchunks = (Lk + 63) / 64;
 
@@ -262,7 +264,9 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
-    const int item = blockIdx.y;
+    // logical block number: all query tiles of an item on one die, so its K and V stay in that L2
+    const uint32_t logical = die_major_block(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+    const int item = (int)(logical / gridDim.x);
     const int head = item % H;
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
@@ -271,7 +275,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 21);
     const int8_t *kb = k + (size_t)item * Lk * DH;
     const int8_t *vb = v + (size_t)item * Lk * DH;
-    const int tile = blockIdx.x * 4 + wave;
+    const int tile = (int)(logical % gridDim.x) * 4 + wave;
     const bool active = tile * 16 < Lq;
     const int nchunks = (Lk + 63) / 64;
 
