@@ -81,21 +81,17 @@ def _check(status):
 
 
 def head_table(table):
-    """[H,3] integers (B, S, Dmax) -> C array of hccs_head_params."""
-    t = np.asarray(table, dtype=np.int64).reshape(-1, 3)
-    arr = (HeadParams * t.shape[0])()
-    for h, (B, S, D) in enumerate(t.tolist()):
-        arr[h] = HeadParams(int(np.clip(B, -2**31, 2**31 - 1)), int(np.clip(S, -2**31, 2**31 - 1)),
-                            int(np.clip(D, -2**31, 2**31 - 1)), 0)
-    return arr, t.shape[0]
+    """[H,3] integers (B, S, Dmax) -> C array of hccs_head_params (values beyond 32 bits are
+    clipped to the int32 range, which the library then rejects as out of range)."""
+    t = np.clip(np.asarray(table, dtype=np.int64).reshape(-1, 3), -2**31, 2**31 - 1)
+    packed = np.zeros((t.shape[0], 4), dtype=np.int32)
+    packed[:, :3] = t
+    return (HeadParams * t.shape[0]).from_buffer_copy(packed.tobytes()), t.shape[0]
 
 
 def requant_table(requant):
-    t = np.asarray(requant, dtype=np.int64).reshape(-1, 2)
-    arr = (Requant * t.shape[0])()
-    for h, (m, s) in enumerate(t.tolist()):
-        arr[h] = Requant(int(m), int(s))
-    return arr, t.shape[0]
+    t = np.clip(np.asarray(requant, dtype=np.int64).reshape(-1, 2), -2**31, 2**31 - 1).astype(np.int32)
+    return (Requant * t.shape[0]).from_buffer_copy(np.ascontiguousarray(t).tobytes()), t.shape[0]
 
 
 def validate_params(table, n, band):
