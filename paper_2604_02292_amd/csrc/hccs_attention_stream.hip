@@ -12,6 +12,10 @@
 #include "hccs_attention_common.h"
 #include <type_traits>
 
+#ifndef HCCS_GPC
+#define HCCS_GPC 2
+#endif
+
 namespace hccs {
 
 template <int ND, int RQ>   // head size d = 64*ND
@@ -249,8 +253,15 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 // pass 2 streams V for O = P.V.  Key slots that do not exist hold u = 0: that is the identity
 // of the maximum, their distance to it is m + 128 -- a known amount taken out of the sum -- and
 // their V rows are staged as zero, so whatever P they get multiplies nothing.
+//
+// A chunk is GPC groups of 64 keys (one barrier per chunk).  Chunks of whole keys take a
+// branch-free path, so that the tiles of a chunk overlap (operand reads, contractions and
+// rescales of different tiles interleave); the one chunk that may be partial is handled once,
+// after them, with registers of its own.
+// The matrix unit multiplies signed bytes, P is unsigned: it gets P - 128, and the missing
+// 128 = 64 + 64 as two more contractions of a constant operand with the same V operand.
 // ---------------------------------------------------------------------------
-template <int NCMAX, int ND, int RQ>
+template <int NCMAX, int ND, int RQ, int GPC>
 __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_stream2_kernel(
     const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v,
     int32_t *__restrict__ o, int H, int Lq, int Lk, HeadTable table, RequantTable requant)
@@ -258,9 +269,12 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     constexpr int DH = 64 * ND;
     constexpr int KSTR = DH + 16;
     constexpr int KPARTS = DH / 16;
-    __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][64 * KSTR];   // pass 1: K chunks; pass 2: V chunks
-    __shared__ __attribute__((aligned(16))) int32_t lds_colsum[DH];
-    static_assert(64 * KSTR >= 64 * DH, "the V chunk reuses the K buffers");
+    constexpr int CK = 64 * GPC;             // keys per chunk
+    constexpr int TPC = 4 * GPC;             // 16-key tiles per chunk
+    constexpr int NCH = NCMAX / GPC;         // chunks of whole keys at most
+    constexpr int KU = ND * GPC;             // staging units per thread (K: 16-byte pieces; V: 4x4 byte blocks)
+    static_assert(NCMAX % GPC == 0, "whole chunks");
+    __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][CK * KSTR];   // pass 1: K chunks; pass 2: V chunks
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
@@ -277,9 +291,10 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     const int8_t *vb = v + (size_t)item * Lk * DH;
     const int tile = (int)(logical % gridDim.x) * 4 + wave;
     const bool active = tile * 16 < Lq;
-    const int nchunks = (Lk + 63) / 64;
-
-    for (int c = tid; c < DH; c += 256) lds_colsum[c] = 0;
+    const int nfull = Lk / CK;
+    const bool tail = (Lk % CK) != 0;
+    const int nchunks = nfull + (tail ? 1 : 0);
+    const int tail_buf = nfull & 1;      // the chunk after the whole ones was staged by their last iteration
 
     v4i qop[ND];
     {
@@ -289,67 +304,65 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
             qop[kd] = *(const v4i *)(q + ((size_t)item * Lq + row) * DH + 64 * kd + 16 * g);
     }
 
-    u32x4 kreg[ND];
-    uint32_t vreg[ND][4];
+    u32x4 kreg[KU];
+    uint32_t vreg[KU][4];
     // K rows past the end are read from the last row instead: their logits are masked anyway
     auto load_k = [&](int chunk) {
 #pragma unroll
-        for (int i = 0; i < ND; ++i) {
+        for (int i = 0; i < KU; ++i) {
             const int c = tid + i * 256;
-            const int key = min(chunk * 64 + c / KPARTS, Lk - 1);
+            const int key = min(chunk * CK + c / KPARTS, Lk - 1);
             kreg[i] = *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16);
         }
     };
     auto store_k = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < ND; ++i) {
+        for (int i = 0; i < KU; ++i) {
             const int c = tid + i * 256;
             *(u32x4 *)(lds_k[buf] + (c / KPARTS) * KSTR + (c % KPARTS) * 16) = kreg[i];
         }
     };
-    // V rows past the end must be zero, which only the last, partial chunk has to check
+    // V staging unit u = T*ND + cg (T = 64-key group of the chunk, cg = 64-column group) of thread
+    // (gg, nn, tt): keys 64*T + 16*tt + 4*gg + r (r = 0..3), columns 64*cg + 4*nn .. +3.
+    // V rows past the end must be zero, which only the last, partial chunk has to check.
     auto load_v = [&](int chunk) {
         const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
-        const int kk0 = chunk * 64 + 16 * tt + 4 * gg;
-        if (chunk * 64 + 64 <= Lk) {
+        const bool whole = chunk * CK + CK <= Lk;
 #pragma unroll
-            for (int i = 0; i < ND; ++i)
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    vreg[i][r] = *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * i + 4 * nn);
-        } else {
-#pragma unroll
-            for (int i = 0; i < ND; ++i)
+        for (int u = 0; u < KU; ++u) {
+            const int T = u / ND, cg = u % ND;
+            const int kk0 = chunk * CK + 64 * T + 16 * tt + 4 * gg;
+            if (whole) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    vreg[i][r] = kk0 + r < Lk ? *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * i + 4 * nn) : 0u;
-        }
-    };
-    auto store_v = [&](int buf) {
-        const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
+                    vreg[u][r] = *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * cg + 4 * nn);
+            } else {
 #pragma unroll
-        for (int i = 0; i < ND; ++i) {
-            uint32_t w[4];
-            transpose4x4(vreg[i], w);
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                *(uint32_t *)(lds_k[buf] + (((i * 4 + dt) * 4 + gg) * 16 + nn) * 16 + tt * 4) = w[dt];
-                atomicAdd(&lds_colsum[64 * i + 4 * nn + dt], __builtin_amdgcn_sdot4((int)w[dt], 0x01010101, 0, false));
+                for (int r = 0; r < 4; ++r)
+                    vreg[u][r] = kk0 + r < Lk ? *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * cg + 4 * nn) : 0u;
             }
         }
     };
-
-    // Chunks of 64 whole keys take a branch-free path, so that the four tiles of a chunk overlap
-    // (operand reads, contractions and rescales of different tiles interleave); the one chunk
-    // that may be partial is handled once, after them, with its own four registers.
-    const int nfull = Lk >> 6;
-    const bool tail = (Lk & 63) != 0;
-    const int tail_buf = nfull & 1;      // the chunk after the full ones was staged by their last iteration
+    // operand of lane (g, qi) for (T, cg, dt): 16 bytes at ((((T*ND + cg)*4 + dt)*4 + g)*16 + qi)*16
+    auto store_v = [&](int buf) {
+        const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
+#pragma unroll
+        for (int u = 0; u < KU; ++u) {
+            uint32_t w[4];
+            transpose4x4(vreg[u], w);
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                *(uint32_t *)(lds_k[buf] + (((u * 4 + dt) * 4 + gg) * 16 + nn) * 16 + tt * 4) = w[dt];
+        }
+    };
+    static_assert(CK * KSTR >= GPC * ND * 4 * 4 * 16 * 16, "the V chunk reuses the K buffers");
 
     // ---- pass 1: logits as offset-binary bytes, running maximum --------------------------------
-    uint32_t xb[NCMAX * 4], xt[4] = {0, 0, 0, 0};
+    uint32_t xb[NCMAX * 4], xt[TPC];
 #pragma unroll
     for (int i = 0; i < NCMAX * 4; ++i) xb[i] = 0;
+#pragma unroll
+    for (int i = 0; i < TPC; ++i) xt[i] = 0;
     short2_t mx2 = {-32768, -32768};
     // tile tt of the chunk in `buf`: logits -> running maximum, bytes u = clamp(x, -128, 127) + 128
     auto tile_bytes = [&](const uint8_t *buf, int tt, auto masked, int key0) -> uint32_t {
@@ -387,12 +400,12 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     store_k(0);
     __syncthreads();
 #pragma unroll
-    for (int c = 0; c < NCMAX; ++c) {
+    for (int c = 0; c < NCH; ++c) {
         if (c < nfull) {
             if (c + 1 < nchunks) load_k(c + 1);
             if (active) {
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt) xb[c * 4 + tt] = tile_bytes(lds_k[c & 1], tt, std::false_type{}, 0);
+                for (int tt = 0; tt < TPC; ++tt) xb[c * TPC + tt] = tile_bytes(lds_k[c & 1], tt, std::false_type{}, 0);
             }
             if (c + 1 < nchunks) store_k((c + 1) & 1);
             __syncthreads();
@@ -402,7 +415,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     if (tail) {
         if (active) {
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) xt[tt] = tile_bytes(lds_k[tail_buf], tt, std::true_type{}, nfull * 64);
+            for (int tt = 0; tt < TPC; ++tt) xt[tt] = tile_bytes(lds_k[tail_buf], tt, std::true_type{}, nfull * CK);
         }
         __syncthreads();                     // the buffers are refilled with V next
     }
@@ -422,7 +435,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
         acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < TPC; ++i) {
         const uint32_t dl = mu4 - xt[i];
         xt[i] = dl;
         acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
@@ -431,7 +444,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     int tsum = (int)acc_d - (int)acc_abs;
     tsum += xor16(tsum);
     tsum += xor32(tsum);
-    constexpr int kSlots = NCMAX * 64 + 64;    // every slot that is not a key holds u = 0
+    constexpr int kSlots = NCMAX * 64 + CK;    // every slot that is not a key holds u = 0
     const int sum_clamped = (tsum + kSlots * D) / 2 - (kSlots - Lk) * (int)min(mu, (uint32_t)D);
     const uint32_t Z = active ? (uint32_t)(Lk * B - S * sum_clamped) : 256u;
     const RowAffine ra = row_affine(Z, B, S, D);
@@ -443,25 +456,36 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) oacc[cg][dt] = (v4i){0, 0, 0, 0};
     auto chunk_pv = [&](const uint8_t *buf, const uint32_t *dist) {
-        v4i pop;
+        const v4i c64 = {0x40404040, 0x40404040, 0x40404040, 0x40404040};
 #pragma unroll
-        for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(dist[tt], ra) ^ 0x80808080u);
+        for (int T = 0; T < GPC; ++T) {
+            v4i pop;
 #pragma unroll
-        for (int cg = 0; cg < ND; ++cg)
+            for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(dist[T * 4 + tt], ra) ^ 0x80808080u);
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                const v4i vop = *(const v4i *)(buf + (((cg * 4 + dt) * 4 + g) * 16 + qi) * 16);
-                oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[cg][dt], 0, 0, 0);
+            for (int cg = 0; cg < ND; ++cg) {
+                v4i vop[4];
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt) {
+                    vop[dt] = *(const v4i *)(buf + ((((T * ND + cg) * 4 + dt) * 4 + g) * 16 + qi) * 16);
+                    oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop[dt], oacc[cg][dt], 0, 0, 0);
+                }
+#pragma unroll
+                for (int rep = 0; rep < 2; ++rep)
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt)
+                        oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop[dt], oacc[cg][dt], 0, 0, 0);
             }
+        }
     };
     load_v(0);
     store_v(0);
     __syncthreads();
 #pragma unroll
-    for (int c = 0; c < NCMAX; ++c) {
+    for (int c = 0; c < NCH; ++c) {
         if (c < nfull) {
             if (c + 1 < nchunks) load_v(c + 1);
-            if (active) chunk_pv(lds_k[c & 1], &xb[c * 4]);
+            if (active) chunk_pv(lds_k[c & 1], &xb[c * TPC]);
             if (c + 1 < nchunks) store_v((c + 1) & 1);
             __syncthreads();
         }
@@ -472,12 +496,10 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     if (active) {
 #pragma unroll
         for (int cg = 0; cg < ND; ++cg) {
-            const v4i cs = *(const v4i *)(lds_colsum + 64 * cg + 4 * qi);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int row = tile * 16 + 4 * g + r;
-                const v4i out = {oacc[cg][0][r] + 128 * cs[0], oacc[cg][1][r] + 128 * cs[1],
-                                 oacc[cg][2][r] + 128 * cs[2], oacc[cg][3][r] + 128 * cs[3]};
+                const v4i out = {oacc[cg][0][r], oacc[cg][1][r], oacc[cg][2][r], oacc[cg][3][r]};
                 if (row < Lq)
                     __builtin_nontemporal_store(out, (v4i *)(o + ((size_t)item * Lq + row) * DH + 64 * cg + 4 * qi));
             }
@@ -485,20 +507,20 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     }
 }
 
-template <int NCMAX, int ND>
+template <int NCMAX, int ND, int GPC>
 static hipError_t launch_stream2(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int items, int H,
                                  int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
                                  hipStream_t st)
 {
     const dim3 grid((Lq + 63) / 64, items), block(256);
     if (kind == kRescaleHigh16)
-        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16>), grid, block, 0, st, q, k, v, o,
+        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16, GPC>), grid, block, 0, st, q, k, v, o,
                            H, Lq, Lk, tab, rq);
     else if (kind == kRescaleShift)
-        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift>), grid, block, 0, st, q, k, v, o,
+        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift, GPC>), grid, block, 0, st, q, k, v, o,
                            H, Lq, Lk, tab, rq);
     else
-        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp>), grid, block, 0, st, q, k, v,
+        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp, GPC>), grid, block, 0, st, q, k, v,
                            o, H, Lq, Lk, tab, rq);
     return hipGetLastError();
 }
@@ -532,11 +554,11 @@ hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_
     if (d != 64 && d != 128) return hipErrorInvalidValue;
     // up to 2048 keys a query tile's logits fit its registers as bytes: Q.K^T once, two passes
     if (Lk <= 1024)
-        return d == 64 ? launch_stream2<16, 1>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-                       : launch_stream2<16, 2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+        return d == 64 ? launch_stream2<16, 1, HCCS_GPC>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                       : launch_stream2<16, 2, HCCS_GPC>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
     if (Lk <= 2048)
-        return d == 64 ? launch_stream2<32, 1>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-                       : launch_stream2<32, 2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+        return d == 64 ? launch_stream2<32, 1, HCCS_GPC>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                       : launch_stream2<32, 2, HCCS_GPC>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
     return d == 64 ? launch_stream_nd<1>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
                    : launch_stream_nd<2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
 }
