@@ -92,8 +92,10 @@ HCCS_API int hccs_validate_params(const hccs_head_params *table_host, int32_t H,
  *               B <= 65535.
  *   Lk          1..HCCS_MAX_ROW_LENGTH.  With 16-byte aligned base pointers every length up
  *               to 16352 (and multiples of 16 beyond) takes the vectorised kernels, fastest
- *               for multiples of 16; misaligned pointers and other lengths beyond 16352 take
- *               a slower byte-wise kernel.
+ *               for multiples of 16.  So do tensors that begin inside a 16-byte line when
+ *               input and output begin the same number of elements behind such a line (a
+ *               slice of a larger tensor, Lk <= 16352).  Other pointer combinations and
+ *               other lengths beyond 16352 take a slower byte-wise kernel.
  *   table_host  H entries, validated against `band` with n = Lk.
  *   out_scale_T must be 255.
  * Errors: NULL pointers, bad shapes, out_scale_T != 255, inadmissible table. */

@@ -351,8 +351,11 @@ inline FastDiv make_fast_div(uint32_t d)
 template <int G, int V, int MODE, bool LONG>
 __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__restrict__ logits,
                                                                uint8_t *__restrict__ out, uint32_t rows,
-                                                               FastDiv by_Lq, FastDiv by_H, int n, HeadTable table)
+                                                               uint32_t first, FastDiv by_Lq, FastDiv by_H, int n,
+                                                               HeadTable table)
 {
+    // `logits` and `out` are the tensors' base addresses rounded down to a vector boundary; the
+    // tensor's first element sits `first` input bytes (elements) behind them in both.
     constexpr int kOutBytes = (MODE & 1) ? 2 : 1;   // bytes per output element
     constexpr int DW = 4 / kOutBytes;               // dwords per input vector
     constexpr int VB = DW * 4;                      // bytes per input vector
@@ -384,8 +387,8 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
     const uint32_t slab = by_Lq.quotient(row);
     const int4 hp = lds_table[slab - by_H.quotient(slab) * by_H.divisor];
     const int B = hp.x, S = hp.y, D = hp.z;
-    const size_t total = (size_t)rows * (size_t)n;
-    const size_t begin = (size_t)row * (size_t)n;         // first byte of the row in the input
+    const size_t total = (size_t)first + (size_t)rows * (size_t)n;   // end of the tensor
+    const size_t begin = (size_t)first + (size_t)row * (size_t)n;    // first byte of the row in the input
     const size_t base = begin & ~(size_t)(VB - 1);        // aligned start of the covering vectors
     const int lo = (int)(begin - base), hi = lo + n;      // the row is bytes [lo, hi) relative to base
     const int nspan = (hi + VB - 1) / VB;                 // vectors that touch the row
@@ -420,7 +423,7 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
         const int vi = v * G + sub;
         if (live && vi < nspan) {
             const size_t at = base + (size_t)vi * VB;
-            if (at + VB <= total) {
+            if (at >= first && at + VB <= total) {
                 if constexpr (DW == 4) {
                     const u32x4 t = load_stream(logits + at);
                     d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
@@ -428,14 +431,14 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
                     const u32x2 t = load_stream8(logits + at);
                     d[v][0] = t[0], d[v][1] = t[1];
                 }
-            } else {                                      // the tensor ends inside this vector: no read past it
+            } else {                                      // the tensor begins or ends inside this vector: no read outside it
 #pragma unroll
                 for (int c = 0; c < DW; ++c) {
                     uint32_t w = 0;
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const size_t k = at + 4 * c + b;
-                        w |= (uint32_t)(k < total ? (uint8_t)logits[k] : 0x80u) << (8 * b);
+                        w |= (uint32_t)(k >= first && k < total ? (uint8_t)logits[k] : 0x80u) << (8 * b);
                     }
                     d[v][c] = w;
                 }
@@ -643,19 +646,27 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
         return launch_rows<64, 32, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // 16-bit modes, 8192 < Lk <= 16384
     }
     {
-        // aligned tensors, ragged row length: aligned vectors over the row's span
+        // Ragged row length, or tensors that begin inside a vector at matching offsets (element e
+        // of the input `first` bytes behind a vector boundary, element e of the output behind a
+        // 16-byte boundary by as many elements): aligned vectors over each row's span.
         constexpr int VB = (MODE & 1) ? 8 : 16;   // input bytes per vector
+        constexpr int kOutBytes = (MODE & 1) ? 2 : 1;
         const int64_t rows = (int64_t)Bt * H * Lq;
-        if (vector_ok && Lk % VB != 0 && Lk <= 16384 - 32 && rows < ((int64_t)1 << 31)) {
-            // widest span of a row over aligned vectors: rows start at multiples of gcd(Lk, VB)
+        const uint32_t first = (uint32_t)((uintptr_t)x % VB);
+        const bool matching = (uintptr_t)p % 16 == (uintptr_t)first * kOutBytes;
+        if (matching && Lk <= 16384 - 32 && rows < ((int64_t)1 << 31)) {
+            // widest span of a row over aligned vectors: rows start at first + multiples of gcd(Lk, VB)
             const int step = (Lk & -Lk & (VB - 1)) ? (Lk & -Lk & (VB - 1)) : VB;
-            const int nspan = (VB - step + Lk + VB - 1) / VB;
+            const int nspan = (VB - step + (int)(first % step) + Lk + VB - 1) / VB;
+            const int8_t *x_al = x - first;
+            uint8_t *p_al = p - first * kOutBytes;
 #define HCCS_LAUNCH_RAGGED(G_, V_, LONG_)                                                                    \
     {                                                                                                      \
         const int64_t per_block = 4 * (64 / G_);                                                           \
         hipLaunchKernelGGL((hccs_rows_ragged_kernel<G_, V_, MODE, LONG_>),                                  \
-                           dim3((uint32_t)((rows + per_block - 1) / per_block)), dim3(256), 0, st, x, p,    \
-                           (uint32_t)rows, make_fast_div((uint32_t)Lq), make_fast_div((uint32_t)H), Lk, tab);  \
+                           dim3((uint32_t)((rows + per_block - 1) / per_block)), dim3(256), 0, st, x_al,    \
+                           p_al, (uint32_t)rows, first, make_fast_div((uint32_t)Lq),                        \
+                           make_fast_div((uint32_t)H), Lk, tab);                                            \
         return hipGetLastError();                                                                          \
     }
             if (Lk < VB) HCCS_LAUNCH_RAGGED(4, 1, false)

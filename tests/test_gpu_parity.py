@@ -152,6 +152,40 @@ def test_softmax_u8_ragged_lengths(oracle, shape, band):
     assert np.array_equal(got_clb.cpu().numpy(), want_clb)
 
 
+@pytest.mark.parametrize("shape,off", [((2, 4, 30, 128), 5), ((1, 3, 33, 100), 9), ((2, 2, 17, 1000), 15),
+                                       ((1, 2, 40, 64), 8), ((1, 2, 9, 4099), 3), ((3, 2, 50, 7), 1)])
+def test_softmax_tensors_that_begin_inside_a_vector(oracle, shape, off):
+    """Input and output begin the same number of elements behind a 16-byte boundary (a slice of
+    a larger tensor): the masked-ends vector kernel takes them; canaries around the output."""
+    H, n = shape[1], shape[3]
+    band = 1 if n * 8 <= 32767 else 0
+    table = synth.head_params(H, n, band, seed=n + H)
+    x = mixed_logits(shape, seed=sum(shape) + off)
+    want, rc = oracle.softmax(x, table, band, threads=THREADS)
+    assert rc == 0
+    print(f"case offset shape={shape} off={off}", flush=True)
+    buf_in = torch.zeros(x.size + 64, dtype=torch.int8, device="cuda")
+    buf_in[off:off + x.size] = torch.from_numpy(x).cuda().view(-1)
+    buf_out = torch.full((x.size + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    binding.calibrated_softmax_i8(buf_in[off:off + x.size].view(shape), table, band,
+                                  out=buf_out[16 + off:16 + off + x.size].view(shape))
+    torch.cuda.synchronize()
+    assert np.array_equal(buf_out[16 + off:16 + off + x.size].view(shape).cpu().numpy(), want)
+    assert bool((buf_out[:16 + off] == 0xA5).all()) and bool((buf_out[16 + off + x.size:] == 0xA5).all())
+    if band == 1:   # 16-bit output: element offsets match when the output is `off` elements behind a boundary
+        want16, _ = oracle.softmax(x, table, band, mode=1, threads=THREADS)
+        buf16 = torch.full((x.size + 64,), 0x5A5A, dtype=torch.int16, device="cuda")
+        o8 = off % 8
+        b_in = torch.zeros(x.size + 64, dtype=torch.int8, device="cuda")
+        b_in[o8:o8 + x.size] = torch.from_numpy(x).cuda().view(-1)
+        binding.calibrated_softmax_i8_ex(b_in[o8:o8 + x.size].view(shape), table, band, out_scale_T=32767,
+                                         out=buf16[8 + o8:8 + o8 + x.size].view(shape))
+        torch.cuda.synchronize()
+        got16 = buf16[8 + o8:8 + o8 + x.size].view(shape).cpu().numpy().view(np.uint16)
+        assert np.array_equal(got16, want16)
+        assert bool((buf16[:8 + o8] == 0x5A5A).all()) and bool((buf16[8 + o8 + x.size:] == 0x5A5A).all())
+
+
 def test_empty_tensors_and_size_limits(oracle):
     """Zero-sized tensors are a no-op; the largest head table (64) and the largest batch extent
     (65535, the grid's z limit) go through; one more is rejected before any launch."""
