@@ -5,6 +5,8 @@
 namespace hccs {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef v2i __attribute__((address_space(3))) lds_v2i;   // operand type of the transposing LDS read
 
 // min(max(x, lo), hi); the compiler selects v_med3_i32 for it
 __device__ __forceinline__ int clamp_i32(int x, int lo, int hi) { return min(max(x, lo), hi); }

@@ -305,7 +305,6 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     }
 
     u32x4 kreg[KU];
-    uint32_t vreg[KU][4];
     // K rows past the end are read from the last row instead: their logits are masked anyway
     auto load_k = [&](int chunk) {
 #pragma unroll
@@ -322,40 +321,20 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
             *(u32x4 *)(lds_k[buf] + (c / KPARTS) * KSTR + (c % KPARTS) * 16) = kreg[i];
         }
     };
-    // V staging unit u = T*ND + cg (T = 64-key group of the chunk, cg = 64-column group) of thread
-    // (gg, nn, tt): keys 64*T + 16*tt + 4*gg + r (r = 0..3), columns 64*cg + 4*nn .. +3.
-    // V rows past the end must be zero, which only the last, partial chunk has to check.
+    // V is staged row-major like K (rows past the end as zeros, which only the last, partial chunk
+    // has to check); its operands are formed by the transposing LDS read, see chunk_pv.
     auto load_v = [&](int chunk) {
-        const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
         const bool whole = chunk * CK + CK <= Lk;
 #pragma unroll
-        for (int u = 0; u < KU; ++u) {
-            const int T = u / ND, cg = u % ND;
-            const int kk0 = chunk * CK + 64 * T + 16 * tt + 4 * gg;
-            if (whole) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    vreg[u][r] = *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * cg + 4 * nn);
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    vreg[u][r] = kk0 + r < Lk ? *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * cg + 4 * nn) : 0u;
-            }
+        for (int i = 0; i < KU; ++i) {
+            const int c = tid + i * 256;
+            const int key = chunk * CK + c / KPARTS;
+            if (whole || key < Lk)
+                kreg[i] = *(const u32x4 *)(vb + (size_t)key * DH + (c % KPARTS) * 16);
+            else
+                kreg[i] = (u32x4){0, 0, 0, 0};
         }
     };
-    // operand of lane (g, qi) for (T, cg, dt): 16 bytes at ((((T*ND + cg)*4 + dt)*4 + g)*16 + qi)*16
-    auto store_v = [&](int buf) {
-        const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
-#pragma unroll
-        for (int u = 0; u < KU; ++u) {
-            uint32_t w[4];
-            transpose4x4(vreg[u], w);
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-                *(uint32_t *)(lds_k[buf] + (((u * 4 + dt) * 4 + gg) * 16 + nn) * 16 + tt * 4) = w[dt];
-        }
-    };
-    static_assert(CK * KSTR >= GPC * ND * 4 * 4 * 16 * 16, "the V chunk reuses the K buffers");
 
     // ---- pass 1: logits as offset-binary bytes, running maximum --------------------------------
     uint32_t xb[NCMAX * 4], xt[TPC];
@@ -455,6 +434,14 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     for (int cg = 0; cg < ND; ++cg)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) oacc[cg][dt] = (v4i){0, 0, 0, 0};
+    // B operand of the second contraction for lane (g, qi), 64-key group T, columns 16*n16 .. +15:
+    // contraction slot (tt, r) of lane group g is key 64*T + 16*tt + 4*g + r (that is how pass 1
+    // left the logits), and the lane's column is 16*n16 + qi.  ds_read_tr8_b64 takes, in each
+    // group of 16 lanes, the 8 bytes at every lane's address, pairs lanes (2j, 2j+1) into eight
+    // 16-byte rows j, and gives lane i the eight bytes of column i: so lane pair j points at the
+    // two halves of the 16 columns of the key of slot j (first read: tt = 0, 1; second: tt = 2, 3).
+    const int slot = qi >> 1;
+    const int v_lane_off = (16 * (slot >> 2) + 4 * g + (slot & 3)) * KSTR + 8 * (qi & 1);
     auto chunk_pv = [&](const uint8_t *buf, const uint32_t *dist) {
         const v4i c64 = {0x40404040, 0x40404040, 0x40404040, 0x40404040};
 #pragma unroll
@@ -463,45 +450,43 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
 #pragma unroll
             for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(dist[T * 4 + tt], ra) ^ 0x80808080u);
 #pragma unroll
-            for (int cg = 0; cg < ND; ++cg) {
-                v4i vop[4];
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    vop[dt] = *(const v4i *)(buf + ((((T * ND + cg) * 4 + dt) * 4 + g) * 16 + qi) * 16);
-                    oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop[dt], oacc[cg][dt], 0, 0, 0);
-                }
-#pragma unroll
-                for (int rep = 0; rep < 2; ++rep)
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt)
-                        oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop[dt], oacc[cg][dt], 0, 0, 0);
+            for (int n16 = 0; n16 < 4 * ND; ++n16) {
+                const uint8_t *at = buf + 64 * T * KSTR + v_lane_off + 16 * n16;
+                const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)at);
+                const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(at + 32 * KSTR));
+                const v4i vop = {lo[0], lo[1], hi[0], hi[1]};
+                v4i &acc = oacc[n16 / 4][n16 % 4];
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop, acc, 0, 0, 0);
             }
         }
     };
     load_v(0);
-    store_v(0);
+    store_k(0);
     __syncthreads();
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         if (c < nfull) {
             if (c + 1 < nchunks) load_v(c + 1);
             if (active) chunk_pv(lds_k[c & 1], &xb[c * TPC]);
-            if (c + 1 < nchunks) store_v((c + 1) & 1);
+            if (c + 1 < nchunks) store_k((c + 1) & 1);
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);
     }
     if (tail && active) chunk_pv(lds_k[tail_buf], xt);   // V rows past the end were staged as zero
 
+    // lane (g, qi) holds rows 4g .. 4g+3 of column 16*n16 + qi: 64 contiguous bytes per row and group of 16 lanes
     if (active) {
 #pragma unroll
-        for (int cg = 0; cg < ND; ++cg) {
+        for (int r = 0; r < 4; ++r) {
+            const int row = tile * 16 + 4 * g + r;
+            if (row < Lq) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = tile * 16 + 4 * g + r;
-                const v4i out = {oacc[cg][0][r], oacc[cg][1][r], oacc[cg][2][r], oacc[cg][3][r]};
-                if (row < Lq)
-                    __builtin_nontemporal_store(out, (v4i *)(o + ((size_t)item * Lq + row) * DH + 64 * cg + 4 * qi));
+                for (int n16 = 0; n16 < 4 * ND; ++n16)
+                    __builtin_nontemporal_store(oacc[n16 / 4][n16 % 4][r],
+                                                o + ((size_t)item * Lq + row) * DH + 16 * n16 + qi);
             }
         }
     }
