@@ -29,8 +29,7 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     constexpr int KSTR = DH + 16;        // padded K row in LDS (bank spread)
     constexpr int KPARTS = DH / 16;      // 16-byte parts of a K row
     __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][64 * KSTR];
-    __shared__ __attribute__((aligned(16))) uint8_t lds_v[2][64 * DH];
-    __shared__ __attribute__((aligned(16))) int32_t lds_colsum[DH];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_v[2][64 * KSTR];   // row-major like K
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
@@ -49,8 +48,6 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     const bool active = tile * 16 < Lq;      // a wave without queries still stages and synchronises
     const int nchunks = (Lk + 63) / 64;
 
-    for (int c = tid; c < DH; c += 256) lds_colsum[c] = 0;
-
     // Q operand: row clamped into range for the tail tile (those rows are never stored)
     v4i qop[ND];
     {
@@ -61,8 +58,7 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     }
 
     // ---- chunk staging -------------------------------------------------------------------
-    u32x4 kreg[ND];
-    uint32_t vreg[ND][4];
+    u32x4 kreg[ND], vreg[ND];
     // K rows past the end are read from the last row instead (their logits are masked anyway);
     // V rows past the end must be zero, which only the last, partial chunk has to check.
     auto load_chunk = [&](int chunk, bool with_v) {
@@ -71,21 +67,13 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
             const int c = tid + i * 256;
-            const int key = min(key0 + c / KPARTS, Lk - 1);
-            kreg[i] = *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16);
+            const int key = key0 + c / KPARTS;
+            kreg[i] = *(const u32x4 *)(kb + (size_t)min(key, Lk - 1) * DH + (c % KPARTS) * 16);
             if (with_v) {
-                // unit (cg = i, gg, nn, tt): keys key0 + 16*tt + 4*gg + r, columns 64*cg + 4*nn .. +3
-                const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
-                const int kk0 = key0 + 16 * tt + 4 * gg;
-                if (whole) {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        vreg[i][r] = *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * i + 4 * nn);
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        vreg[i][r] = kk0 + r < Lk ? *(const uint32_t *)(vb + (size_t)(kk0 + r) * DH + 64 * i + 4 * nn) : 0u;
-                }
+                if (whole || key < Lk)
+                    vreg[i] = *(const u32x4 *)(vb + (size_t)key * DH + (c % KPARTS) * 16);
+                else
+                    vreg[i] = (u32x4){0, 0, 0, 0};
             }
         }
     };
@@ -93,17 +81,9 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
             const int c = tid + i * 256;
-            *(u32x4 *)(lds_k[buf] + (c / KPARTS) * KSTR + (c % KPARTS) * 16) = kreg[i];
-            if (with_v) {
-                const int tt = tid & 3, nn = (tid >> 2) & 15, gg = tid >> 6;
-                uint32_t w[4];
-                transpose4x4(vreg[i], w);
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt) {
-                    *(uint32_t *)(lds_v[buf] + (((i * 4 + dt) * 4 + gg) * 16 + nn) * 16 + tt * 4) = w[dt];
-                    atomicAdd(&lds_colsum[64 * i + 4 * nn + dt], __builtin_amdgcn_sdot4((int)w[dt], 0x01010101, 0, false));
-                }
-            }
+            const int at = (c / KPARTS) * KSTR + (c % KPARTS) * 16;
+            *(u32x4 *)(lds_k[buf] + at) = kreg[i];
+            if (with_v) *(u32x4 *)(lds_v[buf] + at) = vreg[i];
         }
     };
 
@@ -138,8 +118,6 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
             __syncthreads();
         }
     };
-
-    __syncthreads();   // colsum zeroed before any atomic
 
     // ---- pass A: row maximum -------------------------------------------------------------
     short2_t mx2 = {-32768, -32768};
@@ -195,6 +173,8 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     const ushort2_t c2 = {cc, cc};
 
     // ---- pass C: probabilities and O = P.V ---------------------------------------------------
+    const int slot = qi >> 1;   // contraction slot (tt, r) = (slot >> 2, slot & 3) is key 16*tt + 4*g + r of a 64-key group
+    const int v_lane_off = (16 * (slot >> 2) + 4 * g + (slot & 3)) * KSTR + 8 * (qi & 1);
     v4i oacc[ND][4];
 #pragma unroll
     for (int cg = 0; cg < ND; ++cg)
@@ -218,27 +198,33 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
             }
             pop[tt] = (int)probabilities_minus_128(s01, s23, rho2);
         }
+        // B operand through the transposing LDS read (see the two-pass kernel below): lane pair j
+        // of a 16-lane group points at the key of contraction slot j, the lane receives its column.
+        // P = (P - 128) + 64 + 64: the offset goes through the matrix unit as well.
+        const v4i c64 = {0x40404040, 0x40404040, 0x40404040, 0x40404040};
 #pragma unroll
-        for (int cg = 0; cg < ND; ++cg)
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                const v4i vop = *(const v4i *)(lds_v[buf] + (((cg * 4 + dt) * 4 + g) * 16 + qi) * 16);
-                oacc[cg][dt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, oacc[cg][dt], 0, 0, 0);
-            }
+        for (int n16 = 0; n16 < 4 * ND; ++n16) {
+            const uint8_t *at = lds_v[buf] + v_lane_off + 16 * n16;
+            const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)at);
+            const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(at + 32 * KSTR));
+            const v4i vop = {lo[0], lo[1], hi[0], hi[1]};
+            v4i &acc = oacc[n16 / 4][n16 % 4];
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop, acc, 0, 0, 0);
+        }
     });
 
-    // ---- O = (P - 128).V + 128 * column sums of V ---------------------------------------------
+    // ---- store: lane (g, qi) holds rows 4g .. 4g+3 of column 16*n16 + qi ---------------------
     if (active) {
 #pragma unroll
-        for (int cg = 0; cg < ND; ++cg) {
-            const v4i cs = *(const v4i *)(lds_colsum + 64 * cg + 4 * qi);
+        for (int r = 0; r < 4; ++r) {
+            const int row = tile * 16 + 4 * g + r;
+            if (row < Lq) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = tile * 16 + 4 * g + r;
-                const v4i out = {oacc[cg][0][r] + 128 * cs[0], oacc[cg][1][r] + 128 * cs[1],
-                                 oacc[cg][2][r] + 128 * cs[2], oacc[cg][3][r] + 128 * cs[3]};
-                if (row < Lq)
-                    __builtin_nontemporal_store(out, (v4i *)(o + ((size_t)item * Lq + row) * DH + 64 * cg + 4 * qi));
+                for (int n16 = 0; n16 < 4 * ND; ++n16)
+                    __builtin_nontemporal_store(oacc[n16 / 4][n16 % 4][r],
+                                                o + ((size_t)item * Lq + row) * DH + 16 * n16 + qi);
             }
         }
     }
