@@ -1,14 +1,16 @@
 // Fused int8 attention block for shapes the resident kernel does not take: any number of
-// queries, any key length, head size 64 or 128.  K and V stream
-// through LDS in chunks of 64 keys, so neither the logits of a row nor K and V have to fit
-// anywhere.  HCCS needs the row maximum before the clamped sum and the sum before the first
-// output, and its floors rule out rescaling partial results, so Q.K^T is recomputed three
-// times: pass A finds the maximum, pass B the sum Z, pass C the probabilities and O = P.V.
-// Same arithmetic per element as the resident kernel (hccs_attention_common.h).
+// queries, any key length, head size 64 or 128.  K and V stream through LDS in chunks (64 keys
+// in the three-pass kernel, 128 in the two-pass one), so neither the logits of a row nor K and V
+// have to fit anywhere.  HCCS needs the row maximum before the clamped sum and the sum before
+// the first output, and its floors rule out rescaling partial results, so Q.K^T is recomputed
+// three times: pass A finds the maximum, pass B the sum Z, pass C the probabilities and
+// O = P.V.  Same arithmetic per element as the resident kernel (hccs_attention_common.h).
 //
-// Grid (query tiles of 64, batch*head); a wave owns 16 queries.  A chunk is double-buffered:
-// the global loads of chunk c+1 are issued before chunk c is computed and written to the
-// other LDS buffer afterwards, one barrier per chunk.
+// Grid (query tiles of 64, batch*head), block numbers remapped so that the tiles of one
+// (batch, head) share a die's L2; a wave owns 16 queries.  A chunk is double-buffered: the
+// global loads of chunk c+1 are issued before chunk c is computed and written to the other LDS
+// buffer afterwards, one barrier per chunk.  K and V are both staged row-major with padded
+// rows; V's operands are formed by the transposing LDS read.
 #include "hccs_attention_common.h"
 #include <type_traits>
 
