@@ -506,6 +506,9 @@ STREAM_SHAPES = [  # (Bt, H, Lq, Lk, d, band)
     (1, 2, 19, 100, 64, 1), (2, 1, 33, 1, 64, 1), (1, 2, 5, 17, 128, 1), (1, 1, 40, 255, 64, 1),
     (1, 2, 16, 1031, 64, 0), (1, 1, 9, 63, 128, 1), (1, 1, 3, 65, 64, 1), (1, 1, 5, 2049, 64, 0),
     (1, 1, 18, 2111, 128, 0), (1, 2, 17, 1999, 64, 0), (1, 1, 70, 2047, 128, 0),
+    # block counts that are no multiple of the number of dies (block renumbering), whole and partial 128-key chunks
+    (3, 3, 200, 96, 64, 1), (1, 5, 150, 130, 64, 1), (1, 11, 65, 128, 64, 1), (1, 3, 129, 384, 128, 1),
+    (1, 1, 300, 2200, 64, 0),
 ]
 
 
