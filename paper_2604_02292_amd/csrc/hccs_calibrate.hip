@@ -138,12 +138,22 @@ __global__ __launch_bounds__(256) void calib_reduce_kernel(const double *__restr
     if (t == 0) K[head] = k;
 }
 
+// log(z) for z = 1 .. 32767 (entry 0 unused): every Z of an admissible candidate is an integer in
+// [256, 32767] (strict band), so the per-row logarithm of pass 3 is a table lookup of the same
+// double the logarithm routine returns.
+__global__ __launch_bounds__(256) void calib_logtab_kernel(double *__restrict__ logtab)
+{
+    const int z = blockIdx.x * 256 + threadIdx.x;
+    if (z < 32768) logtab[z] = z > 0 ? log((double)z) : 0.0;
+}
+
 // Pass 3: one block per (candidate, head).
 __global__ __launch_bounds__(256) void calib_objective_kernel(const hccs_head_params *__restrict__ cand, int nc,
                                                               int Bt, int H, int Lq, int n, int64_t rows_total,
                                                               const int32_t *__restrict__ ctab,
                                                               const double *__restrict__ W,
                                                               const double *__restrict__ K,
+                                                              const double *__restrict__ logtab,
                                                               double *__restrict__ objective)
 {
     __shared__ double scratch[4];
@@ -156,13 +166,20 @@ __global__ __launch_bounds__(256) void calib_objective_kernel(const hccs_head_pa
         if (t == 0) objective[(int64_t)head * nc + c] = __longlong_as_double(0x7ff0000000000000ll);
         return;
     }
-    const double term2 = block_sum_f64(W[head * 256 + t] * log((double)(B - S * min((int64_t)t, D))), scratch);
+    const double term2 = block_sum_f64(W[head * 256 + t] * logtab[B - S * min((int64_t)t, D)], scratch);
+    // rows of the head: (batch b, query q) for i = b*Lq + q = t, t + 256, ...; b and q advance
+    // without a division per row
     double z = 0.0;
     const int64_t R = (int64_t)Bt * Lq;
     const int32_t *col = ctab + D * rows_total;
+    const int nB = n * (int)B, iS = (int)S;
+    const int step_b = 256 / Lq, step_q = 256 % Lq;
+    int b = t / Lq, q = t % Lq;
     for (int64_t i = t; i < R; i += 256) {
-        const int64_t row = ((i / Lq) * H + head) * Lq + i % Lq;
-        z += log((double)((int64_t)n * B - S * (int64_t)col[row]));
+        const int64_t row = ((int64_t)b * H + head) * Lq + q;
+        z += logtab[nB - iS * col[row]];
+        b += step_b, q += step_q;
+        if (q >= Lq) q -= Lq, ++b;
     }
     const double term3 = block_sum_f64(z, scratch);
     if (t == 0) objective[(int64_t)head * nc + c] = (K[head] - term2 + term3) / (double)R;
@@ -198,7 +215,7 @@ __global__ __launch_bounds__(256) void calib_argmin_kernel(const double *__restr
 int64_t calibrate_workspace_bytes(int64_t Bt, int64_t H, int64_t Lq)
 {
     const int64_t rows = Bt * H * Lq;
-    return rows * 128 * 4 + rows * 8 + Bt * H * 256 * 8 + H * 256 * 8 + H * 8;
+    return rows * 128 * 4 + rows * 8 + Bt * H * 256 * 8 + H * 256 * 8 + H * 8 + 32768 * 8;
 }
 
 hipError_t launch_calibrate(const int8_t *logits, int Bt, int H, int Lq, int Lk, const double *alpha,
@@ -211,13 +228,15 @@ hipError_t launch_calibrate(const int8_t *logits, int Bt, int H, int Lq, int Lk,
     double *wpart = rowconst + rows;
     double *W = wpart + (int64_t)Bt * H * 256;
     double *K = W + (int64_t)H * 256;
+    double *logtab = K + H;
     AlphaTable at;
     for (int h = 0; h < HCCS_MAX_HEADS; ++h) at.e[h] = h < H ? alpha[h] : 0.0;
     hipLaunchKernelGGL(calib_stats_kernel, dim3(H, Bt), dim3(256), 0, st, logits, Lq, Lk, at, rows, ctab, rowconst,
                        wpart);
     hipLaunchKernelGGL(calib_reduce_kernel, dim3(H), dim3(256), 0, st, wpart, rowconst, Bt, H, Lq, W, K);
+    hipLaunchKernelGGL(calib_logtab_kernel, dim3(128), dim3(256), 0, st, logtab);
     hipLaunchKernelGGL(calib_objective_kernel, dim3(nc, H), dim3(256), 0, st, cand, nc, Bt, H, Lq, Lk, rows, ctab, W,
-                       K, objective);
+                       K, logtab, objective);
     hipLaunchKernelGGL(calib_argmin_kernel, dim3(H), dim3(256), 0, st, objective, nc, best);
     return hipGetLastError();
 }
