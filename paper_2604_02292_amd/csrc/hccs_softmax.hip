@@ -85,6 +85,50 @@ struct RowOutput {
     }
 };
 
+// Stage 1 of a lane's share of a row (Alg. 1, first step): the maximum of its V x DW dwords of
+// int8 bytes; the caller reduces it over the lanes that share the row.
+template <int V, int DW>
+__device__ __forceinline__ int lane_max(const uint32_t (&d)[V][DW])
+{
+    ByteMax bm;
+    bm.init(d[0][0]);
+#pragma unroll
+    for (int c = 1; c < DW; ++c) bm.add(d[0][c]);
+#pragma unroll
+    for (int v = 1; v < V; ++v)
+#pragma unroll
+        for (int c = 0; c < DW; ++c) bm.add(d[v][c]);
+    return bm.result();
+}
+
+// Stage 2: the bytes become their unclamped distances to the row maximum m, and the lane's
+// part of (sum delta - sum |delta - D|) is returned; over a row of `count` slots
+// sum min(delta, D) = (sum delta + count*D - sum |delta - D|) / 2: two byte-SAD accumulations.
+template <int V, int DW>
+__device__ __forceinline__ int lane_distances(uint32_t (&d)[V][DW], int m, int D)
+{
+    const uint32_t D4 = (uint32_t)D * 0x01010101u;
+    const uint32_t neg_base4 = 0u - (uint32_t)(127 - m) * 0x01010101u;
+    uint32_t acc_d = 0, acc_abs = 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int c = 0; c < DW; ++c) {
+            const uint32_t dl = distance4(d[v][c], neg_base4);
+            d[v][c] = dl;
+            acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
+            acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
+        }
+    return (int)acc_d - (int)acc_abs;
+}
+
+// Sum of the clamped distances of the n real elements of a row held in `slots` byte slots: the
+// slots that are not elements hold -128, whose distance m + 128 is taken out again.
+__device__ __forceinline__ int clamped_sum(int t, int slots, int n, uint32_t mu, int D)
+{
+    return (t + slots * D) / 2 - (slots - n) * (int)min(mu, (uint32_t)D);
+}
+
 // ---------------------------------------------------------------------------
 // Register-resident kernel for rows whose length is a multiple of 16.
 //
@@ -150,40 +194,13 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
         }
     }
 
-    const uint32_t D4 = (uint32_t)D * 0x01010101u;
-    const int npad = kPaddedLen - n;   // padding bytes sit at distance m+128
     int tsum[R];                       // sum delta - sum |delta - D| of each batch's row
     uint32_t mu[R];                    // row maximum in offset-binary form
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        // stage 1: row maximum (Alg. 1, first step)
-        ByteMax bm;
-        bm.init(d[j][0][0]);
-#pragma unroll
-        for (int c = 1; c < DW; ++c) bm.add(d[j][0][c]);
-#pragma unroll
-        for (int v = 1; v < V; ++v) {
-#pragma unroll
-            for (int c = 0; c < DW; ++c) bm.add(d[j][v][c]);
-        }
-        const int m = group_max<G>(bm.result());
+        const int m = group_max<G>(lane_max(d[j]));
         mu[j] = (uint32_t)(m + 128);
-
-        // stage 2: unclamped distances; sum of the clamped ones from two byte-SAD
-        // accumulations: sum min(delta, D) = (sum delta + count*D - sum |delta - D|) / 2
-        const uint32_t neg_base4 = 0u - (uint32_t)(127 - m) * 0x01010101u;
-        uint32_t acc_d = 0, acc_abs = 0;
-#pragma unroll
-        for (int v = 0; v < V; ++v) {
-#pragma unroll
-            for (int c = 0; c < DW; ++c) {
-                const uint32_t dl = distance4(d[j][v][c], neg_base4);
-                d[j][v][c] = dl;
-                acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
-                acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
-            }
-        }
-        tsum[j] = group_sum<G>((int)acc_d - (int)acc_abs);
+        tsum[j] = group_sum<G>(lane_distances(d[j], m, D));
     }
 
     // stages 3-5: Z = n*B - S*sum min(delta, D)  (Eq. (3), (5)), reciprocal, normalise.
@@ -191,8 +208,7 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
     // lane i of each quad takes row i % R, so the reciprocal and the row constants are computed
     // once per R rows instead of R times, and come back through quad broadcasts.
     auto row_output = [&](int t, uint32_t mu_) {
-        const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu_, (uint32_t)D);
-        return RowOutput<MODE>((uint32_t)(n * B - S * sum_clamped), B, S, D);
+        return RowOutput<MODE>((uint32_t)(n * B - S * clamped_sum(t, kPaddedLen, n, mu_, D)), B, S, D);
     };
     auto emit = [&](int j, const RowOutput<MODE> &ro) {
         const int row = row0 + j * kRowsPerBatch;
@@ -266,38 +282,17 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
             for (int c = 0; c < DW; ++c) d[v][c] = kPadWord;
         }
     }
-    ByteMax bm;
-    bm.init(d[0][0]);
-#pragma unroll
-    for (int c = 1; c < DW; ++c) bm.add(d[0][c]);
-#pragma unroll
-    for (int v = 1; v < V; ++v)
-#pragma unroll
-        for (int c = 0; c < DW; ++c) bm.add(d[v][c]);
-    int m = group_max<64>(bm.result());
+    int m = group_max<64>(lane_max(d));
     if (lane == 0) red[0][wave] = m;
     __syncthreads();
     m = max(max(red[0][0], red[0][1]), max(red[0][2], red[0][3]));
     const uint32_t mu = (uint32_t)(m + 128);
 
-    const uint32_t D4 = (uint32_t)D * 0x01010101u;
-    const uint32_t neg_base4 = 0u - (uint32_t)(127 - m) * 0x01010101u;
-    uint32_t acc_d = 0, acc_abs = 0;
-#pragma unroll
-    for (int v = 0; v < V; ++v)
-#pragma unroll
-        for (int c = 0; c < DW; ++c) {
-            const uint32_t dl = distance4(d[v][c], neg_base4);
-            d[v][c] = dl;
-            acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
-            acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
-        }
-    int t = group_sum<64>((int)acc_d - (int)acc_abs);
+    int t = group_sum<64>(lane_distances(d, m, D));
     if (lane == 0) red[1][wave] = t;
     __syncthreads();
     t = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
-    const int npad = kPaddedLen - n;
-    const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu, (uint32_t)D);
+    const int sum_clamped = clamped_sum(t, kPaddedLen, n, mu, D);
     const uint32_t Z = (uint32_t)(n * B - S * sum_clamped);
     const RowOutput<MODE> ro(Z, B, S, D);
 #pragma unroll
@@ -454,32 +449,10 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
         }
     }
 
-    ByteMax bm;
-    bm.init(d[0][0]);
-#pragma unroll
-    for (int c = 1; c < DW; ++c) bm.add(d[0][c]);
-#pragma unroll
-    for (int v = 1; v < V; ++v)
-#pragma unroll
-        for (int c = 0; c < DW; ++c) bm.add(d[v][c]);
-    const int m = group_max<G>(bm.result());
+    const int m = group_max<G>(lane_max(d));
     const uint32_t mu = (uint32_t)(m + 128);
-    const uint32_t D4 = (uint32_t)D * 0x01010101u;
-    const uint32_t neg_base4 = 0u - (uint32_t)(127 - m) * 0x01010101u;
-    uint32_t acc_d = 0, acc_abs = 0;
-#pragma unroll
-    for (int v = 0; v < V; ++v)
-#pragma unroll
-        for (int c = 0; c < DW; ++c) {
-            const uint32_t dl = distance4(d[v][c], neg_base4);
-            d[v][c] = dl;
-            acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
-            acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
-        }
-    const int t = group_sum<G>((int)acc_d - (int)acc_abs);
-    const int npad = kPaddedLen - n;
-    const int sum_clamped = (t + kPaddedLen * D) / 2 - npad * (int)min(mu, (uint32_t)D);
-    const RowOutput<MODE> ro((uint32_t)(n * B - S * sum_clamped), B, S, D);
+    const int t = group_sum<G>(lane_distances(d, m, D));
+    const RowOutput<MODE> ro((uint32_t)(n * B - S * clamped_sum(t, kPaddedLen, n, mu, D)), B, S, D);
 
     // own elements of a boundary vector, one at a time
     auto store_elements = [&](uint8_t *dst, const u32x4 &o, int vi) {
