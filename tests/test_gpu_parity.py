@@ -552,3 +552,95 @@ def test_attention_streaming_equals_resident_definition(oracle):
 def test_attention_full_size(oracle):
     w = synth.make_workload("fused_attention")
     check_attention(w["q"], w["k"], w["v"], w["table"], w["requant"], w["band"], oracle, "full")
+
+
+# ---------------------------------------------------------------- seeded random sweeps
+def _random_table(g, H, n, band):
+    """Admissible per-head parameters: mostly the workload recipe, sometimes the corners of the band."""
+    table = synth.head_params(H, n, band, seed=int(g.integers(1 << 30)))
+    cap = (32767 if band == 1 else 255 << 15) // n
+    for h in range(H):
+        kind = int(g.integers(6))
+        if kind == 0 and cap >= 1:                       # largest base the band allows, no slope
+            table[h] = (min(cap, 32767), 0, int(g.integers(0, 128)))
+        elif kind == 1:                                  # smallest admissible floor: n*(B - S*D) >= 256
+            floor = -(-256 // n)
+            S, D = int(g.integers(0, 4)), int(g.integers(0, 128))
+            if floor + S * D <= min(cap, 32767):
+                table[h] = (floor + S * D, S, D)
+    assert binding.validate_params(table, n, band) == (0, -1)
+    return table
+
+
+def test_softmax_random_sweep(oracle):
+    """500 seeded random cases over shapes, lengths, bands, output modes and value mixes."""
+    g = np.random.default_rng(20260427)
+    for case in range(500):
+        Bt, H, Lq = int(g.integers(1, 4)), int(g.integers(1, 7)), int(g.integers(1, 70))
+        pick = int(g.integers(5))
+        if pick == 0:
+            n = 16 * int(g.integers(1, 40))
+        elif pick == 1:
+            n = int(g.integers(1, 300))
+        elif pick == 2:
+            n = 8 * int(g.integers(1, 60))
+        elif pick == 3:
+            n = int(g.integers(300, 5000))
+        else:
+            n = int(g.integers(1, 40))
+        band = int(g.integers(2))
+        if band == 1 and n > 32767 // 2:
+            band = 0
+        mode = int(g.integers(4))
+        if mode & 1 and band != 1:                       # 16-bit output exists under the strict band only
+            mode &= 2
+        table = _random_table(g, H, n, band)
+        x = mixed_logits((Bt, H, Lq, n), seed=int(g.integers(1 << 30)))
+        if g.integers(3) == 0:
+            x = g.integers(-128, 128, size=x.shape, dtype=np.int8)
+        print(f"sweep case {case}: shape={(Bt, H, Lq, n)} band={band} mode={mode}", flush=True)
+        want, rc = oracle.softmax(x, table, band, mode=mode, threads=THREADS)
+        assert rc == 0
+        T, recip = (32767 if mode & 1 else 255), (1 if mode & 2 else 0)
+        got = binding.calibrated_softmax_i8_ex(torch.from_numpy(x).cuda(), table, band, out_scale_T=T,
+                                               reciprocal=recip)
+        torch.cuda.synchronize()
+        got = got.cpu().numpy()
+        if T == 32767:
+            got = got.view(np.uint16)
+        assert np.array_equal(got, want), f"case {case} shape={(Bt, H, Lq, n)} band={band} mode={mode}"
+
+
+def test_attention_random_sweep(oracle):
+    """200 seeded random fused blocks: resident and streaming shapes, both head sizes, every rescale form."""
+    g = np.random.default_rng(20260428)
+    for case in range(200):
+        Bt, H = int(g.integers(1, 3)), int(g.integers(1, 5))
+        d = 64 if g.integers(3) else 128
+        pick = int(g.integers(4))
+        if pick == 0:                                    # resident: square, multiple of 64, d = 64
+            Lq = Lk = 64 * int(g.integers(1, 9))
+            d = 64
+        elif pick == 1:
+            Lq, Lk = int(g.integers(1, 200)), int(g.integers(1, 700))
+        elif pick == 2:
+            Lq, Lk = int(g.integers(1, 100)), int(g.integers(900, 2300))
+        else:
+            Lq, Lk = int(g.integers(1, 40)), 64 * int(g.integers(1, 40))
+        band = int(g.integers(2))
+        if band == 1 and Lk > 4000:
+            band = 0
+        table = _random_table(g, H, Lk, band)
+        full = g.integers(2) == 0
+        lo, hi = (-128, 128) if full else (-64, 64)
+        q = g.integers(lo, hi, size=(Bt, H, Lq, d), dtype=np.int8)
+        k = g.integers(lo, hi, size=(Bt, H, Lk, d), dtype=np.int8)
+        v = g.integers(-128, 128, size=(Bt, H, Lk, d), dtype=np.int8)
+        kind = int(g.integers(3))
+        if kind == 0:
+            rq = np.stack([g.integers(1, 256, H), g.integers(10, 17, H)], 1)
+        elif kind == 1:
+            rq = np.stack([g.integers(1, 4097, H), g.integers(17, 24, H)], 1)
+        else:
+            rq = np.stack([g.integers(2048, 4097, H), g.integers(1, 24, H)], 1)
+        check_attention(q, k, v, table, rq.astype(np.int32), band, oracle, f"sweep {case} Lq={Lq} Lk={Lk} d={d} rq={kind}")
