@@ -138,9 +138,10 @@ HCCS_API int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const i
  *   d = 64 or 128; 1 <= Lk <= HCCS_MAX_ROW_LENGTH; Lq >= 0 (0 is a no-op);
  *   B*H <= 65535.  The row length of HCCS, and of the band check, is n = Lk.
  * Square blocks with d = 64 and Lk a multiple of 64 up to 512 keep a query tile's logits in
- * registers and K, V in LDS; every other shape streams K and V in chunks of 64 keys and
- * recomputes Q.K^T three times (maximum, sum, output), because the floors of HCCS do not allow
- * partial results to be rescaled.  Both are bit-exact to the same definition. */
+ * registers and K, V in LDS; every other shape streams K and V through LDS in chunks.  Up to
+ * 2048 keys a query tile's logits stay in registers as bytes (Q.K^T once, two passes); beyond
+ * that Q.K^T is recomputed three times (maximum, sum, output), because the floors of HCCS do
+ * not allow partial results to be rescaled.  All are bit-exact to the same definition. */
 HCCS_API int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev,
                                   int32_t B, int32_t H, int32_t Lq, int32_t Lk, int32_t d,
                                   const hccs_head_params *table_host, const hccs_requant *requant_host,
