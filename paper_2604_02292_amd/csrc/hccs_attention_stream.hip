@@ -200,8 +200,9 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
             }
             pop[tt] = (int)probabilities_minus_128(s01, s23, rho2);
         }
-        // B operand through the transposing LDS read (see the two-pass kernel below): lane pair j
+        // V operand through the transposing LDS read (see the two-pass kernel below): lane pair j
         // of a 16-lane group points at the key of contraction slot j, the lane receives its column.
+        // The contraction runs transposed, O^T tile = V^T . P^T, with V^T as the first operand.
         // P = (P - 128) + 64 + 64: the offset goes through the matrix unit as well.
         const v4i c64 = {0x40404040, 0x40404040, 0x40404040, 0x40404040};
 #pragma unroll
@@ -211,23 +212,21 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
             const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(at + 32 * KSTR));
             const v4i vop = {lo[0], lo[1], hi[0], hi[1]};
             v4i &acc = oacc[n16 / 4][n16 % 4];
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, pop, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
         }
     });
 
-    // ---- store: lane (g, qi) holds rows 4g .. 4g+3 of column 16*n16 + qi ---------------------
+    // ---- store: the contraction ran transposed (V^T . P^T), so lane (g, qi) holds columns
+    // 16*n16 + 4g .. +3 of query qi: 16 contiguous bytes per lane
     if (active) {
+        const int row = tile * 16 + qi;
+        if (row < Lq) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = tile * 16 + 4 * g + r;
-            if (row < Lq) {
-#pragma unroll
-                for (int n16 = 0; n16 < 4 * ND; ++n16)
-                    __builtin_nontemporal_store(oacc[n16 / 4][n16 % 4][r],
-                                                o + ((size_t)item * Lq + row) * DH + 16 * n16 + qi);
-            }
+            for (int n16 = 0; n16 < 4 * ND; ++n16)
+                __builtin_nontemporal_store(oacc[n16 / 4][n16 % 4],
+                                            (v4i *)(o + ((size_t)item * Lq + row) * DH + 16 * n16 + 4 * g));
         }
     }
 }
@@ -422,7 +421,9 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     for (int cg = 0; cg < ND; ++cg)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) oacc[cg][dt] = (v4i){0, 0, 0, 0};
-    // B operand of the second contraction for lane (g, qi), 64-key group T, columns 16*n16 .. +15:
+    // V operand of the second contraction, which runs transposed (O^T tile = V^T . P^T, so that a
+    // lane ends up with four consecutive columns of one query), for lane (g, qi), 64-key group T,
+    // columns 16*n16 .. +15:
     // contraction slot (tt, r) of lane group g is key 64*T + 16*tt + 4*g + r (that is how pass 1
     // left the logits), and the lane's column is 16*n16 + qi.  ds_read_tr8_b64 takes, in each
     // group of 16 lanes, the 8 bytes at every lane's address, pairs lanes (2j, 2j+1) into eight
@@ -444,9 +445,9 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
                 const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(at + 32 * KSTR));
                 const v4i vop = {lo[0], lo[1], hi[0], hi[1]};
                 v4i &acc = oacc[n16 / 4][n16 % 4];
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(pop, vop, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(c64, vop, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, pop, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
             }
         }
     };
@@ -465,17 +466,15 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     }
     if (tail && active) chunk_pv(lds_k[tail_buf], xt);   // V rows past the end were staged as zero
 
-    // lane (g, qi) holds rows 4g .. 4g+3 of column 16*n16 + qi: 64 contiguous bytes per row and group of 16 lanes
+    // the contraction ran transposed (V^T . P^T), so lane (g, qi) holds columns
+    // 16*n16 + 4g .. +3 of query qi: 16 contiguous bytes per lane
     if (active) {
+        const int row = tile * 16 + qi;
+        if (row < Lq) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = tile * 16 + 4 * g + r;
-            if (row < Lq) {
-#pragma unroll
-                for (int n16 = 0; n16 < 4 * ND; ++n16)
-                    __builtin_nontemporal_store(oacc[n16 / 4][n16 % 4][r],
-                                                o + ((size_t)item * Lq + row) * DH + 16 * n16 + qi);
-            }
+            for (int n16 = 0; n16 < 4 * ND; ++n16)
+                __builtin_nontemporal_store(oacc[n16 / 4][n16 % 4],
+                                            (v4i *)(o + ((size_t)item * Lq + row) * DH + 16 * n16 + 4 * g));
         }
     }
 }
