@@ -602,13 +602,29 @@ def test_softmax_random_sweep(oracle):
         want, rc = oracle.softmax(x, table, band, mode=mode, threads=THREADS)
         assert rc == 0
         T, recip = (32767 if mode & 1 else 255), (1 if mode & 2 else 0)
-        got = binding.calibrated_softmax_i8_ex(torch.from_numpy(x).cuda(), table, band, out_scale_T=T,
-                                               reciprocal=recip)
+        # a third of the cases run on tensors that begin `off` elements behind a 16-byte line (input
+        # and output alike), a few of the 8-bit ones in place
+        off = int(g.integers(1, 16)) if g.integers(3) == 0 else 0
+        in_place = T == 255 and g.integers(8) == 0
+        buf_in = torch.zeros(x.size + 32, dtype=torch.int8, device="cuda")
+        buf_in[off:off + x.size] = torch.from_numpy(x).cuda().view(-1)
+        t_in = buf_in[off:off + x.size].view(x.shape)
+        if in_place:
+            t_out = t_in.view(torch.uint8)
+        else:
+            buf_out = torch.full((x.size + 48,), 0x5A if T == 255 else 0x5A5A,
+                                 dtype=torch.uint8 if T == 255 else torch.int16, device="cuda")
+            lead = 16 + off if T == 255 else 8 + off      # elements: the same offset behind a 16-byte line
+            t_out = buf_out[lead:lead + x.size].view(x.shape)
+        binding.calibrated_softmax_i8_ex(t_in, table, band, out_scale_T=T, reciprocal=recip, out=t_out)
         torch.cuda.synchronize()
-        got = got.cpu().numpy()
+        got = t_out.cpu().numpy()
         if T == 32767:
             got = got.view(np.uint16)
-        assert np.array_equal(got, want), f"case {case} shape={(Bt, H, Lq, n)} band={band} mode={mode}"
+        assert np.array_equal(got, want), f"case {case} shape={(Bt, H, Lq, n)} band={band} mode={mode} off={off}"
+        if not in_place:
+            canary = 0x5A if T == 255 else 0x5A5A
+            assert bool((buf_out[:lead] == canary).all()) and bool((buf_out[lead + x.size:] == canary).all())
 
 
 def test_attention_random_sweep(oracle):
