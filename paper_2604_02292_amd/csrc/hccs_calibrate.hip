@@ -131,9 +131,16 @@ __global__ __launch_bounds__(256) void calib_reduce_kernel(const double *__restr
     double w = 0.0;
     for (int b = 0; b < Bt; ++b) w += wpart[((int64_t)b * H + head) * 256 + t];
     W[head * 256 + t] = w;
+    // rows of the head: (batch b, query q) for i = b*Lq + q = t, t + 256, ...; no division per row
     double k = 0.0;
     const int64_t R = (int64_t)Bt * Lq;
-    for (int64_t i = t; i < R; i += 256) k += rowconst[((i / Lq) * H + head) * Lq + i % Lq];
+    const int step_b = 256 / Lq, step_q = 256 % Lq;
+    int b = t / Lq, q = t % Lq;
+    for (int64_t i = t; i < R; i += 256) {
+        k += rowconst[((int64_t)b * H + head) * Lq + q];
+        b += step_b, q += step_q;
+        if (q >= Lq) q -= Lq, ++b;
+    }
     k = block_sum_f64(k, scratch);
     if (t == 0) K[head] = k;
 }
