@@ -66,6 +66,9 @@ __global__ __launch_bounds__(256) void calib_stats_kernel(const int8_t *__restri
     const int64_t slab = (int64_t)blockIdx.y * gridDim.x + head;
     const double a = alpha.e[head];
     double wacc[4] = {0.0, 0.0, 0.0, 0.0};   // weights of delta = lane + 64*k, summed over this wave's rows
+    double e[4];                             // exp(-alpha*delta) of the lane's four distances: the same for every row
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) e[kk] = exp(-a * (double)(lane + 64 * kk));
 
     for (int q0 = 0; q0 < Lq; q0 += 4) {     // same trip count in every wave
         const int q = q0 + wave;
@@ -87,9 +90,8 @@ __global__ __launch_bounds__(256) void calib_stats_kernel(const int8_t *__restri
             double ce[4], den = 0.0, t1 = 0.0;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                const int delta = lane + 64 * kk;
-                c[kk] = hist[wave][delta];
-                ce[kk] = (double)c[kk] * exp(-a * (double)delta);
+                c[kk] = hist[wave][lane + 64 * kk];
+                ce[kk] = (double)c[kk] * e[kk];
                 den += ce[kk];
             }
             den = wave_sum_f64(den);
