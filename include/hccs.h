@@ -38,7 +38,7 @@ typedef struct {
 
 /* Fixed-point rescale of the fused block's int32 Q.K^T accumulator to an
  * int8 logit:  x = clamp((acc * mult + 2^(shift-1)) >> shift, -128, 127)
- * with a flooring shift (round half up).  1 <= mult <= 4096, 1 <= shift <= 23.
+ * with a flooring shift (round half up).  1 <= mult <= 4096, 1 <= shift <= 24.
  * The paper starts from int8 logits and does not define this step. */
 typedef struct {
     int32_t mult;

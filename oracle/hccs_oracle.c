@@ -29,7 +29,9 @@
  * rational sandwich for the two-step normalisation, invariants (range,
  * monotonicity, sum bounds), closed forms for flat / one-hot rows, brute
  * force over every int8 row of length 2 against an independent big-integer
- * Python version, and an exhaustive check of the reciprocal.
+ * Python version, and an exhaustive check of the reciprocal; the same cases also run
+ * through a build of this file with the address and undefined-behaviour sanitizers
+ * (sanitize_driver.c).
  * The fused block has no definition in the paper: its composition is pinned
  * to the row function and to library matrix products, its requantisation to
  * exact rational rounding.  Parity for the fused block is therefore pinned to
@@ -255,7 +257,9 @@ int hccs_oracle_softmax(const int8_t *logits, void *out, int64_t Bt, int64_t H, 
  *             with a flooring (arithmetic) shift: round half up
  *   p[i][.] = HCCS 8-bit row of x[i][.] with n = Lk and head h's constants
  *   O[i][t] = sum_j p[i][j]*V[j][t]
- * requant holds H pairs (mult, shift), 1 <= mult <= 4096, 1 <= shift <= 23.
+ * requant holds H pairs (mult, shift), 1 <= mult <= 4096, 1 <= shift <= 24 (the largest
+ * product, 2^18 * 2^12 for 64 products of 6-bit magnitudes, still fits 32 bits; here it
+ * is held in 64).
  * This requantisation rule is this repository's definition, not the paper's. */
 int hccs_oracle_attention_i8(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o,
                              int64_t Bt, int64_t H, int64_t Lq, int64_t Lk, int64_t d,
@@ -267,7 +271,7 @@ int hccs_oracle_attention_i8(const int8_t *q, const int8_t *k, const int8_t *v, 
         int rc = hccs_oracle_check_params(table[3 * h], table[3 * h + 1], table[3 * h + 2], Lk, band);
         if (rc != ORACLE_OK) return rc;
         if (requant[2 * h] < 1 || requant[2 * h] > 4096) return ORACLE_E_ARG;
-        if (requant[2 * h + 1] < 1 || requant[2 * h + 1] > 23) return ORACLE_E_ARG;
+        if (requant[2 * h + 1] < 1 || requant[2 * h + 1] > 24) return ORACLE_E_ARG;
     }
     int status = ORACLE_OK;
     if (threads < 1) threads = 1;
@@ -325,7 +329,7 @@ int hccs_oracle_requant_logits(const int8_t *q, const int8_t *k, int8_t *x, int6
     for (int64_t bh = 0; bh < Bt * H; ++bh) {
         const int64_t h = bh % H;
         const int64_t mult = requant[2 * h], shift = requant[2 * h + 1];
-        if (mult < 1 || mult > 4096 || shift < 1 || shift > 23) return ORACLE_E_ARG;
+        if (mult < 1 || mult > 4096 || shift < 1 || shift > 24) return ORACLE_E_ARG;
         const int8_t *Q = q + bh * Lq * d, *K = k + bh * Lk * d;
         for (int64_t i = 0; i < Lq; ++i)
             for (int64_t j = 0; j < Lk; ++j) {

@@ -120,7 +120,7 @@ int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t 
     if (rc != HCCS_OK) return rc;
     for (int h = 0; h < H; ++h) {
         if (requant_host[h].mult < 1 || requant_host[h].mult > 4096) return HCCS_E_REQUANT;
-        if (requant_host[h].shift < 1 || requant_host[h].shift > 23) return HCCS_E_REQUANT;
+        if (requant_host[h].shift < 1 || requant_host[h].shift > 24) return HCCS_E_REQUANT;
     }
     if (B == 0 || Lq == 0) return HCCS_OK;
     if (!q_dev || !k_dev || !v_dev || !o_dev) return HCCS_E_NULL;
@@ -129,7 +129,7 @@ int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t 
     fill_table(table_host, H, tab);
     hccs::RequantTable rq;
     for (int h = 0; h < HCCS_MAX_HEADS; ++h)
-        rq.e[h] = h < H ? make_int2(requant_host[h].mult, requant_host[h].shift) : make_int2(1, 1);
+        rq.e[h] = h < H ? make_int4(requant_host[h].mult, requant_host[h].shift, 0, 0) : make_int4(1, 1, 0, 0);
     // square blocks whose rows fit the register file go to the resident kernel, everything else streams
     const bool resident = d == 64 && Lq == Lk && Lk % 64 == 0 && Lk <= 512;
     const hipError_t e =

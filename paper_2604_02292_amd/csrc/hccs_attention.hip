@@ -120,9 +120,8 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
     const int qi = lane & 15;      // query inside the 16-row tile / output column group
     const int g = lane >> 4;       // which quarter of the contraction slots this lane feeds
     const int round_c = 1 << (shift - 1);
-    // Saturation bound for the accumulator when acc*mult could leave 32 bits: any
-    // |acc| >= lim rescales to a value beyond the int8 range already.
-    const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 20);
+    // saturation bounds for the accumulator when acc*mult could leave 32 bits (from the host)
+    const int lim_lo = requant.e[head].z, lim_hi = requant.e[head].w;
 
     v4i qop = {0, 0, 0, 0};
     if (wave < NT) qop = *(const v4i *)(q + base + (size_t)(wave * 16 + qi) * 64 + g * 16);
@@ -141,7 +140,7 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
                 const v4i kop = *(const v4i *)(lds_k + ((t + 1) * 16 + qi) * kKStride + g * 16);
                 acc_next = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
             }
-            rescale_tile<RQ>(acc, mult, shift, round_c, lim, xp[t][0], xp[t][1]);
+            rescale_tile<RQ>(acc, mult, shift, round_c, lim_lo, lim_hi, xp[t][0], xp[t][1]);
             mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(xp[t][0], xp[t][1]));
             acc = acc_next;
             __builtin_amdgcn_sched_barrier(0);

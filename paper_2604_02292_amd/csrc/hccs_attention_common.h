@@ -46,14 +46,14 @@ enum : int {
 // Rescale of four accumulators of one key tile to two 16-bit logit pairs (before the int8
 // saturation): keys r = 0,1 in the first pair, r = 2,3 in the second.
 template <int RQ>
-__device__ __forceinline__ void rescale_tile(const v4i &acc, int mult, int shift, int round_c, int lim,
-                                             short2_t &p01, short2_t &p23)
+__device__ __forceinline__ void rescale_tile(const v4i &acc, int mult, int shift, int round_c, int lim_lo,
+                                             int lim_hi, short2_t &p01, short2_t &p23)
 {
     int y[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         int a = acc[r];
-        if constexpr (RQ == kRescalePreclamp) a = clamp_i32(a, -lim, lim);
+        if constexpr (RQ == kRescalePreclamp) a = clamp_i32(a, lim_lo, lim_hi);
         y[r] = __mul24(a, mult) + round_c;
     }
     if constexpr (RQ == kRescaleHigh16) {
@@ -115,10 +115,26 @@ __device__ __forceinline__ uint32_t die_major_block(uint32_t linear, uint32_t to
     return die * per + min(die, extra) + slot;
 }
 
+// Saturation bounds for the accumulator of one head (kRescalePreclamp): the smallest a whose
+// rescaled value is already >= 127 and the largest a whose rescaled value is already <= -128.
+// Clamping the accumulator to [lo, hi] therefore changes no logit, and hi*mult + 2^(shift-1)
+// <= 127*2^shift + mult - 1 and lo*mult + 2^(shift-1) >= -127*2^shift - mult stay inside 32 bits
+// for every mult <= 4096 and shift <= 24.  Both are also held within the accumulator's own range
+// (the 24-bit multiply needs |a| < 2^23).
+inline void preclamp_limits(int64_t mult, int64_t shift, int64_t acc_bound, int &lo, int &hi)
+{
+    const int64_t half = (int64_t)1 << (shift - 1), top = (int64_t)127 << shift;
+    const int64_t hi64 = (top - half + mult - 1) / mult;                 // ceil((127*2^shift - half) / mult)
+    const int64_t lo64 = -((top + half + 1 + mult - 1) / mult);          // floor((-127*2^shift - half - 1) / mult)
+    hi = (int)(hi64 < acc_bound ? hi64 : acc_bound);
+    lo = (int)(lo64 > -acc_bound ? lo64 : -acc_bound);
+}
+
 // Picks the cheapest exact rescale form for a set of heads (|acc| <= acc_bound) and rewrites
 // the table for it: every rule as (mult << (16-shift), 16) if that keeps acc*mult + 2^15 (plus
 // `headroom`, for a kernel that adds an offset to the rounding constant) in 32 bits, else
-// multiply-add and shift, with the accumulator saturated first if needed.
+// multiply-add and shift, with the accumulator saturated first if needed (entries z, w of the
+// rewritten table: the bounds of preclamp_limits).
 inline int choose_rescale(const RequantTable &in, int H, int64_t acc_bound, RequantTable &out, int64_t headroom = 0)
 {
     out = in;
@@ -128,8 +144,10 @@ inline int choose_rescale(const RequantTable &in, int H, int64_t acc_bound, Requ
         if (shift > 16 || (acc_bound * (mult << (16 - shift)) + (1 << 15) + headroom) > 0x7fffffffll) high16 = false;
         if (acc_bound * mult + ((int64_t)1 << (shift - 1)) > 0x7fffffffll) preclamp = true;
     }
-    if (high16)
-        for (int h = 0; h < H; ++h) out.e[h] = make_int2(in.e[h].x << (16 - in.e[h].y), 16);
+    for (int h = 0; h < H; ++h) {
+        if (high16) out.e[h].x = in.e[h].x << (16 - in.e[h].y), out.e[h].y = 16;
+        preclamp_limits(in.e[h].x, in.e[h].y, acc_bound, out.e[h].z, out.e[h].w);
+    }
     return high16 ? kRescaleHigh16 : (preclamp ? kRescalePreclamp : kRescaleShift);
 }
 

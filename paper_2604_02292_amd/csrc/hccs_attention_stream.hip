@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     const int B = hp.x, S = hp.y, D = hp.z;
     const int mult = requant.e[head].x, shift = requant.e[head].y;
     const int round_c = 1 << (shift - 1);
-    const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 21);
+    const int lim_lo = requant.e[head].z, lim_hi = requant.e[head].w;   // accumulator saturation bounds
     const int8_t *kb = k + (size_t)item * Lk * DH;
     const int8_t *vb = v + (size_t)item * Lk * DH;
     const int tile = (int)(logical % gridDim.x) * 4 + wave;
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
             const v4i kop = *(const v4i *)(lds_k[buf] + (16 * tt + qi) * KSTR + 64 * kd + 16 * g);
             acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(kop, qop[kd], acc, 0, 0, 0);
         }
-        rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
+        rescale_tile<RQ>(acc, mult, shift, round_c, lim_lo, lim_hi, p01, p23);
     };
 
     // Chunks of 64 whole keys take a branch-free body (the four tiles of a chunk overlap); the one
@@ -273,7 +273,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     const int B = hp.x, S = hp.y, D = hp.z;
     const int mult = requant.e[head].x, shift = requant.e[head].y;
     const int round_c = 1 << (shift - 1);
-    const int lim = min((int)((128ll << shift) / mult) + 1, 1 << 21);
+    const int lim_lo = requant.e[head].z, lim_hi = requant.e[head].w;   // accumulator saturation bounds
     const int8_t *kb = k + (size_t)item * Lk * DH;
     const int8_t *vb = v + (size_t)item * Lk * DH;
     const int tile = (int)(logical % gridDim.x) * 4 + wave;
@@ -342,9 +342,9 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
         // offset rides on the rounding constant (the host has checked the headroom for it)
         short2_t p01, p23;
         if constexpr (RQ == kRescaleHigh16) {
-            rescale_tile<RQ>(acc, mult, shift, round_c + (128 << 16), lim, p01, p23);
+            rescale_tile<RQ>(acc, mult, shift, round_c + (128 << 16), lim_lo, lim_hi, p01, p23);
         } else {
-            rescale_tile<RQ>(acc, mult, shift, round_c, lim, p01, p23);
+            rescale_tile<RQ>(acc, mult, shift, round_c, lim_lo, lim_hi, p01, p23);
             const short2_t c128 = {128, 128};
             p01 = __builtin_elementwise_add_sat(p01, c128);
             p23 = __builtin_elementwise_add_sat(p23, c128);

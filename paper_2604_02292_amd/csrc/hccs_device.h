@@ -20,8 +20,9 @@ struct HeadTable {
     int4 e[HCCS_MAX_HEADS];
 };
 
+// Rescale rule of the fused block per head: (mult, shift, accumulator saturation bounds lo, hi).
 struct RequantTable {
-    int2 e[HCCS_MAX_HEADS];
+    int4 e[HCCS_MAX_HEADS];
 };
 
 // 16 bytes of a row, as the hardware moves them (global_load/store_dwordx4).

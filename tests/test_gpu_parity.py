@@ -486,8 +486,9 @@ def test_attention_full_range_inputs_and_large_multiplier(oracle):
     table = np.array([[30000, 127, 127], [65280, 0, 0], [20000, 100, 127], [255, 1, 127]], np.int32)
     table[1] = [32767, 127, 100]
     assert binding.validate_params(table, 128, 0) == (0, -1)
-    rq = np.array([[4096, 23], [4096, 12], [1, 1], [2047, 16]], np.int32)
-    check_attention(q, k, v, table, rq, 0, oracle, "extremes")
+    for rq in ([[4096, 23], [4096, 12], [1, 1], [2047, 16]],
+               [[4096, 24], [1, 24], [4095, 24], [3000, 22]]):   # the top of the shift range
+        check_attention(q, k, v, table, np.array(rq, np.int32), 0, oracle, f"extremes {rq}")
 
 
 def rect_qkv(seed, Bt, H, Lq, Lk, d, lo=-64, hi=63):
@@ -533,7 +534,8 @@ def test_attention_streaming_rescale_kinds_and_extremes(oracle):
     assert binding.validate_params(table, Lk, 0) == (0, -1)
     for rq in ([[100, 16], [7, 12], [255, 16]],          # high-half form
                [[100, 17], [900, 20], [3, 2]],           # shift form
-               [[4096, 23], [4096, 12], [2047, 16]]):    # accumulator saturation needed
+               [[4096, 23], [4096, 12], [2047, 16]],     # accumulator saturation needed
+               [[4096, 24], [1, 24], [2049, 24]]):       # the top of the shift range
         check_attention(q, k, v, table, np.array(rq, np.int32), 0, oracle, f"rescale {rq}")
 
 
@@ -656,7 +658,7 @@ def test_attention_random_sweep(oracle):
         if kind == 0:
             rq = np.stack([g.integers(1, 256, H), g.integers(10, 17, H)], 1)
         elif kind == 1:
-            rq = np.stack([g.integers(1, 4097, H), g.integers(17, 24, H)], 1)
+            rq = np.stack([g.integers(1, 4097, H), g.integers(17, 25, H)], 1)
         else:
-            rq = np.stack([g.integers(2048, 4097, H), g.integers(1, 24, H)], 1)
+            rq = np.stack([g.integers(2048, 4097, H), g.integers(1, 25, H)], 1)
         check_attention(q, k, v, table, rq.astype(np.int32), band, oracle, f"sweep {case} Lq={Lq} Lk={Lk} d={d} rq={kind}")

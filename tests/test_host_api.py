@@ -138,7 +138,7 @@ def test_attention_rejections_launch_nothing(lib):
     assert call(q=4100) == -3
     assert call(T=32767) == -4
     assert call(rq_=binding.requant_table([[4097, 16]])[0]) == -9
-    assert call(rq_=binding.requant_table([[128, 24]])[0]) == -9
+    assert call(rq_=binding.requant_table([[128, 25]])[0]) == -9
     assert call(rq_=binding.requant_table([[128, 0]])[0]) == -9
     assert call(tab=binding.head_table([[128, 1, 126]])[0]) == -7
     assert call(B=0, q=0, k=0, v=0, o=0) == 0

@@ -36,7 +36,7 @@ def test_hand_worked_block(oracle):
     assert [r[0] for r in o_py] == g["o"]
 
 
-@pytest.mark.parametrize("mult,shift", [(1, 1), (97, 16), (256, 16), (4096, 12), (4096, 23), (3, 2)])
+@pytest.mark.parametrize("mult,shift", [(1, 1), (97, 16), (256, 16), (4096, 12), (4096, 23), (4096, 24), (1, 24), (3, 2)])
 def test_requant_is_round_half_up_of_the_exact_ratio(oracle, mult, shift):
     q, k, _ = _qkv(shift * 7 + mult, (1, 2, 24, 64), -128, 127)
     rq = np.array([[mult, shift]] * 2, np.int32)
