@@ -13,8 +13,18 @@
  *   - Per-head constants travel by value in the kernel arguments, so the host
  *     table may be freed as soon as the call returns.
  *   - All checks run on the host before anything is launched.  A call that
- *     returns non-zero has launched nothing and has not touched its outputs.
+ *     returns any status other than HCCS_OK or HCCS_E_HIP has launched nothing
+ *     and has not touched its outputs.  HCCS_E_HIP is what the runtime answered
+ *     to one of the call's own launches (an error left over from an earlier,
+ *     unrelated runtime call is not reported here); an entry point that enqueues
+ *     several kernels (hccs_calibrate_grid) may then have enqueued the earlier
+ *     ones, and its outputs are undefined.
  *   - Return value: HCCS_OK (0) or a negative hccs_status.
+ *   - Sizes: B*H*Lq (the number of rows) must stay below 2^31.
+ *
+ * Entry points that exist for tests and benchmarks only (the reciprocal and
+ * normalise stages on their own, a copy kernel, a float32 comparison softmax)
+ * are declared in hccs_testing.h.
  */
 #ifndef HCCS_H
 #define HCCS_H
@@ -89,7 +99,7 @@ HCCS_API int hccs_validate_params(const hccs_head_params *table_host, int32_t H,
  *   probs_dev   same shape, uint8 in [0,255]; may be the same buffer as
  *               logits_dev (in place) but must not partially overlap it.
  *   B,H,Lq      >= 0 for B and Lq (an empty tensor is a no-op), 1 <= H <= HCCS_MAX_HEADS,
- *               B <= 65535.
+ *               B*H*Lq < 2^31.
  *   Lk          1..HCCS_MAX_ROW_LENGTH.  With 16-byte aligned base pointers every length up
  *               to 16352 (and multiples of 16 beyond) takes the vectorised kernels, fastest
  *               for multiples of 16.  So do tensors that begin inside a 16-byte line when
@@ -136,7 +146,7 @@ HCCS_API int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const i
 /* The same block with separate query and key lengths:
  *   q_dev [B,H,Lq,d], k_dev and v_dev [B,H,Lk,d] int8, o_dev [B,H,Lq,d] int32, all 16-byte aligned.
  *   d = 64 or 128; 1 <= Lk <= HCCS_MAX_ROW_LENGTH; Lq >= 0 (0 is a no-op);
- *   B*H <= 65535.  The row length of HCCS, and of the band check, is n = Lk.
+ *   B*H*Lq < 2^31.  The row length of HCCS, and of the band check, is n = Lk.
  * Square blocks with d = 64 and Lk a multiple of 64 up to 512 keep a query tile's logits in
  * registers and K, V in LDS; every other shape streams K and V through LDS in chunks.  Up to
  * 2048 keys a query tile's logits stay in registers as bytes (Q.K^T once, two passes); beyond
@@ -164,31 +174,6 @@ HCCS_API int hccs_calibrate_grid(const int8_t *logits_dev, int32_t B, int32_t H,
                                  const double *alpha_host, const hccs_head_params *candidates_dev,
                                  int32_t n_candidates, double *objective_dev, int32_t *best_dev,
                                  void *workspace_dev, int64_t workspace_bytes, void *hip_stream);
-
-/* Comparison kernel for benchmarks only (never parity-checked): exact-exponential
- * float32 softmax of the same int8 logits, out = rint(255 * softmax(scale_h * x)),
- * same traffic (1 byte in, 1 byte out per element).  scale_host: H floats.
- * Requires Lk a multiple of 16, Lk <= 16384, 16-byte aligned pointers. */
-HCCS_API int hccs_exp_softmax_i8_f32(const int8_t *logits_dev, uint8_t *probs_dev, int32_t B, int32_t H,
-                            int32_t Lq, int32_t Lk, const float *scale_host, void *hip_stream);
-
-/* Test hook: runs the kernels' reciprocal routine, rho = floor(255*2^15 / Z),
- * over an array.  z_dev, rho_dev: count uint32 values on the device, every
- * Z in [256, 255*2^15] (the range the admissibility band guarantees).  Lets
- * the exhaustive check of Eq. (8) reach the GPU code. */
-HCCS_API int hccs_reciprocal_u8(const uint32_t *z_dev, uint32_t *rho_dev, int64_t count, void *hip_stream);
-
-/* Test hook: the kernels' normalise stage alone.  bsdz_dev: count quadruples (B, S, Dmax, Z) of
- * int32 on the device (16-byte aligned), each with 0 <= S*Dmax <= B <= Z and 256 <= Z <= 255*2^15,
- * which is what a row under either band produces.  out_dev: count*256 bytes, entry i holding
- * ((B - S*min(delta, Dmax)) * floor(255*2^15 / Z)) >> 15 for delta = 0..255.  Lets a sweep over the
- * constants reach the exact-float arithmetic of the 8-bit path directly. */
-HCCS_API int hccs_normalise_table_u8(const int32_t *bsdz_dev, uint8_t *out_dev, int64_t count, void *hip_stream);
-
-/* Plain device-to-device copy kernel (uint4 per lane), used to scale hardware
- * byte counters and as the streaming reference point in benchmarks.
- * bytes must be a multiple of 16; pointers 16-byte aligned. */
-HCCS_API int hccs_copy_bytes(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream);
 
 /* Static description of a status code. */
 HCCS_API const char *hccs_status_string(int status);

@@ -135,7 +135,8 @@ def calibrated_softmax_i8_ex(logits, table, band, out_scale_T=255, reciprocal=RE
     dtype = torch.uint8 if out_scale_T == 255 else torch.int16
     if out is None:
         out = torch.empty(logits.shape, dtype=dtype, device=logits.device)
-    assert out.is_cuda and out.is_contiguous() and out.shape == logits.shape
+    assert out.is_cuda and out.dtype == dtype and out.is_contiguous() and out.shape == logits.shape
+    assert out.device == logits.device
     B, H, Lq, Lk = logits.shape
     arr, Ht = head_table(table)
     if Ht != H:
@@ -168,8 +169,19 @@ def prepare_softmax(logits, out, table, band, out_scale_T=255):
     return launch
 
 
+def _check_attention_tensors(q, k, v, out):
+    import torch
+    for t in (q, k, v):
+        assert t.is_cuda and t.dtype == torch.int8 and t.is_contiguous() and t.dim() == 4 and t.device == q.device
+    assert k.shape == v.shape and q.shape[:2] == k.shape[:2] and q.shape[3] == k.shape[3]
+    assert out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and out.shape == q.shape
+    assert out.device == q.device
+
+
 def prepare_attention(q, k, v, out, table, requant, band, out_scale_T=255):
-    """Same as prepare_softmax for hccs_attention_i8."""
+    """Same as prepare_softmax for hccs_attention_i8 (square blocks: Lq = Lk)."""
+    _check_attention_tensors(q, k, v, out)
+    assert q.shape == k.shape, "prepare_attention takes square blocks; use attention_i8 for Lq != Lk"
     B, H, L, d = q.shape
     arr, Ht = head_table(table)
     rq, Hr = requant_table(requant)
@@ -191,12 +203,9 @@ def attention_i8(q, k, v, table, requant, band, out=None, out_scale_T=255, strea
     """q: int8 CUDA [B,H,Lq,d]; k, v: int8 CUDA [B,H,Lk,d].  Returns O int32 [B,H,Lq,d].
     Square inputs go through hccs_attention_i8, others through hccs_attention_i8_ex."""
     import torch
-    for t in (q, k, v):
-        assert t.is_cuda and t.dtype == torch.int8 and t.is_contiguous() and t.dim() == 4
-    assert k.shape == v.shape and q.shape[:2] == k.shape[:2] and q.shape[3] == k.shape[3]
     if out is None:
         out = torch.empty(q.shape, dtype=torch.int32, device=q.device)
-    assert out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and out.shape == q.shape
+    _check_attention_tensors(q, k, v, out)
     B, H, Lq, d = q.shape
     Lk = k.shape[2]
     arr, Ht = head_table(table)
@@ -220,21 +229,29 @@ def calibrate_grid(logits, alpha, candidates, stream=None):
     import torch
     assert logits.is_cuda and logits.dtype == torch.int8 and logits.is_contiguous() and logits.dim() == 4
     B, H, Lq, Lk = logits.shape
+    assert len(alpha) == H
     cand = np.zeros((len(candidates), 4), dtype=np.int32)
     cand[:, :3] = np.asarray(candidates, dtype=np.int64).reshape(-1, 3).clip(-2**31, 2**31 - 1)
-    cand_dev = torch.from_numpy(cand).to(logits.device)
     nc = cand.shape[0]
     need = lib().hccs_calibrate_workspace_bytes(B, H, Lq, Lk)
     if need < 0:
         _check(int(need))
-    work = torch.empty(need // 8 + 1, dtype=torch.float64, device=logits.device)
-    obj = torch.empty((H, nc), dtype=torch.float64, device=logits.device)
-    best = torch.empty(H, dtype=torch.int32, device=logits.device)
+    if stream is None:
+        stream = torch.cuda.current_stream(logits.device)
+    # the temporaries are allocated, filled and used on `stream`, and told to the allocator as in use
+    # there, so that freeing them on return cannot hand their memory out while the kernels still run
+    with torch.cuda.stream(stream):
+        cand_dev = torch.from_numpy(cand).to(logits.device)
+        work = torch.empty(need // 8 + 1, dtype=torch.float64, device=logits.device)
+        obj = torch.empty((H, nc), dtype=torch.float64, device=logits.device)
+        best = torch.empty(H, dtype=torch.int32, device=logits.device)
     al = (ctypes.c_double * H)(*[float(a) for a in alpha])
     _check(lib().hccs_calibrate_grid(ctypes.c_void_p(logits.data_ptr()), B, H, Lq, Lk, al,
                                      ctypes.c_void_p(cand_dev.data_ptr()), nc, ctypes.c_void_p(obj.data_ptr()),
                                      ctypes.c_void_p(best.data_ptr()), ctypes.c_void_p(work.data_ptr()),
                                      work.numel() * 8, _stream_handle(stream)))
+    for t in (cand_dev, work):
+        t.record_stream(stream)
     return obj, best
 
 
@@ -244,7 +261,9 @@ def exp_softmax_i8_f32(logits, scale, out=None, stream=None):
     assert logits.is_cuda and logits.dtype == torch.int8 and logits.is_contiguous() and logits.dim() == 4
     if out is None:
         out = torch.empty(logits.shape, dtype=torch.uint8, device=logits.device)
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous() and out.shape == logits.shape
     B, H, Lq, Lk = logits.shape
+    assert len(scale) == H
     sc = (ctypes.c_float * H)(*[float(s) for s in scale])
     _check(lib().hccs_exp_softmax_i8_f32(ctypes.c_void_p(logits.data_ptr()), ctypes.c_void_p(out.data_ptr()),
                                          B, H, Lq, Lk, sc, _stream_handle(stream)))
@@ -257,6 +276,7 @@ def reciprocal_u8(z, out=None, stream=None):
     assert z.is_cuda and z.dtype == torch.int32 and z.is_contiguous()
     if out is None:
         out = torch.empty_like(z)
+    assert out.is_cuda and out.dtype == torch.int32 and out.is_contiguous() and out.numel() == z.numel()
     _check(lib().hccs_reciprocal_u8(ctypes.c_void_p(z.data_ptr()), ctypes.c_void_p(out.data_ptr()),
                                     z.numel(), _stream_handle(stream)))
     return out

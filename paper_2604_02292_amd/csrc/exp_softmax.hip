@@ -87,17 +87,16 @@ __global__ __launch_bounds__(256) void exp_softmax_kernel(const int8_t *__restri
 }
 
 template <int G, int V>
-static hipError_t launch_exp(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int n16, const ScaleTable &sc,
+static hipError_t launch_exp(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int n16, const ScaleTable &sc,
                              hipStream_t st)
 {
     constexpr int kRowsPerBlock = 4 * (64 / G);
     dim3 grid;
     const BlockPlace place = place_blocks((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt, grid);
-    hipLaunchKernelGGL((exp_softmax_kernel<G, V>), grid, dim3(256), 0, st, x, p, Lq, n16, place, sc);
-    return hipGetLastError();
+    return launch(exp_softmax_kernel<G, V>, grid, dim3(256), st, x, p, Lq, n16, place, sc);
 }
 
-hipError_t launch_exp_softmax(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const float *scale,
+hipError_t launch_exp_softmax(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const float *scale,
                               hipStream_t st)
 {
     ScaleTable sc;

@@ -1,25 +1,26 @@
-// C ABI of the library (see include/hccs.h): argument checks, the admissibility
-// test of Sec. IV-C, and hand-off to the kernel launchers.  Host code only.
+// C ABI of the library (see include/hccs.h and include/hccs_testing.h): argument checks, the
+// admissibility test of Sec. IV-C, and hand-off to the kernel launchers.  Host code only.
 #include <hip/hip_runtime.h>
 
 #include "hccs_device.h"
+#include "../../include/hccs_testing.h"
 
 namespace hccs {
-hipError_t launch_softmax(const int8_t *x, void *out, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
+hipError_t launch_softmax(const int8_t *x, void *out, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
                           int mode, bool vector_ok, hipStream_t st);
 hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hipStream_t st);
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
 hipError_t launch_normalise_table(const int32_t *bsdz, uint8_t *out, int64_t count, hipStream_t st);
-hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
+hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H, int L,
                             int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st);
-hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H,
+hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H,
                                    int Lq, int Lk, int d, const HeadTable &tab, const RequantTable &rq,
                                    hipStream_t st);
 int64_t calibrate_workspace_bytes(int64_t Bt, int64_t H, int64_t Lq);
 hipError_t launch_calibrate(const int8_t *logits, int Bt, int H, int Lq, int Lk, const double *alpha,
                             const hccs_head_params *cand, int nc, double *objective, int32_t *best, void *workspace,
                             hipStream_t st);
-hipError_t launch_exp_softmax(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const float *scale,
+hipError_t launch_exp_softmax(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const float *scale,
                               hipStream_t st);
 }  // namespace hccs
 
@@ -40,6 +41,9 @@ int check_head(const hccs_head_params &hp, int64_t n, int band)
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+// rows = B*H*Lq must stay below 2^31: row and block numbers are 32-bit in the kernels
+bool rows_fit(int64_t B, int64_t H, int64_t Lq) { return B * H * Lq < ((int64_t)1 << 31); }
 
 int fill_table(const hccs_head_params *table_host, int H, hccs::HeadTable &out)
 {
@@ -74,7 +78,7 @@ int hccs_calibrated_softmax_i8_ex(const int8_t *logits_dev, void *out_dev, int32
                                   int32_t reciprocal, int32_t band, void *hip_stream)
 {
     if (!table_host) return HCCS_E_NULL;
-    if (B < 0 || B > 65535 || H < 1 || H > HCCS_MAX_HEADS || Lq < 0 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH)
+    if (B < 0 || H < 1 || H > HCCS_MAX_HEADS || Lq < 0 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH || !rows_fit(B, H, Lq))
         return HCCS_E_SHAPE;
     if (out_scale_T != 255 && out_scale_T != 32767) return HCCS_E_SCALE;
     if (reciprocal != HCCS_RECIP_EXACT && reciprocal != HCCS_RECIP_CLB) return HCCS_E_SCALE;
@@ -113,8 +117,9 @@ int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t 
                          const hccs_requant *requant_host, int32_t out_scale_T, int32_t band, void *hip_stream)
 {
     if (!table_host || !requant_host) return HCCS_E_NULL;
-    if (B < 0 || H < 1 || H > HCCS_MAX_HEADS || (int64_t)B * H > 65535) return HCCS_E_SHAPE;
+    if (B < 0 || H < 1 || H > HCCS_MAX_HEADS) return HCCS_E_SHAPE;
     if ((d != 64 && d != 128) || Lq < 0 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH) return HCCS_E_SHAPE;
+    if (!rows_fit(B, H, Lq > 0 ? Lq : 1)) return HCCS_E_SHAPE;
     if (out_scale_T != 255) return HCCS_E_SCALE;
     const int rc = hccs_validate_params(table_host, H, Lk, band, nullptr);
     if (rc != HCCS_OK) return rc;
@@ -149,7 +154,7 @@ int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_
 
 int64_t hccs_calibrate_workspace_bytes(int32_t B, int32_t H, int32_t Lq, int32_t Lk)
 {
-    if (B < 1 || B > 65535 || H < 1 || H > HCCS_MAX_HEADS || Lq < 1 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH)
+    if (B < 1 || H < 1 || H > HCCS_MAX_HEADS || Lq < 1 || Lk < 1 || Lk > HCCS_MAX_ROW_LENGTH || !rows_fit(B, H, Lq))
         return HCCS_E_SHAPE;
     return hccs::calibrate_workspace_bytes(B, H, Lq);
 }
@@ -179,7 +184,7 @@ int hccs_exp_softmax_i8_f32(const int8_t *logits_dev, uint8_t *probs_dev, int32_
                             int32_t Lk, const float *scale_host, void *hip_stream)
 {
     if (!scale_host) return HCCS_E_NULL;
-    if (B < 0 || B > 65535 || H < 1 || H > HCCS_MAX_HEADS || Lq < 0 || Lk < 16 || Lk > 16384 || Lk % 16 != 0)
+    if (B < 0 || H < 1 || H > HCCS_MAX_HEADS || Lq < 0 || Lk < 16 || Lk > 16384 || Lk % 16 != 0 || !rows_fit(B, H, Lq))
         return HCCS_E_SHAPE;
     if (B == 0 || Lq == 0) return HCCS_OK;
     if (!logits_dev || !probs_dev) return HCCS_E_NULL;

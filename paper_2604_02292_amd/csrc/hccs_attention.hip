@@ -211,30 +211,26 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
 }
 
 template <int NT>
-static hipError_t launch_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int blocks, int H,
+static hipError_t launch_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t blocks, int H,
                             const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
 {
     // eight waves per block (two per SIMD) when there are at least eight query tiles
     constexpr int WAVES = NT >= 8 ? 8 : 4;
+    const dim3 grid((uint32_t)blocks), block(64 * WAVES);
     if (kind == kRescaleHigh16)
-        hipLaunchKernelGGL((hccs_attention_kernel<NT, kRescaleHigh16, WAVES>), dim3(blocks), dim3(64 * WAVES), 0, st,
-                           q, k, v, o, H, tab, rq);
-    else if (kind == kRescaleShift)
-        hipLaunchKernelGGL((hccs_attention_kernel<NT, kRescaleShift, WAVES>), dim3(blocks), dim3(64 * WAVES), 0, st,
-                           q, k, v, o, H, tab, rq);
-    else
-        hipLaunchKernelGGL((hccs_attention_kernel<NT, kRescalePreclamp, WAVES>), dim3(blocks), dim3(64 * WAVES), 0,
-                           st, q, k, v, o, H, tab, rq);
-    return hipGetLastError();
+        return launch(hccs_attention_kernel<NT, kRescaleHigh16, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
+    if (kind == kRescaleShift)
+        return launch(hccs_attention_kernel<NT, kRescaleShift, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
+    return launch(hccs_attention_kernel<NT, kRescalePreclamp, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
 }
 
-hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H, int L,
+hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H, int L,
                             int d, const HeadTable &tab, const RequantTable &rq_in, hipStream_t st)
 {
     (void)d;   // 64, checked by the caller
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
-    const int blocks = Bt * H;
+    const int64_t blocks = Bt * H;
     switch (L / 16) {
         case 4: return launch_nt<4>(q, k, v, o, blocks, H, tab, rq, kind, st);
         case 8: return launch_nt<8>(q, k, v, o, blocks, H, tab, rq, kind, st);

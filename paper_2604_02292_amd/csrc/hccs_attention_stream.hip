@@ -6,26 +6,25 @@
 // three times: pass A finds the maximum, pass B the sum Z, pass C the probabilities and
 // O = P.V.  Same arithmetic per element as the resident kernel (hccs_attention_common.h).
 //
-// Grid (query tiles of 64, batch*head), block numbers remapped so that the tiles of one
-// (batch, head) share a die's L2; a wave owns 16 queries.  A chunk is double-buffered: the
+// One block per (query tile of 64, batch*head) on a one-dimensional grid, block numbers remapped
+// so that the tiles of one (batch, head) share a die's L2; a wave owns 16 queries.  A chunk is double-buffered: the
 // global loads of chunk c+1 are issued before chunk c is computed and written to the other LDS
 // buffer afterwards, one barrier per chunk.  K and V are both staged row-major with padded
 // rows; V's operands are formed by the transposing LDS read.
 #include "hccs_attention_common.h"
 #include <type_traits>
 
-#ifndef HCCS_GPC
-#define HCCS_GPC 2
-#endif
-
 namespace hccs {
+
+constexpr int kGroupsPerChunk = 2;   // the two-pass kernel stages 128 keys per chunk
 
 template <int ND, int RQ>   // head size d = 64*ND
 __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t *__restrict__ q,
                                                                     const int8_t *__restrict__ k,
                                                                     const int8_t *__restrict__ v,
                                                                     int32_t *__restrict__ o, int H, int Lq, int Lk,
-                                                                    HeadTable table, RequantTable requant)
+                                                                    uint32_t qtiles, HeadTable table,
+                                                                    RequantTable requant)
 {
     constexpr int DH = 64 * ND;          // head size
     constexpr int KSTR = DH + 16;        // padded K row in LDS (bank spread)
@@ -36,8 +35,8 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
     // logical block number: all query tiles of an item on one die, so its K and V stay in that L2
-    const uint32_t logical = die_major_block(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
-    const int item = (int)(logical / gridDim.x);
+    const uint32_t logical = die_major_block(blockIdx.x, gridDim.x);
+    const int item = (int)(logical / qtiles);
     const int head = item % H;
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
@@ -46,7 +45,7 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     const int lim_lo = requant.e[head].z, lim_hi = requant.e[head].w;   // accumulator saturation bounds
     const int8_t *kb = k + (size_t)item * Lk * DH;
     const int8_t *vb = v + (size_t)item * Lk * DH;
-    const int tile = (int)(logical % gridDim.x) * 4 + wave;
+    const int tile = (int)(logical % qtiles) * 4 + wave;
     const bool active = tile * 16 < Lq;      // a wave without queries still stages and synchronises
     const int nchunks = (Lk + 63) / 64;
 
@@ -251,7 +250,7 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 template <int NCMAX, int ND, int RQ, int GPC>
 __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_stream2_kernel(
     const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v,
-    int32_t *__restrict__ o, int H, int Lq, int Lk, HeadTable table, RequantTable requant)
+    int32_t *__restrict__ o, int H, int Lq, int Lk, uint32_t qtiles, HeadTable table, RequantTable requant)
 {
     constexpr int DH = 64 * ND;
     constexpr int KSTR = DH + 16;
@@ -266,8 +265,8 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
     // logical block number: all query tiles of an item on one die, so its K and V stay in that L2
-    const uint32_t logical = die_major_block(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
-    const int item = (int)(logical / gridDim.x);
+    const uint32_t logical = die_major_block(blockIdx.x, gridDim.x);
+    const int item = (int)(logical / qtiles);
     const int head = item % H;
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
@@ -276,7 +275,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     const int lim_lo = requant.e[head].z, lim_hi = requant.e[head].w;   // accumulator saturation bounds
     const int8_t *kb = k + (size_t)item * Lk * DH;
     const int8_t *vb = v + (size_t)item * Lk * DH;
-    const int tile = (int)(logical % gridDim.x) * 4 + wave;
+    const int tile = (int)(logical % qtiles) * 4 + wave;
     const bool active = tile * 16 < Lq;
     const int nfull = Lk / CK;
     const bool tail = (Lk % CK) != 0;
@@ -480,57 +479,55 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
 }
 
 template <int NCMAX, int ND, int GPC>
-static hipError_t launch_stream2(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int items, int H,
+static hipError_t launch_stream2(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
                                  int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
                                  hipStream_t st)
 {
-    const dim3 grid((Lq + 63) / 64, items), block(256);
+    const uint32_t qtiles = (uint32_t)((Lq + 63) / 64);
+    const dim3 grid((uint32_t)(qtiles * items)), block(256);
     if (kind == kRescaleHigh16)
-        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16, GPC>), grid, block, 0, st, q, k, v, o,
-                           H, Lq, Lk, tab, rq);
-    else if (kind == kRescaleShift)
-        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift, GPC>), grid, block, 0, st, q, k, v, o,
-                           H, Lq, Lk, tab, rq);
-    else
-        hipLaunchKernelGGL((hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp, GPC>), grid, block, 0, st, q, k, v,
-                           o, H, Lq, Lk, tab, rq);
-    return hipGetLastError();
+        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16, GPC>, grid, block, st, q, k, v, o, H, Lq,
+                      Lk, qtiles, tab, rq);
+    if (kind == kRescaleShift)
+        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift, GPC>, grid, block, st, q, k, v, o, H, Lq,
+                      Lk, qtiles, tab, rq);
+    return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp, GPC>, grid, block, st, q, k, v, o, H, Lq,
+                  Lk, qtiles, tab, rq);
 }
 
 template <int ND>
-static hipError_t launch_stream_nd(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int items, int H,
+static hipError_t launch_stream_nd(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
                                    int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
                                    hipStream_t st)
 {
-    const dim3 grid((Lq + 63) / 64, items), block(256);
+    const uint32_t qtiles = (uint32_t)((Lq + 63) / 64);
+    const dim3 grid((uint32_t)(qtiles * items)), block(256);
     if (kind == kRescaleHigh16)
-        hipLaunchKernelGGL((hccs_attention_stream_kernel<ND, kRescaleHigh16>), grid, block, 0, st, q, k, v, o, H, Lq,
-                           Lk, tab, rq);
-    else if (kind == kRescaleShift)
-        hipLaunchKernelGGL((hccs_attention_stream_kernel<ND, kRescaleShift>), grid, block, 0, st, q, k, v, o, H, Lq,
-                           Lk, tab, rq);
-    else
-        hipLaunchKernelGGL((hccs_attention_stream_kernel<ND, kRescalePreclamp>), grid, block, 0, st, q, k, v, o, H,
-                           Lq, Lk, tab, rq);
-    return hipGetLastError();
+        return launch(hccs_attention_stream_kernel<ND, kRescaleHigh16>, grid, block, st, q, k, v, o, H, Lq, Lk, qtiles,
+                      tab, rq);
+    if (kind == kRescaleShift)
+        return launch(hccs_attention_stream_kernel<ND, kRescaleShift>, grid, block, st, q, k, v, o, H, Lq, Lk, qtiles,
+                      tab, rq);
+    return launch(hccs_attention_stream_kernel<ND, kRescalePreclamp>, grid, block, st, q, k, v, o, H, Lq, Lk, qtiles,
+                  tab, rq);
 }
 
-hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int Bt, int H,
+hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H,
                                    int Lq, int Lk, int d, const HeadTable &tab, const RequantTable &rq_in,
                                    hipStream_t st)
 {
     RequantTable rq;
     // |acc| <= d*128*128; the two-pass kernel adds 128 << 16 to the rounding constant
     const int kind = choose_rescale(rq_in, H, (int64_t)d << 14, rq, Lk <= 2048 ? (int64_t)128 << 16 : 0);
-    const int items = Bt * H;
+    const int64_t items = Bt * H;
     if (d != 64 && d != 128) return hipErrorInvalidValue;
     // up to 2048 keys a query tile's logits fit its registers as bytes: Q.K^T once, two passes
     if (Lk <= 1024)
-        return d == 64 ? launch_stream2<16, 1, HCCS_GPC>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-                       : launch_stream2<16, 2, HCCS_GPC>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+        return d == 64 ? launch_stream2<16, 1, kGroupsPerChunk>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                       : launch_stream2<16, 2, kGroupsPerChunk>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
     if (Lk <= 2048)
-        return d == 64 ? launch_stream2<32, 1, HCCS_GPC>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-                       : launch_stream2<32, 2, HCCS_GPC>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+        return d == 64 ? launch_stream2<32, 1, kGroupsPerChunk>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                       : launch_stream2<32, 2, kGroupsPerChunk>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
     return d == 64 ? launch_stream_nd<1>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
                    : launch_stream_nd<2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
 }

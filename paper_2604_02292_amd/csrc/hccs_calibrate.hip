@@ -54,7 +54,7 @@ __device__ __forceinline__ double block_sum_f64(double v, double *scratch4)
 
 // Pass 1: one block per (batch, head) slab, a wave per row.  Writes the row constants, the
 // D-major table ctab[D][row] and the slab's summed weights wpart[slab][delta].
-__global__ __launch_bounds__(256) void calib_stats_kernel(const int8_t *__restrict__ logits, int Lq, int n,
+__global__ __launch_bounds__(256) void calib_stats_kernel(const int8_t *__restrict__ logits, int H, int Lq, int n,
                                                           AlphaTable alpha, int64_t rows_total,
                                                           int32_t *__restrict__ ctab, double *__restrict__ rowconst,
                                                           double *__restrict__ wpart)
@@ -62,8 +62,8 @@ __global__ __launch_bounds__(256) void calib_stats_kernel(const int8_t *__restri
     __shared__ int hist[4][256];
     __shared__ double wsum[4][256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int head = blockIdx.x;
-    const int64_t slab = (int64_t)blockIdx.y * gridDim.x + head;
+    const int64_t slab = blockIdx.x;
+    const int head = (int)(blockIdx.x % (uint32_t)H);
     const double a = alpha.e[head];
     double wacc[4] = {0.0, 0.0, 0.0, 0.0};   // weights of delta = lane + 64*k, summed over this wave's rows
     double e[4];                             // exp(-alpha*delta) of the lane's four distances: the same for every row
@@ -240,14 +240,16 @@ hipError_t launch_calibrate(const int8_t *logits, int Bt, int H, int Lq, int Lk,
     double *logtab = K + H;
     AlphaTable at;
     for (int h = 0; h < HCCS_MAX_HEADS; ++h) at.e[h] = h < H ? alpha[h] : 0.0;
-    hipLaunchKernelGGL(calib_stats_kernel, dim3(H, Bt), dim3(256), 0, st, logits, Lq, Lk, at, rows, ctab, rowconst,
-                       wpart);
-    hipLaunchKernelGGL(calib_reduce_kernel, dim3(H), dim3(256), 0, st, wpart, rowconst, Bt, H, Lq, W, K);
-    hipLaunchKernelGGL(calib_logtab_kernel, dim3(128), dim3(256), 0, st, logtab);
-    hipLaunchKernelGGL(calib_objective_kernel, dim3(nc, H), dim3(256), 0, st, cand, nc, Bt, H, Lq, Lk, rows, ctab, W,
-                       K, logtab, objective);
-    hipLaunchKernelGGL(calib_argmin_kernel, dim3(H), dim3(256), 0, st, objective, nc, best);
-    return hipGetLastError();
+    const dim3 block(256);
+    hipError_t e = launch(calib_stats_kernel, dim3((uint32_t)(Bt * H)), block, st, logits, H, Lq, Lk, at, rows, ctab,
+                          rowconst, wpart);
+    if (e == hipSuccess) e = launch(calib_reduce_kernel, dim3(H), block, st, wpart, rowconst, Bt, H, Lq, W, K);
+    if (e == hipSuccess) e = launch(calib_logtab_kernel, dim3(128), block, st, logtab);
+    if (e == hipSuccess)
+        e = launch(calib_objective_kernel, dim3(nc, H), block, st, cand, nc, Bt, H, Lq, Lk, rows, ctab, W, K, logtab,
+                   objective);
+    if (e == hipSuccess) e = launch(calib_argmin_kernel, dim3(H), block, st, objective, nc, best);
+    return e;
 }
 
 }  // namespace hccs

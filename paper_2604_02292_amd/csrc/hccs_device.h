@@ -7,6 +7,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "../../include/hccs.h"
 
 namespace hccs {
@@ -29,37 +32,10 @@ struct RequantTable {
 // The loads and stores are marked non-temporal: every byte is touched once.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-#ifndef HCCS_STREAM_LOAD_NT
-#define HCCS_STREAM_LOAD_NT 1
-#endif
-#ifndef HCCS_STREAM_STORE_NT
-#define HCCS_STREAM_STORE_NT 1
-#endif
-__device__ __forceinline__ u32x4 load_stream(const void *p)
-{
-#if HCCS_STREAM_LOAD_NT
-    return __builtin_nontemporal_load((const u32x4 *)p);
-#else
-    return *(const u32x4 *)p;
-#endif
-}
-__device__ __forceinline__ void store_stream(void *p, u32x4 v)
-{
-#if HCCS_STREAM_STORE_NT
-    __builtin_nontemporal_store(v, (u32x4 *)p);
-#else
-    *(u32x4 *)p = v;
-#endif
-}
+__device__ __forceinline__ u32x4 load_stream(const void *p) { return __builtin_nontemporal_load((const u32x4 *)p); }
+__device__ __forceinline__ void store_stream(void *p, u32x4 v) { __builtin_nontemporal_store(v, (u32x4 *)p); }
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ u32x2 load_stream8(const void *p)
-{
-#if HCCS_STREAM_LOAD_NT
-    return __builtin_nontemporal_load((const u32x2 *)p);
-#else
-    return *(const u32x2 *)p;
-#endif
-}
+__device__ __forceinline__ u32x2 load_stream8(const void *p) { return __builtin_nontemporal_load((const u32x2 *)p); }
 constexpr uint32_t kPadWord = 0x80808080u;   // four logits of -128
 
 // ---- cross-lane movement -------------------------------------------------
@@ -279,37 +255,42 @@ inline FastDiv make_fast_div(uint32_t d)
     return f;
 }
 
-// Where a block works: tile inside a (batch, head) slab, head, slab number.  With back-to-back
-// stream launches a one-dimensional grid of tiles*H*B blocks measured 3 % faster than the same
-// blocks as a (tiles, H, B) grid (12.5 against 12.9 us on a 67 MB batch, identical work; inside a
-// replayed graph the two are equal), so the launch is linear whenever the block count fits, and
-// the block number is taken apart by multiply-shift divisions.
+// Where a block works: tile inside a (batch, head) slab, head, slab number.  The grid is
+// one-dimensional (tiles*H*B blocks; the entry points keep the row count, hence the block
+// count, below 2^31) and the block number is taken apart by multiply-shift divisions.
 struct BlockPlace {
-    FastDiv by_tiles, by_H;   // by_tiles.divisor = 0: three-dimensional grid (tiles, H, B) instead
+    FastDiv by_tiles, by_H;
     __device__ __forceinline__ void locate(uint32_t &tile, uint32_t &head, uint32_t &slab) const
     {
-        if (by_tiles.divisor != 0) {
-            slab = by_tiles.quotient(blockIdx.x);
-            tile = blockIdx.x - slab * by_tiles.divisor;
-            head = slab - by_H.quotient(slab) * by_H.divisor;
-        } else {
-            tile = blockIdx.x, head = blockIdx.y, slab = blockIdx.z * gridDim.y + blockIdx.y;
-        }
+        slab = by_tiles.quotient(blockIdx.x);
+        tile = blockIdx.x - slab * by_tiles.divisor;
+        head = slab - by_H.quotient(slab) * by_H.divisor;
     }
 };
-// grid and block placement for `tiles` blocks per slab
-inline BlockPlace place_blocks(int64_t tiles, int H, int Bt, dim3 &grid)
+// grid and block placement for `tiles` blocks per slab (tiles*H*Bt < 2^31)
+inline BlockPlace place_blocks(int64_t tiles, int H, int64_t Bt, dim3 &grid)
 {
     BlockPlace bp;
-    const int64_t blocks = tiles * H * Bt;
-    if (blocks < ((int64_t)1 << 31)) {
-        bp.by_tiles = make_fast_div((uint32_t)tiles), bp.by_H = make_fast_div((uint32_t)H);
-        grid = dim3((uint32_t)blocks);
-    } else {
-        bp.by_tiles = FastDiv{0, 0, 0}, bp.by_H = FastDiv{0, 0, 0};
-        grid = dim3((uint32_t)tiles, H, Bt);
-    }
+    bp.by_tiles = make_fast_div((uint32_t)tiles), bp.by_H = make_fast_div((uint32_t)H);
+    grid = dim3((uint32_t)(tiles * H * Bt));
     return bp;
+}
+
+// Launches `kernel` and returns the status of this launch alone (an error left behind by an
+// earlier, unrelated runtime call is neither reported nor cleared here).
+template <typename... Params, typename... Args, size_t... I>
+inline hipError_t launch_impl(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t st,
+                              std::index_sequence<I...>, Args &&...args)
+{
+    std::tuple<Params...> held(static_cast<Params>(std::forward<Args>(args))...);
+    void *ptrs[] = {(void *)&std::get<I>(held)...};
+    return hipLaunchKernel((const void *)kernel, grid, block, ptrs, 0, st);
+}
+template <typename... Params, typename... Args>
+inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t st, Args &&...args)
+{
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    return launch_impl(kernel, grid, block, st, std::index_sequence_for<Params...>{}, std::forward<Args>(args)...);
 }
 
 }  // namespace hccs

@@ -571,19 +571,17 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src
 // host side: choose the lane-group shape for a row length
 // ---------------------------------------------------------------------------
 template <int G, int V, int R, int WPB = 4, int MODE = kModeU8>
-static hipError_t launch_rows(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int nvec,
+static hipError_t launch_rows(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int nvec,
                               const HeadTable &tab, hipStream_t st)
 {
     constexpr int kRowsPerBlock = WPB * R * (64 / G);
     dim3 grid;
     const BlockPlace place = place_blocks((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt, grid);
-    hipLaunchKernelGGL((hccs_rows_kernel<G, V, R, WPB, MODE>), grid, dim3(64 * WPB), 0, st, x, p, Lq, nvec, place,
-                       tab);
-    return hipGetLastError();
+    return launch(hccs_rows_kernel<G, V, R, WPB, MODE>, grid, dim3(64 * WPB), st, x, p, Lq, nvec, place, tab);
 }
 
 template <int MODE>
-static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
+static hipError_t launch_mode(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
                               bool vector_ok, hipStream_t st)
 {
     if (vector_ok && Lk % ((MODE & 1) ? 8 : 16) == 0 && Lk <= 16384) {
@@ -609,10 +607,10 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
         // 16-byte boundary by as many elements): aligned vectors over each row's span.
         constexpr int VB = (MODE & 1) ? 8 : 16;   // input bytes per vector
         constexpr int kOutBytes = (MODE & 1) ? 2 : 1;
-        const int64_t rows = (int64_t)Bt * H * Lq;
+        const int64_t rows = Bt * H * Lq;
         const uint32_t first = (uint32_t)((uintptr_t)x % VB);
         const bool matching = (uintptr_t)p % 16 == (uintptr_t)first * kOutBytes;
-        if (matching && Lk <= 16384 - 32 && rows < ((int64_t)1 << 31)) {
+        if (matching && Lk <= 16384 - 32) {
             // widest span of a row over aligned vectors: rows start at first + multiples of gcd(Lk, VB)
             const int step = (Lk & -Lk & (VB - 1)) ? (Lk & -Lk & (VB - 1)) : VB;
             const int nspan = (VB - step + (int)(first % step) + Lk + VB - 1) / VB;
@@ -621,11 +619,10 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
 #define HCCS_LAUNCH_RAGGED(G_, V_, LONG_)                                                                    \
     {                                                                                                      \
         const int64_t per_block = 4 * (64 / G_);                                                           \
-        hipLaunchKernelGGL((hccs_rows_ragged_kernel<G_, V_, MODE, LONG_>),                                  \
-                           dim3((uint32_t)((rows + per_block - 1) / per_block)), dim3(256), 0, st, x_al,    \
-                           p_al, (uint32_t)rows, first, make_fast_div((uint32_t)Lq),                        \
-                           make_fast_div((uint32_t)H), Lk, tab);                                            \
-        return hipGetLastError();                                                                          \
+        return launch(hccs_rows_ragged_kernel<G_, V_, MODE, LONG_>,                                         \
+                      dim3((uint32_t)((rows + per_block - 1) / per_block)), dim3(256), st, x_al, p_al,      \
+                      (uint32_t)rows, first, make_fast_div((uint32_t)Lq), make_fast_div((uint32_t)H), Lk,   \
+                      tab);                                                                                 \
     }
             if (Lk < VB) HCCS_LAUNCH_RAGGED(4, 1, false)
             if (nspan <= 4) HCCS_LAUNCH_RAGGED(4, 1, true)
@@ -648,17 +645,14 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int Bt, int H, int Lq
     const BlockPlace place = place_blocks(Lq, H, Bt, grid);   // one block per row
     if (vector_ok && Lk % 16 == 0) {   // 16384 < Lk <= 65536: one block per row, the row in the block's registers
         const int nvec = Lk / ((MODE & 1) ? 8 : 16);
-        if (nvec <= 2048)
-            hipLaunchKernelGGL((hccs_row_block_kernel<8, MODE>), grid, dim3(256), 0, st, x, p, Lq, nvec, place, tab);
-        else   // at most 4096: Lk <= 65536 in the 8-bit modes, and the 16-bit modes need Lk*B <= 32767
-            hipLaunchKernelGGL((hccs_row_block_kernel<16, MODE>), grid, dim3(256), 0, st, x, p, Lq, nvec, place, tab);
-        return hipGetLastError();
+        if (nvec <= 2048) return launch(hccs_row_block_kernel<8, MODE>, grid, dim3(256), st, x, p, Lq, nvec, place, tab);
+        // at most 4096: Lk <= 65536 in the 8-bit modes, and the 16-bit modes need Lk*B <= 32767
+        return launch(hccs_row_block_kernel<16, MODE>, grid, dim3(256), st, x, p, Lq, nvec, place, tab);
     }
-    hipLaunchKernelGGL(hccs_row_bytes_kernel<MODE>, grid, dim3(256), 0, st, x, p, Lq, Lk, place, tab);
-    return hipGetLastError();
+    return launch(hccs_row_bytes_kernel<MODE>, grid, dim3(256), st, x, p, Lq, Lk, place, tab);
 }
 
-hipError_t launch_softmax(const int8_t *x, void *out, int Bt, int H, int Lq, int Lk, const HeadTable &tab,
+hipError_t launch_softmax(const int8_t *x, void *out, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
                           int mode, bool vector_ok, hipStream_t st)
 {
     if (Bt == 0 || Lq == 0) return hipSuccess;
@@ -675,26 +669,22 @@ hipError_t launch_softmax(const int8_t *x, void *out, int Bt, int H, int Lq, int
 hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hipStream_t st)
 {
     if (count == 0) return hipSuccess;
-    hipLaunchKernelGGL(reciprocal_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, z, rho,
-                       count);
-    return hipGetLastError();
+    return launch(reciprocal_kernel, dim3((unsigned)((count + 255) / 256)), dim3(256), st, z, rho, count);
 }
 
 hipError_t launch_normalise_table(const int32_t *bsdz, uint8_t *out, int64_t count, hipStream_t st)
 {
     if (count == 0) return hipSuccess;
-    hipLaunchKernelGGL(normalise_table_kernel, dim3((unsigned)count), dim3(64), 0, st, (const int4 *)bsdz,
-                       (uint32_t *)out, count);
-    return hipGetLastError();
+    return launch(normalise_table_kernel, dim3((unsigned)count), dim3(64), st, (const int4 *)bsdz, (uint32_t *)out,
+                  count);
 }
 
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st)
 {
     const int64_t count = bytes / 16;
     if (count == 0) return hipSuccess;
-    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((count + 1023) / 1024)), dim3(256), 0, st,
-                       (const u32x4 *)src, (u32x4 *)dst, count);
-    return hipGetLastError();
+    return launch(copy_kernel, dim3((unsigned)((count + 1023) / 1024)), dim3(256), st, (const u32x4 *)src,
+                  (u32x4 *)dst, count);
 }
 
 }  // namespace hccs

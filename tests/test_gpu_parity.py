@@ -187,8 +187,8 @@ def test_softmax_tensors_that_begin_inside_a_vector(oracle, shape, off):
 
 
 def test_empty_tensors_and_size_limits(oracle):
-    """Zero-sized tensors are a no-op; the largest head table (64) and the largest batch extent
-    (65535, the grid's z limit) go through; one more is rejected before any launch."""
+    """Zero-sized tensors are a no-op; the largest head table (64) and a batch extent beyond 65535
+    (no grid dimension is tied to it) go through."""
     for shape in [(0, 4, 8, 64), (3, 4, 0, 64)]:
         x = torch.empty(shape, dtype=torch.int8, device="cuda")
         out = binding.calibrated_softmax_i8(x, synth.head_params(4, 64, 1, seed=1), 1)
@@ -197,10 +197,12 @@ def test_empty_tensors_and_size_limits(oracle):
     table = synth.head_params(64, 32, 1, seed=64)
     check(mixed_logits((2, 64, 3, 32), 64), table, 1, oracle, "64 heads")
     table = synth.head_params(1, 16, 1, seed=2)
-    check(mixed_logits((65535, 1, 1, 16), 65535), table, 1, oracle, "65535 batches")
-    with pytest.raises(binding.HccsError) as e:
-        binding.calibrated_softmax_i8(torch.zeros((65536, 1, 1, 16), dtype=torch.int8, device="cuda"), table, 1)
-    assert e.value.status == -2
+    check(mixed_logits((70001, 1, 1, 16), 65535), table, 1, oracle, "70001 batches")
+    table = synth.head_params(2, 100, 1, seed=3)
+    check(mixed_logits((66000, 2, 1, 100), 66000), table, 1, oracle, "66000 batches, ragged rows")
+    q, k, v = rect_qkv(66000, 33000, 2, 2, 16, 64)       # 66000 (batch, head) items through the streaming kernel
+    check_attention(q, k, v, synth.head_params(2, 16, 1, seed=5), synth.requant_params(2, seed=5), 1, oracle,
+                    "66000 items")
     q = torch.empty((0, 2, 64, 64), dtype=torch.int8, device="cuda")
     o = binding.attention_i8(q, q, q, synth.head_params(2, 64, 1, seed=1), synth.requant_params(2, seed=1), 1)
     torch.cuda.synchronize()

@@ -24,7 +24,8 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "hccs.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", f)).read()
+                     for f in sorted(os.listdir(os.path.join(ROOT, "include"))) if f.endswith(".h"))
     declared = set(re.findall(r"\b(hccs_[a-z0-9_]+)\s*\(", header))
     assert declared, "no declarations found"
     assert declared == set(binding.EXPORTS)
@@ -100,6 +101,7 @@ def test_softmax_rejections_launch_nothing(lib):
     assert _softmax_rc(lib, 4096, 8192, 1, 65, 4, 64, ok * 65) == -2
     assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 0, ok) == -2
     assert _softmax_rc(lib, 4096, 8192, 1, 1, 4, 65537, ok) == -2
+    assert _softmax_rc(lib, 4096, 8192, 1 << 20, 64, 32, 64, ok * 64) == -2   # 2^31 rows: one too many
     assert _softmax_rc(lib, 4096, 4096 + 64, 1, 1, 4, 64, ok) == -3  # partial overlap
     assert _softmax_rc(lib, 0, 0, 0, 1, 4, 64, ok) == 0             # empty tensor: no-op
     assert _softmax_rc(lib, 0, 0, 1, 1, 0, 64, ok) == 0
@@ -146,7 +148,7 @@ def test_attention_rejections_launch_nothing(lib):
     def call_ex(q=4096, k=8192, v=12288, o=16384, B=1, H=1, Lq=40, Lk=256, d=64, band=1):
         return lib.hccs_attention_i8_ex(vp(q), vp(k), vp(v), vp(o), B, H, Lq, Lk, d, arr, rq, 255, band, None)
 
-    assert call_ex(Lk=0) == -2 and call_ex(d=96) == -2 and call_ex(Lq=-1) == -2 and call_ex(B=70000) == -2
+    assert call_ex(Lk=0) == -2 and call_ex(d=96) == -2 and call_ex(Lq=-1) == -2 and call_ex(B=1 << 26) == -2   # 2^31 rows and more
     assert call_ex(Lq=0, q=0, o=0) == 0               # no queries: nothing to do
     assert call_ex(k=0) == -1 and call_ex(o=16388) == -3
     assert call_ex(Lk=512) == -7                      # band is checked with n = Lk
@@ -158,6 +160,7 @@ def test_calibration_entry_point_rejections(lib):
                                                               + 32768 * 8)   # + the table of logarithms
     assert lib.hccs_calibrate_workspace_bytes(0, 3, 4, 64) == -2
     assert lib.hccs_calibrate_workspace_bytes(2, 65, 4, 64) == -2
+    assert lib.hccs_calibrate_workspace_bytes(1 << 20, 64, 32, 64) == -2
     al = (ctypes.c_double * 2)(0.1, 0.2)
 
     def call(x=4096, B=1, H=2, Lq=4, Lk=64, alpha=al, cand=8192, nc=5, obj=16384, best=32768, ws=65536, wsb=1 << 20):
