@@ -65,7 +65,8 @@ typedef enum {
     HCCS_E_PARAM_FLOOR = -6, /* n*(B - S*Dmax) < 256: the row sum could drop below 256   */
     HCCS_E_PARAM_CEIL = -7,  /* n*B above the band's ceiling                             */
     HCCS_E_HIP = -8,         /* the HIP runtime refused the launch                       */
-    HCCS_E_REQUANT = -9      /* mult or shift outside its range                          */
+    HCCS_E_REQUANT = -9,     /* mult or shift outside its range                          */
+    HCCS_E_SCRATCH = -10     /* more work memory needed than the static buffer holds     */
 } hccs_status;
 
 /* Admissibility bands (Sec. IV-C "Integer Range Constraints", Eq. (11)).
@@ -174,6 +175,23 @@ HCCS_API int hccs_calibrate_grid(const int8_t *logits_dev, int32_t B, int32_t H,
                                  const double *alpha_host, const hccs_head_params *candidates_dev,
                                  int32_t n_candidates, double *objective_dev, int32_t *best_dev,
                                  void *workspace_dev, int64_t workspace_bytes, void *hip_stream);
+
+/* hccs_calibrate_grid for callers that cannot allocate device memory or bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * inputs, outputs, arithmetic and bits as hccs_calibrate_grid; the work memory is a buffer of
+ * HCCS_STATIC_SCRATCH_BYTES that lives inside the library (one per GPU the library runs on, held
+ * until the process ends).  The call allocates and frees nothing.  A problem whose
+ * hccs_calibrate_workspace_bytes(...) exceeds HCCS_STATIC_SCRATCH_BYTES returns HCCS_E_SCRATCH and
+ * launches nothing (the limit covers 64 batches of [8 heads, 128 queries], the calibration set of
+ * Sec. V-A).  Every call on a GPU uses that GPU's one buffer: calls that overlap in time on one
+ * GPU (different streams, or different host threads) race on it and must be serialised by the
+ * caller; calls on one stream are ordered by the stream.  Nothing in the buffer has to survive
+ * from one call to the next, and nothing in it has to start at zero. */
+#define HCCS_STATIC_SCRATCH_BYTES (36 * 1024 * 1024)
+HCCS_API int hccs_calibrate_grid_static(const int8_t *logits_dev, int32_t B, int32_t H, int32_t Lq, int32_t Lk,
+                                        const double *alpha_host, const hccs_head_params *candidates_dev,
+                                        int32_t n_candidates, double *objective_dev, int32_t *best_dev,
+                                        void *hip_stream);
 
 /* Static description of a status code. */
 HCCS_API const char *hccs_status_string(int status);

@@ -16,7 +16,7 @@ BAND_U8, BAND_STRICT = 0, 1
 RECIP_EXACT, RECIP_CLB = 0, 1
 
 EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_calibrated_softmax_i8_ex", "hccs_attention_i8", "hccs_attention_i8_ex",
-           "hccs_calibrate_workspace_bytes", "hccs_calibrate_grid",
+           "hccs_calibrate_workspace_bytes", "hccs_calibrate_grid", "hccs_calibrate_grid_static",
            "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_normalise_table_u8", "hccs_copy_bytes", "hccs_status_string"]
 
 
@@ -58,6 +58,8 @@ def lib():
         L.hccs_calibrate_workspace_bytes.restype = i64
         L.hccs_calibrate_grid.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_double), vp, i32, vp, vp, vp,
                                           i64, vp]
+        L.hccs_calibrate_grid_static.argtypes = [vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_double), vp, i32, vp,
+                                                 vp, vp]
         L.hccs_exp_softmax_i8_f32.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_float), vp]
         L.hccs_reciprocal_u8.argtypes = [vp, vp, i64, vp]
         L.hccs_copy_bytes.argtypes = [vp, vp, i64, vp]
@@ -253,6 +255,27 @@ def calibrate_grid(logits, alpha, candidates, stream=None):
     for t in (cand_dev, work):
         t.record_stream(stream)
     return obj, best
+
+
+def calibrate_grid_static(logits, alpha, candidates_dev, objective, best, stream=None):
+    """hccs_calibrate_grid_static: every buffer is the caller's (candidates_dev int32 CUDA [nc,4] rows of
+    (B, S, Dmax, 0), objective float64 CUDA [H,nc], best int32 CUDA [H]); nothing is allocated."""
+    import torch
+    assert logits.is_cuda and logits.dtype == torch.int8 and logits.is_contiguous() and logits.dim() == 4
+    B, H, Lq, Lk = logits.shape
+    nc = candidates_dev.shape[0]
+    assert candidates_dev.is_cuda and candidates_dev.dtype == torch.int32 and candidates_dev.is_contiguous()
+    assert candidates_dev.dim() == 2 and candidates_dev.shape[1] == 4
+    assert objective.is_cuda and objective.dtype == torch.float64 and objective.is_contiguous()
+    assert tuple(objective.shape) == (H, nc)
+    assert best.is_cuda and best.dtype == torch.int32 and best.is_contiguous() and tuple(best.shape) == (H,)
+    assert len(alpha) == H
+    al = (ctypes.c_double * H)(*[float(a) for a in alpha])
+    _check(lib().hccs_calibrate_grid_static(ctypes.c_void_p(logits.data_ptr()), B, H, Lq, Lk, al,
+                                            ctypes.c_void_p(candidates_dev.data_ptr()), nc,
+                                            ctypes.c_void_p(objective.data_ptr()), ctypes.c_void_p(best.data_ptr()),
+                                            _stream_handle(stream)))
+    return objective, best
 
 
 def exp_softmax_i8_f32(logits, scale, out=None, stream=None):

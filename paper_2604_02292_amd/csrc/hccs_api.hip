@@ -20,6 +20,7 @@ int64_t calibrate_workspace_bytes(int64_t Bt, int64_t H, int64_t Lq);
 hipError_t launch_calibrate(const int8_t *logits, int Bt, int H, int Lq, int Lk, const double *alpha,
                             const hccs_head_params *cand, int nc, double *objective, int32_t *best, void *workspace,
                             hipStream_t st);
+hipError_t static_scratch(void **ptr);
 hipError_t launch_exp_softmax(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const float *scale,
                               hipStream_t st);
 }  // namespace hccs
@@ -180,6 +181,19 @@ int hccs_calibrate_grid(const int8_t *logits_dev, int32_t B, int32_t H, int32_t 
     return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
 }
 
+int hccs_calibrate_grid_static(const int8_t *logits_dev, int32_t B, int32_t H, int32_t Lq, int32_t Lk,
+                               const double *alpha_host, const hccs_head_params *candidates_dev, int32_t n_candidates,
+                               double *objective_dev, int32_t *best_dev, void *hip_stream)
+{
+    const int64_t need = hccs_calibrate_workspace_bytes(B, H, Lq, Lk);
+    if (need < 0) return HCCS_E_SHAPE;
+    if (need > (int64_t)HCCS_STATIC_SCRATCH_BYTES) return HCCS_E_SCRATCH;
+    void *scratch_dev = nullptr;
+    if (hccs::static_scratch(&scratch_dev) != hipSuccess) return HCCS_E_HIP;
+    return hccs_calibrate_grid(logits_dev, B, H, Lq, Lk, alpha_host, candidates_dev, n_candidates, objective_dev,
+                               best_dev, scratch_dev, (int64_t)HCCS_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
 int hccs_exp_softmax_i8_f32(const int8_t *logits_dev, uint8_t *probs_dev, int32_t B, int32_t H, int32_t Lq,
                             int32_t Lk, const float *scale_host, void *hip_stream)
 {
@@ -236,6 +250,7 @@ const char *hccs_status_string(int status)
         case HCCS_E_PARAM_CEIL: return "n*B exceeds the ceiling of the chosen band";
         case HCCS_E_HIP: return "the HIP runtime reported an error at launch";
         case HCCS_E_REQUANT: return "requantisation multiplier or shift out of range";
+        case HCCS_E_SCRATCH: return "the problem needs more work memory than the library's static buffer holds";
         default: return "unknown status";
     }
 }

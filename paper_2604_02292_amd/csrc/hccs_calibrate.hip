@@ -14,7 +14,14 @@
 // All sums are taken in a fixed order (no floating-point atomics): results are reproducible.
 #include "hccs_device.h"
 
+#include <mutex>
+
 namespace hccs {
+
+// Work memory of hccs_calibrate_grid_static: the same layout launch_calibrate gives a caller's
+// workspace, but owned by the library so that the call allocates nothing.  Each device holds its
+// own copy of the array at its own address; `scratch` itself is only a host-side stand-in for it.
+static __device__ __align__(256) unsigned char scratch[HCCS_STATIC_SCRATCH_BYTES];
 
 struct AlphaTable {
     double e[HCCS_MAX_HEADS];
@@ -250,6 +257,28 @@ hipError_t launch_calibrate(const int8_t *logits, int Bt, int H, int Lq, int Lk,
                    objective);
     if (e == hipSuccess) e = launch(calib_argmin_kernel, dim3(H), block, st, objective, nc, best);
     return e;
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t static_scratch(void **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static void *address[kMaxDevices] = {};
+    static std::mutex guard;
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(guard);
+    if (!address[device]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        address[device] = p;
+    }
+    *ptr = address[device];
+    return hipSuccess;
 }
 
 }  // namespace hccs

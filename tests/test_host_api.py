@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings(lib):
     assert binding.status_string(0) == "ok"
-    for code in range(-9, 0):
+    for code in range(-10, 0):
         assert binding.status_string(code) != "unknown status"
     assert binding.status_string(-77) == "unknown status"
 
@@ -172,6 +172,21 @@ def test_calibration_entry_point_rejections(lib):
     assert call(ws=65540) == -3 and call(obj=16388) == -3
     assert call(alpha=(ctypes.c_double * 2)(0.1, 0.0)) == -4
     assert call(alpha=(ctypes.c_double * 2)(0.1, float("nan"))) == -4
+
+
+def test_static_calibration_entry_point_rejections(lib):
+    """The size limit and the shape checks come before anything touches a device."""
+    vp = ctypes.c_void_p
+    al = (ctypes.c_double * 8)(*([0.1] * 8))
+
+    def call(B=1, H=8, Lq=4, Lk=64, nc=5):
+        return lib.hccs_calibrate_grid_static(vp(4096), B, H, Lq, Lk, al, vp(8192), nc, vp(16384), vp(32768), None)
+
+    assert lib.hccs_calibrate_workspace_bytes(64, 8, 128, 128) <= 36 << 20 < lib.hccs_calibrate_workspace_bytes(
+        80, 8, 128, 128)
+    assert call(B=80, Lq=128, Lk=128) == -10
+    assert call(B=0) == -2 and call(H=65) == -2 and call(Lk=0) == -2
+    assert binding.status_string(-10) != "unknown status"
 
 
 def test_other_entry_points_reject_bad_arguments(lib):
