@@ -101,12 +101,11 @@ HCCS_API int hccs_validate_params(const hccs_head_params *table_host, int32_t H,
  *               logits_dev (in place) but must not partially overlap it.
  *   B,H,Lq      >= 0 for B and Lq (an empty tensor is a no-op), 1 <= H <= HCCS_MAX_HEADS,
  *               B*H*Lq < 2^31.
- *   Lk          1..HCCS_MAX_ROW_LENGTH.  With 16-byte aligned base pointers every length up
- *               to 16352 (and multiples of 16 beyond) takes the vectorised kernels, fastest
- *               for multiples of 16.  So do tensors that begin inside a 16-byte line when
- *               input and output begin the same number of elements behind such a line (a
- *               slice of a larger tensor, Lk <= 16352).  Other pointer combinations and
- *               other lengths beyond 16352 take a slower byte-wise kernel.
+ *   Lk          1..HCCS_MAX_ROW_LENGTH.  Any length and any tensor address run on the same
+ *               vectorised kernels (rows up to 16384 elements in one wave's registers, longer
+ *               ones in one block's); fastest when both tensors begin on a 16-byte boundary
+ *               and Lk is a multiple of 16 (every vector aligned), otherwise rows are read
+ *               and written with 16-byte accesses wherever they lie.
  *   table_host  H entries, validated against `band` with n = Lk.
  *   out_scale_T must be 255.
  * Errors: NULL pointers, bad shapes, out_scale_T != 255, inadmissible table. */
@@ -116,9 +115,9 @@ HCCS_API int hccs_calibrated_softmax_i8(const int8_t *logits_dev, uint8_t *probs
 
 /* The other output modes of the same row operation.
  *   out_scale_T = 255:   out_dev is uint8  [B,H,Lq,Lk], as above.
- *   out_scale_T = 32767: out_dev is uint16 [B,H,Lq,Lk] (2-byte aligned; 16-byte aligned for the
- *                        vectorised kernels): Alg. 1 as printed, rho = floor(32767 / Z), p = s * rho
- *                        (Eq. (6), (7)).  Needs Z <= 32767, so the table is validated against
+ *   out_scale_T = 32767: out_dev is uint16 [B,H,Lq,Lk] (2-byte aligned; every vector is aligned
+ *                        when both tensors are 16-byte aligned and Lk is a multiple of 8):
+ *                        Alg. 1 as printed, rho = floor(32767 / Z), p = s * rho (Eq. (6), (7)).  Needs Z <= 32767, so the table is validated against
  *                        HCCS_BAND_STRICT whatever `band` says.  No in-place use.
  *   reciprocal = HCCS_RECIP_EXACT: floor division.
  *   reciprocal = HCCS_RECIP_CLB:   leading-bit approximation of Sec. III-B, Eq. (9):

@@ -130,25 +130,122 @@ __device__ __forceinline__ int clamped_sum(int t, int slots, int n, uint32_t mu,
 }
 
 // ---------------------------------------------------------------------------
-// Register-resident kernel for rows whose length is a multiple of 16.
+// Vector access at any byte address.  The unaligned-access mode of this target lets a 16-byte
+// (8-, 4-, 2-byte) global access start at any byte; the under-aligned pointee types below tell
+// the compiler so, and it still emits one global_load/store_dwordx4 (x2, dword, short) for them.
+// ---------------------------------------------------------------------------
+typedef u32x4 __attribute__((aligned(1))) u32x4_any;
+typedef u32x2 __attribute__((aligned(1))) u32x2_any;
+typedef uint32_t __attribute__((aligned(1))) u32_any;
+typedef uint16_t __attribute__((aligned(1))) u16_any;
+
+// One input vector (DW dwords) of a row.  ANY = false: the address is a multiple of the vector
+// size.  ANY = true: any address.
+template <int DW, bool ANY>
+__device__ __forceinline__ void load_vector(const int8_t *p, uint32_t (&d)[DW])
+{
+    if constexpr (DW == 4) {
+        u32x4 t;
+        if constexpr (ANY) t = __builtin_nontemporal_load((const u32x4_any *)p);
+        else t = load_stream(p);
+        d[0] = t[0], d[1] = t[1], d[2] = t[2], d[3] = t[3];
+    } else {
+        u32x2 t;
+        if constexpr (ANY) t = __builtin_nontemporal_load((const u32x2_any *)p);
+        else t = load_stream8(p);
+        d[0] = t[0], d[1] = t[1];
+    }
+}
+// The last `count` input bytes of the tensor, one by one (the one vector that would reach past
+// the tensor's end); the other bytes become padding.
+template <int DW>
+__device__ __forceinline__ void load_vector_bytes(const int8_t *p, int count, uint32_t (&d)[DW])
+{
+#pragma unroll
+    for (int c = 0; c < DW; ++c) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) w |= (uint32_t)(4 * c + b < count ? (uint8_t)p[4 * c + b] : 0x80u) << (8 * b);
+        d[c] = w;
+    }
+}
+template <bool ANY>
+__device__ __forceinline__ void store_vector(uint8_t *p, u32x4 o)
+{
+    if constexpr (ANY) __builtin_nontemporal_store(o, (u32x4_any *)p);
+    else store_stream(p, o);
+}
+// The first `bytes` (1..15, the same in every lane that gets here) bytes of an output vector, as
+// at most four stores of 8, 4, 2 and 1 bytes.
+__device__ __forceinline__ void store_vector_head(uint8_t *p, u32x4 o, int bytes)
+{
+    if (bytes & 8) {
+        __builtin_nontemporal_store((u32x2){o[0], o[1]}, (u32x2_any *)p);
+        o[0] = o[2], o[1] = o[3], p += 8;
+    }
+    if (bytes & 4) {
+        __builtin_nontemporal_store(o[0], (u32_any *)p);
+        o[0] = o[1], p += 4;
+    }
+    if (bytes & 2) {
+        __builtin_nontemporal_store((uint16_t)o[0], (u16_any *)p);
+        o[0] >>= 16, p += 2;
+    }
+    if (bytes & 1) __builtin_nontemporal_store((uint8_t)o[0], p);
+}
+
+// What a lane has to know about the row's last vector when the row length is not a multiple of
+// the vector size (RAGGED kernels).  It is the same for every row, so it is worked out once per
+// lane: `tail_elems` elements of vector `last_vec` exist, the other byte slots are padding.
+template <int DW>
+struct RowTail {
+    int last_vec, tail_elems;   // tail_elems in 1..VB (VB: the last vector is whole)
+    uint32_t keep[DW];          // byte mask of the existing elements of the last vector
+    __device__ __forceinline__ RowTail(int n, int nvec) : last_vec(nvec - 1), tail_elems(n - (nvec - 1) * DW * 4)
+    {
+#pragma unroll
+        for (int c = 0; c < DW; ++c) {
+            const int left = tail_elems - 4 * c;
+            keep[c] = left >= 4 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << (8 * left)) - 1u));
+        }
+    }
+    __device__ __forceinline__ void pad(uint32_t (&d)[DW]) const
+    {
+#pragma unroll
+        for (int c = 0; c < DW; ++c) d[c] = (d[c] & keep[c]) | (kPadWord & ~keep[c]);
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Register-resident kernel.
 //
 // A row is shared by G adjacent lanes (G a power of two, 4..64); each lane holds V
 // vectors of it, vector number v*G + lane_in_group, so one load instruction of a
 // group covers G contiguous vectors.  A vector is 16 input bytes in the 8-bit modes
 // and 8 input bytes in the 16-bit modes, i.e. always 16 output bytes: every store
 // instruction of a group writes G*16 contiguous bytes.  A wave works on R batches
-// of 64/G rows at once (R*V loads in flight per lane).  The grid is (row tiles, H,
-// B): a block never straddles heads, so the head's constants are wave-uniform.
+// of 64/G rows at once (R*V loads in flight per lane).  A block never straddles
+// heads, so the head's constants are wave-uniform.
 //
 // Vectors past the end of a short row, and rows past the end of the slab, are
 // replaced by the byte -128: that is the identity of the maximum, and its
 // distance to the maximum is (m + 128), a known amount that is taken out of
 // the sum again.
+//
+// RAGGED = false: the row length is a multiple of the vector size and both tensors
+// begin on a 16-byte boundary, so every vector is aligned.
+// RAGGED = true: any row length, tensors at any address.  Row r begins at byte r*n,
+// wherever that falls; vectors are read and written where they lie.  The byte slots of
+// the row's last vector beyond its n-th element are overwritten with padding after the
+// load (the load itself reads the first bytes of the next row there; only the vector that
+// would reach past the end of the whole tensor is read byte by byte), and only the
+// existing elements of that vector are stored.  Which vector is the last one, and how
+// many of its elements exist, is the same for every row.
 // ---------------------------------------------------------------------------
-template <int G, int V, int R, int WPB, int MODE>
+template <int G, int V, int R, int WPB, int MODE, bool RAGGED>
 __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__restrict__ logits,
-                                                             uint8_t *__restrict__ out, int Lq, int nvec,
-                                                             BlockPlace place, HeadTable table)
+                                                             uint8_t *__restrict__ out, int Lq, int n,
+                                                             uint32_t last_slab, BlockPlace place, HeadTable table)
 {
     constexpr int kRowsPerBatch = 64 / G;
     constexpr int kRowsPerWave = R * kRowsPerBatch;
@@ -165,12 +262,21 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
     place.locate(tile, head, slab_no);
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
-    const int n = nvec * kVecBytes;
+    const int nvec = RAGGED ? (n + kVecBytes - 1) / kVecBytes : n / kVecBytes;
+    const RowTail<DW> tail(n, nvec);
 
     const size_t slab = (size_t)slab_no * (size_t)Lq;
     const int wave_row0 = ((int)tile * WPB + wave) * kRowsPerWave;
     if (wave_row0 >= Lq) return;   // whole wave past the slab
     const int row0 = wave_row0 + grp;
+    // The last vector of a row is read whole, i.e. kVecBytes - tail_elems bytes into the rows that
+    // follow.  A row with fewer bytes than that between its end and the end of the tensor reads
+    // its last vector byte by byte instead: the tensor's last row, or its last few rows when
+    // rows are shorter than a vector.  `near_end` (block-uniform) says whether this slab can
+    // hold such a row at all.
+    const int over_read = kVecBytes - tail.tail_elems;
+    const uint64_t rows_behind_slab = (uint64_t)(last_slab - slab_no) * (uint64_t)Lq;
+    const bool near_end = RAGGED && over_read > 0 && rows_behind_slab * (uint64_t)n < (uint64_t)over_read;
 
     uint32_t d[R][V][DW];
 #pragma unroll
@@ -181,13 +287,12 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
         for (int v = 0; v < V; ++v) {
             const int vi = v * G + sub;
             if (row < Lq && vi < nvec) {
-                if constexpr (DW == 4) {
-                    const u32x4 t = load_stream(src + vi * 16);
-                    d[j][v][0] = t[0], d[j][v][1] = t[1], d[j][v][2] = t[2], d[j][v][3] = t[3];
-                } else {
-                    const u32x2 t = load_stream8(src + vi * 8);
-                    d[j][v][0] = t[0], d[j][v][1] = t[1];
-                }
+                if (RAGGED && near_end && vi == tail.last_vec &&
+                    (rows_behind_slab + (uint64_t)(Lq - 1 - row)) * (uint64_t)n < (uint64_t)over_read)
+                    load_vector_bytes<DW>(src + vi * kVecBytes, tail.tail_elems, d[j][v]);
+                else
+                    load_vector<DW, RAGGED>(src + vi * kVecBytes, d[j][v]);
+                if (RAGGED && vi == tail.last_vec) tail.pad(d[j][v]);
             } else {
 #pragma unroll
                 for (int c = 0; c < DW; ++c) d[j][v][c] = kPadWord;
@@ -218,7 +323,12 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
         for (int v = 0; v < V; ++v) {
             const int vi = v * G + sub;
             const u32x4 o = ro.vector(d[j][v]);
-            if (row < Lq && vi < nvec) store_stream(dst + vi * 16, o);
+            if (row < Lq && vi < nvec) {
+                if (RAGGED && vi == tail.last_vec && tail.tail_elems < kVecBytes)
+                    store_vector_head(dst + vi * 16, o, tail.tail_elems * kOutBytes);
+                else
+                    store_vector<RAGGED>(dst + vi * 16, o);
+            }
         }
     };
     if constexpr (R == 2) {
@@ -244,12 +354,12 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
 // ---------------------------------------------------------------------------
 // One block (four waves) per row, for rows beyond a wave's registers (16384 < Lk <= 65536):
 // thread t holds vectors t, t + 256, ...; the maximum and the sum cross waves through LDS.
-// Same arithmetic and the same padding rule as the kernel above.
+// Same arithmetic, the same padding rule and the same RAGGED forms as the kernel above.
 // ---------------------------------------------------------------------------
-template <int V, int MODE>
+template <int V, int MODE, bool RAGGED>
 __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__restrict__ logits,
-                                                             uint8_t *__restrict__ out, int Lq, int nvec,
-                                                             BlockPlace place, HeadTable table)
+                                                             uint8_t *__restrict__ out, int Lq, int n,
+                                                             uint32_t last_slab, BlockPlace place, HeadTable table)
 {
     constexpr int kOutBytes = (MODE & 1) ? 2 : 1;
     constexpr int DW = 4 / kOutBytes;
@@ -262,23 +372,23 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
     place.locate(tile, head, slab_no);
     const int4 hp = table.e[head];
     const int B = hp.x, S = hp.y, D = hp.z;
-    const int n = nvec * kVecBytes;
+    const int nvec = RAGGED ? (n + kVecBytes - 1) / kVecBytes : n / kVecBytes;
+    const RowTail<DW> tail(n, nvec);
     const size_t row = (size_t)slab_no * (size_t)Lq + tile;
     const int8_t *src = logits + row * (size_t)n;
     uint8_t *dst = out + row * (size_t)n * kOutBytes;
+    const bool last_row = RAGGED && slab_no == last_slab && (int)tile == Lq - 1 && tail.tail_elems < kVecBytes;
 
     uint32_t d[V][DW];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int vi = v * 256 + tid;
         if (vi < nvec) {
-            if constexpr (DW == 4) {
-                const u32x4 t = load_stream(src + vi * 16);
-                d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
-            } else {
-                const u32x2 t = load_stream8(src + vi * 8);
-                d[v][0] = t[0], d[v][1] = t[1];
-            }
+            if (RAGGED && last_row && vi == tail.last_vec)
+                load_vector_bytes<DW>(src + vi * kVecBytes, tail.tail_elems, d[v]);
+            else
+                load_vector<DW, RAGGED>(src + vi * kVecBytes, d[v]);
+            if (RAGGED && vi == tail.last_vec) tail.pad(d[v]);
         } else {
 #pragma unroll
             for (int c = 0; c < DW; ++c) d[v][c] = kPadWord;
@@ -301,235 +411,12 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
     for (int v = 0; v < V; ++v) {
         const int vi = v * 256 + tid;
         const u32x4 o = ro.vector(d[v]);
-        if (vi < nvec) store_stream(dst + vi * 16, o);
-    }
-}
-
-// ---------------------------------------------------------------------------
-// Rows of any length on 16-byte aligned tensors: row r starts at byte r*n of the input, which
-// is aligned to an input vector only when n is a multiple of the vector size VB (16 bytes in the
-// 8-bit modes, 8 bytes in the 16-bit modes, so that an output vector is 16 bytes in both).  A
-// lane group loads the ALIGNED vectors that cover the row; bytes of the first and last vector
-// that belong to the neighbouring rows are overwritten with -128 before use, i.e. they become
-// padding (identity of the maximum, known distance, taken out of the sum like every other pad).
-// Element positions are kept, so a lane's result is an aligned 16-byte vector of the output as
-// well, and one set of masks serves both.
-//
-// Interior vectors are stored whole.  The vector in which one row ends and the next begins is
-// put together inside the block: the upper row leaves its part of it in LDS, the lower row's
-// first lane adds its own and stores the whole vector.  Rows are numbered through the whole
-// tensor (the head comes from the row number), a block owns 4*(64/G) consecutive rows, and
-// that is a multiple of 16 rows whenever G <= 16: then every block begins and ends on a vector
-// boundary.  Only where it does not (longer rows of odd length, the end of the tensor) the
-// first and last vector of a block are stored element by element, in branches that whole waves
-// skip.  With LONG = false (rows shorter than a vector, which can then hold several rows) every
-// boundary vector is stored element by element instead.
-// ---------------------------------------------------------------------------
-template <int G, int V, int MODE, bool LONG>
-__global__ __launch_bounds__(256) void hccs_rows_ragged_kernel(const int8_t *__restrict__ logits,
-                                                               uint8_t *__restrict__ out, uint32_t rows,
-                                                               uint32_t first, FastDiv by_Lq, FastDiv by_H, int n,
-                                                               HeadTable table)
-{
-    // `logits` and `out` are the tensors' base addresses rounded down to a vector boundary; the
-    // tensor's first element sits `first` input bytes (elements) behind them in both.
-    constexpr int kOutBytes = (MODE & 1) ? 2 : 1;   // bytes per output element
-    constexpr int DW = 4 / kOutBytes;               // dwords per input vector
-    constexpr int VB = DW * 4;                      // bytes per input vector
-    constexpr int kRowsPerWave = 64 / G;
-    constexpr int kRowsPerBlock = 4 * kRowsPerWave;
-    constexpr int kPaddedLen = G * V * VB;
-    __shared__ int4 lds_table[64];
-    __shared__ __attribute__((aligned(16))) u32x4 lds_tail[kRowsPerBlock];
-    __shared__ __attribute__((aligned(16))) u32x4 lds_low[VB + 1];   // entry c: the low c input bytes of a vector set
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int sub = lane % G, grp = lane / G;
-    if (tid < 64) lds_table[tid] = table.e[tid];
-    if (tid >= 64 && tid < 64 + VB + 1) {
-        const int c = tid - 64;
-        u32x4 mk = {0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < DW; ++j) {
-            const int cj = c - 4 * j;
-            mk[j] = cj >= 4 ? 0xffffffffu : (cj <= 0 ? 0u : ((1u << (8 * cj)) - 1u));
+        if (vi < nvec) {
+            if (RAGGED && vi == tail.last_vec && tail.tail_elems < kVecBytes)
+                store_vector_head(dst + vi * 16, o, tail.tail_elems * kOutBytes);
+            else
+                store_vector<RAGGED>(dst + vi * 16, o);
         }
-        lds_low[c] = mk;
-    }
-    __syncthreads();
-
-    const int rib = wave * kRowsPerWave + grp;                  // row inside the block
-    const uint32_t row_raw = blockIdx.x * (uint32_t)kRowsPerBlock + (uint32_t)rib;
-    const bool live = row_raw < rows;
-    const uint32_t row = live ? row_raw : 0;
-    const uint32_t slab = by_Lq.quotient(row);
-    const int4 hp = lds_table[slab - by_H.quotient(slab) * by_H.divisor];
-    const int B = hp.x, S = hp.y, D = hp.z;
-    const size_t total = (size_t)first + (size_t)rows * (size_t)n;   // end of the tensor
-    const size_t begin = (size_t)first + (size_t)row * (size_t)n;    // first byte of the row in the input
-    const size_t base = begin & ~(size_t)(VB - 1);        // aligned start of the covering vectors
-    const int lo = (int)(begin - base), hi = lo + n;      // the row is bytes [lo, hi) relative to base
-    const int nspan = (hi + VB - 1) / VB;                 // vectors that touch the row
-
-    // input bytes of vector vi that belong to the row: offsets k of the span with lo <= k < hi
-    struct Mask {
-        uint32_t w[DW];
-    };
-    auto own_bytes = [&](int vi) -> Mask {
-        const u32x4 below = lds_low[min(max(lo - VB * vi, 0), VB)], upto = lds_low[min(max(hi - VB * vi, 0), VB)];
-        Mask mk;
-#pragma unroll
-        for (int c = 0; c < DW; ++c) mk.w[c] = upto[c] & ~below[c];
-        return mk;
-    };
-    // the same as a mask over the 16 output bytes of the vector
-    auto own_out = [&](int vi) -> u32x4 {
-        const Mask mk = own_bytes(vi);
-        if constexpr (DW == 4) {
-            return (u32x4){mk.w[0], mk.w[1], mk.w[2], mk.w[3]};
-        } else {
-            return (u32x4){__builtin_amdgcn_perm(mk.w[0], mk.w[0], 0x01010000u),
-                           __builtin_amdgcn_perm(mk.w[0], mk.w[0], 0x03030202u),
-                           __builtin_amdgcn_perm(mk.w[1], mk.w[1], 0x01010000u),
-                           __builtin_amdgcn_perm(mk.w[1], mk.w[1], 0x03030202u)};
-        }
-    };
-
-    uint32_t d[V][DW];
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        const int vi = v * G + sub;
-        if (live && vi < nspan) {
-            const size_t at = base + (size_t)vi * VB;
-            if (at >= first && at + VB <= total) {
-                if constexpr (DW == 4) {
-                    const u32x4 t = load_stream(logits + at);
-                    d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
-                } else {
-                    const u32x2 t = load_stream8(logits + at);
-                    d[v][0] = t[0], d[v][1] = t[1];
-                }
-            } else {                                      // the tensor begins or ends inside this vector: no read outside it
-#pragma unroll
-                for (int c = 0; c < DW; ++c) {
-                    uint32_t w = 0;
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const size_t k = at + 4 * c + b;
-                        w |= (uint32_t)(k >= first && k < total ? (uint8_t)logits[k] : 0x80u) << (8 * b);
-                    }
-                    d[v][c] = w;
-                }
-            }
-            if (vi == 0 || vi == nspan - 1) {             // boundary vectors: foreign bytes become padding
-                const Mask mk = own_bytes(vi);
-#pragma unroll
-                for (int c = 0; c < DW; ++c) d[v][c] = (d[v][c] & mk.w[c]) | (kPadWord & ~mk.w[c]);
-            }
-        } else {
-#pragma unroll
-            for (int c = 0; c < DW; ++c) d[v][c] = kPadWord;
-        }
-    }
-
-    const int m = group_max<G>(lane_max(d));
-    const uint32_t mu = (uint32_t)(m + 128);
-    const int t = group_sum<G>(lane_distances(d, m, D));
-    const RowOutput<MODE> ro((uint32_t)(n * B - S * clamped_sum(t, kPaddedLen, n, mu, D)), B, S, D);
-
-    // own elements of a boundary vector, one at a time
-    auto store_elements = [&](uint8_t *dst, const u32x4 &o, int vi) {
-#pragma unroll
-        for (int e = 0; e < VB; ++e) {
-            const int kk = VB * vi + e;                   // input byte = element number
-            if (kk >= lo && kk < hi) {
-                if constexpr (kOutBytes == 1)
-                    dst[e] = (uint8_t)(o[e >> 2] >> (8 * (e & 3)));
-                else
-                    ((uint16_t *)dst)[e] = (uint16_t)(o[e >> 1] >> (16 * (e & 1)));
-            }
-        }
-    };
-    // the row's last vector is shared with the next row, which is in this block and exists
-    const bool tail_shared = (hi % VB) != 0;
-    const bool tail_to_lds = LONG && live && tail_shared && rib + 1 < kRowsPerBlock && row_raw + 1 < rows;
-    const bool head_shared = lo != 0;
-    const bool head_from_lds = LONG && live && head_shared && rib > 0;
-    u32x4 head_o = {0, 0, 0, 0};
-    uint8_t *out_base = out + base * kOutBytes;
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        const int vi = v * G + sub;
-        if (!live || vi >= nspan) continue;
-        u32x4 o = ro.vector(d[v]);
-        uint8_t *dst = out_base + (size_t)vi * 16;
-        if (VB * vi >= lo && VB * vi + VB <= hi) {
-            store_stream(dst, o);
-        } else if (v == 0 && vi == 0 && head_from_lds) {
-            const u32x4 mk = own_out(0);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) head_o[c] = o[c] & mk[c];   // finished after the barrier
-        } else if (vi == nspan - 1 && tail_to_lds) {
-            const u32x4 mk = own_out(vi);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) o[c] &= mk[c];
-            lds_tail[rib] = o;
-        } else {
-            store_elements(dst, o, vi);
-        }
-    }
-    if constexpr (LONG) {
-        __syncthreads();
-        if (sub == 0 && head_from_lds) {
-            const u32x4 above = lds_tail[rib - 1];
-            store_stream(out_base, (u32x4){head_o[0] | above[0], head_o[1] | above[1], head_o[2] | above[2],
-                                           head_o[3] | above[3]});
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------
-// One block per row, any length and alignment: the plain integer form of
-// Alg. 1 with byte accesses.  Slow; it exists so that every admissible shape
-// has a path.  Three passes over the row (the second and third re-read it
-// through the caches), LDS for the cross-wave maximum and sum.
-// ---------------------------------------------------------------------------
-template <int MODE>
-__global__ __launch_bounds__(256) void hccs_row_bytes_kernel(const int8_t *__restrict__ logits,
-                                                             uint8_t *__restrict__ out, int Lq, int n,
-                                                             BlockPlace place, HeadTable table)
-{
-    __shared__ int red[4];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t tile, head, slab_no;   // one block per row: the tile is the row inside the slab
-    place.locate(tile, head, slab_no);
-    const int4 hp = table.e[head];
-    const int B = hp.x, S = hp.y, D = hp.z;
-    const size_t row = (size_t)slab_no * (size_t)Lq + tile;
-    const int8_t *x = logits + row * (size_t)n;
-
-    int m = -128;
-    for (int i = threadIdx.x; i < n; i += 256) m = max(m, (int)x[i]);
-    m = group_max<64>(m);
-    if (lane == 0) red[wave] = m;
-    __syncthreads();
-    m = max(max(red[0], red[1]), max(red[2], red[3]));
-    __syncthreads();
-
-    int z = 0;
-    for (int i = threadIdx.x; i < n; i += 256) z += B - S * min(m - (int)x[i], D);
-    z = group_sum<64>(z);
-    if (lane == 0) red[wave] = z;
-    __syncthreads();
-    const uint32_t Z = (uint32_t)(red[0] + red[1] + red[2] + red[3]);
-    const uint32_t rho = reciprocal_for_mode<MODE>(Z);
-    // 8-bit modes: every thread reads only the bytes it later overwrites, so in-place use is safe
-    for (int i = threadIdx.x; i < n; i += 256) {
-        const uint32_t s = (uint32_t)(B - S * min(m - (int)x[i], D));
-        const uint32_t p = scale_score<MODE>(s, rho);
-        if constexpr (MODE & 1)
-            ((uint16_t *)out)[row * (size_t)n + i] = (uint16_t)p;
-        else
-            out[row * (size_t)n + i] = (uint8_t)p;
     }
 }
 
@@ -570,98 +457,71 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src
 // ---------------------------------------------------------------------------
 // host side: choose the lane-group shape for a row length
 // ---------------------------------------------------------------------------
-template <int G, int V, int R, int WPB = 4, int MODE = kModeU8>
-static hipError_t launch_rows(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int nvec,
-                              const HeadTable &tab, hipStream_t st)
+template <int G, int V, int R, int WPB, int MODE, bool RAGGED>
+static hipError_t launch_rows(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int n, const HeadTable &tab,
+                              hipStream_t st)
 {
     constexpr int kRowsPerBlock = WPB * R * (64 / G);
     dim3 grid;
     const BlockPlace place = place_blocks((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt, grid);
-    return launch(hccs_rows_kernel<G, V, R, WPB, MODE>, grid, dim3(64 * WPB), st, x, p, Lq, nvec, place, tab);
+    return launch(hccs_rows_kernel<G, V, R, WPB, MODE, RAGGED>, grid, dim3(64 * WPB), st, x, p, Lq, n,
+                  (uint32_t)(Bt * H - 1), place, tab);
+}
+
+template <int MODE, bool RAGGED>
+static hipError_t launch_shape(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
+                               hipStream_t st)
+{
+    constexpr int VB = (MODE & 1) ? 8 : 16;   // input bytes per vector
+    const int nvec = (Lk + VB - 1) / VB;
+    if (Lk <= 16384) {                        // a wave holds the row
+        // Lane-group width G: a power of two that covers the row with one or two vectors
+        // per lane, so that each load/store instruction touches G contiguous vectors of a
+        // row; beyond 128 vectors the row takes V vectors per lane of a whole wave.  Few rows
+        // in flight per wave (R) and many waves measured faster than the reverse; with vectors
+        // at any address one row batch per wave measured best ([64,12,197,197]: 15.3 against
+        // 16.0 us, [256,8,128,250]: 26.2 against 29.4 us).
+        constexpr int R = RAGGED ? 1 : 2;
+        if (nvec <= 4) return launch_rows<4, 1, R, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
+        if (nvec <= 8) return launch_rows<8, 1, R, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
+        if (nvec <= 16) return launch_rows<16, 1, R, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
+        if (nvec <= 32) return launch_rows<16, 2, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
+        if (nvec <= 64) return launch_rows<32, 2, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);   // measured against <64,1,2>: up to 20 % faster below 48 vectors, equal at 64
+        if (nvec <= 128) return launch_rows<64, 2, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
+        if (nvec <= 256) return launch_rows<64, 4, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
+        if (nvec <= 512) return launch_rows<64, 8, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
+        if (nvec <= 1024) return launch_rows<64, 16, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
+        return launch_rows<64, 32, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);   // 16-bit modes, 8192 < Lk <= 16384
+    }
+    // 16384 < Lk <= 65536: one block per row, the row in the block's registers
+    dim3 grid;
+    const BlockPlace place = place_blocks(Lq, H, Bt, grid);
+    const uint32_t last_slab = (uint32_t)(Bt * H - 1);
+    if (nvec <= 2048)
+        return launch(hccs_row_block_kernel<8, MODE, RAGGED>, grid, dim3(256), st, x, p, Lq, Lk, last_slab, place, tab);
+    // at most 4096 vectors: Lk <= 65536 in the 8-bit modes, and the 16-bit modes need Lk*B <= 32767
+    return launch(hccs_row_block_kernel<16, MODE, RAGGED>, grid, dim3(256), st, x, p, Lq, Lk, last_slab, place, tab);
 }
 
 template <int MODE>
 static hipError_t launch_mode(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
-                              bool vector_ok, hipStream_t st)
+                              bool aligned, hipStream_t st)
 {
-    if (vector_ok && Lk % ((MODE & 1) ? 8 : 16) == 0 && Lk <= 16384) {
-        // Lane-group width G: a power of two that covers the row with one or two vectors
-        // per lane, so that each load/store instruction touches G contiguous vectors of a
-        // row; beyond 128 vectors the row takes V vectors per lane of a whole wave.  Few rows
-        // in flight per wave (R) and many waves measured faster than the reverse.
-        const int nvec = Lk / ((MODE & 1) ? 8 : 16);
-        if (nvec <= 4) return launch_rows<4, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        if (nvec <= 8) return launch_rows<8, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        if (nvec <= 16) return launch_rows<16, 1, 2, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        if (nvec <= 32) return launch_rows<16, 2, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        if (nvec <= 64) return launch_rows<32, 2, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // measured against <64,1,2>: up to 20 % faster below 48 vectors, equal at 64
-        if (nvec <= 128) return launch_rows<64, 2, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        if (nvec <= 256) return launch_rows<64, 4, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        if (nvec <= 512) return launch_rows<64, 8, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        if (nvec <= 1024) return launch_rows<64, 16, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);
-        return launch_rows<64, 32, 1, 4, MODE>(x, p, Bt, H, Lq, nvec, tab, st);   // 16-bit modes, 8192 < Lk <= 16384
-    }
-    {
-        // Ragged row length, or tensors that begin inside a vector at matching offsets (element e
-        // of the input `first` bytes behind a vector boundary, element e of the output behind a
-        // 16-byte boundary by as many elements): aligned vectors over each row's span.
-        constexpr int VB = (MODE & 1) ? 8 : 16;   // input bytes per vector
-        constexpr int kOutBytes = (MODE & 1) ? 2 : 1;
-        const int64_t rows = Bt * H * Lq;
-        const uint32_t first = (uint32_t)((uintptr_t)x % VB);
-        const bool matching = (uintptr_t)p % 16 == (uintptr_t)first * kOutBytes;
-        if (matching && Lk <= 16384 - 32) {
-            // widest span of a row over aligned vectors: rows start at first + multiples of gcd(Lk, VB)
-            const int step = (Lk & -Lk & (VB - 1)) ? (Lk & -Lk & (VB - 1)) : VB;
-            const int nspan = (VB - step + (int)(first % step) + Lk + VB - 1) / VB;
-            const int8_t *x_al = x - first;
-            uint8_t *p_al = p - first * kOutBytes;
-#define HCCS_LAUNCH_RAGGED(G_, V_, LONG_)                                                                    \
-    {                                                                                                      \
-        const int64_t per_block = 4 * (64 / G_);                                                           \
-        return launch(hccs_rows_ragged_kernel<G_, V_, MODE, LONG_>,                                         \
-                      dim3((uint32_t)((rows + per_block - 1) / per_block)), dim3(256), st, x_al, p_al,      \
-                      (uint32_t)rows, first, make_fast_div((uint32_t)Lq), make_fast_div((uint32_t)H), Lk,   \
-                      tab);                                                                                 \
-    }
-            if (Lk < VB) HCCS_LAUNCH_RAGGED(4, 1, false)
-            if (nspan <= 4) HCCS_LAUNCH_RAGGED(4, 1, true)
-            if (nspan <= 8) HCCS_LAUNCH_RAGGED(8, 1, true)
-            // measured: two vectors per lane in a narrower group beat one per lane in a wide,
-            // half-empty one (the per-row index and mask work is shared by more payload)
-            if (nspan <= 12) HCCS_LAUNCH_RAGGED(8, 2, true)
-            if (nspan <= 16) HCCS_LAUNCH_RAGGED(16, 1, true)
-            if (nspan <= 32) HCCS_LAUNCH_RAGGED(16, 2, true)
-            if (nspan <= 64) HCCS_LAUNCH_RAGGED(32, 2, true)
-            if (nspan <= 128) HCCS_LAUNCH_RAGGED(32, 4, true)
-            if (nspan <= 256) HCCS_LAUNCH_RAGGED(64, 4, true)
-            if (nspan <= 512) HCCS_LAUNCH_RAGGED(64, 8, true)
-            if (nspan <= 1024) HCCS_LAUNCH_RAGGED(64, 16, true)
-            HCCS_LAUNCH_RAGGED(64, 32, true)
-#undef HCCS_LAUNCH_RAGGED
-        }
-    }
-    dim3 grid;
-    const BlockPlace place = place_blocks(Lq, H, Bt, grid);   // one block per row
-    if (vector_ok && Lk % 16 == 0) {   // 16384 < Lk <= 65536: one block per row, the row in the block's registers
-        const int nvec = Lk / ((MODE & 1) ? 8 : 16);
-        if (nvec <= 2048) return launch(hccs_row_block_kernel<8, MODE>, grid, dim3(256), st, x, p, Lq, nvec, place, tab);
-        // at most 4096: Lk <= 65536 in the 8-bit modes, and the 16-bit modes need Lk*B <= 32767
-        return launch(hccs_row_block_kernel<16, MODE>, grid, dim3(256), st, x, p, Lq, nvec, place, tab);
-    }
-    return launch(hccs_row_bytes_kernel<MODE>, grid, dim3(256), st, x, p, Lq, Lk, place, tab);
+    // aligned vectors when both tensors begin on a 16-byte boundary and rows are whole vectors
+    if (aligned && Lk % ((MODE & 1) ? 8 : 16) == 0) return launch_shape<MODE, false>(x, p, Bt, H, Lq, Lk, tab, st);
+    return launch_shape<MODE, true>(x, p, Bt, H, Lq, Lk, tab, st);
 }
 
 hipError_t launch_softmax(const int8_t *x, void *out, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
-                          int mode, bool vector_ok, hipStream_t st)
+                          int mode, bool aligned, hipStream_t st)
 {
     if (Bt == 0 || Lq == 0) return hipSuccess;
     uint8_t *p = (uint8_t *)out;
     switch (mode) {
-        case kModeU8: return launch_mode<kModeU8>(x, p, Bt, H, Lq, Lk, tab, vector_ok, st);
-        case kModeI16: return launch_mode<kModeI16>(x, p, Bt, H, Lq, Lk, tab, vector_ok, st);
-        case kModeClbU8: return launch_mode<kModeClbU8>(x, p, Bt, H, Lq, Lk, tab, vector_ok, st);
-        case kModeClbI16: return launch_mode<kModeClbI16>(x, p, Bt, H, Lq, Lk, tab, vector_ok, st);
+        case kModeU8: return launch_mode<kModeU8>(x, p, Bt, H, Lq, Lk, tab, aligned, st);
+        case kModeI16: return launch_mode<kModeI16>(x, p, Bt, H, Lq, Lk, tab, aligned, st);
+        case kModeClbU8: return launch_mode<kModeClbU8>(x, p, Bt, H, Lq, Lk, tab, aligned, st);
+        case kModeClbI16: return launch_mode<kModeClbI16>(x, p, Bt, H, Lq, Lk, tab, aligned, st);
         default: return hipErrorInvalidValue;
     }
 }

@@ -47,7 +47,7 @@ def mixed_logits(shape, seed):
     return np.clip(np.rint(x), -128, 127).astype(np.int8)
 
 
-# every lane-group shape of the register kernel, full tiles and ragged tails, plus the byte kernel
+# every lane-group shape of the register kernel, full tiles and ragged tails
 SHAPES = [
     ((1, 4, 64, 64), 1), ((3, 8, 37, 128), 1), ((2, 3, 50, 16), 1), ((2, 2, 33, 32), 1), ((2, 2, 20, 48), 1),
     ((1, 2, 21, 96), 1), ((1, 2, 19, 112), 1), ((1, 3, 9, 256), 1), ((1, 2, 7, 208), 1), ((2, 12, 40, 512), 1),
@@ -98,7 +98,7 @@ def test_softmax_in_place_and_unaligned(oracle):
     out = binding.calibrated_softmax_i8(t, table, 1, out=t.view(torch.uint8))
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), want)
-    # misaligned base pointers take the byte-granular kernel
+    # misaligned base pointers, input and output at different offsets inside a 16-byte line
     buf_in = torch.zeros(x.size + 16, dtype=torch.int8, device="cuda")
     buf_out = torch.zeros(x.size + 16, dtype=torch.uint8, device="cuda")
     buf_in[1:1 + x.size] = torch.from_numpy(x).cuda().view(-1)
@@ -109,8 +109,8 @@ def test_softmax_in_place_and_unaligned(oracle):
     assert int(buf_out[:3].sum()) == 0 and int(buf_out[3 + x.size:].sum()) == 0
 
 
-# ragged row lengths on aligned tensors: every lane-group shape of the masked-ends kernel, rows
-# that start at every offset inside a 16-byte line, its longest length and the first one past it
+# ragged row lengths: every lane-group shape of the kernel, rows that start at every offset inside a
+# 16-byte line, the longest register-resident length and the first one past it
 RAGGED_SHAPES = [
     ((2, 3, 40, 1), 1), ((1, 2, 33, 7), 1), ((1, 2, 70, 33), 1), ((2, 2, 50, 49), 1), ((1, 3, 37, 50), 1),
     ((1, 2, 19, 100), 1), ((2, 2, 33, 113), 1), ((1, 2, 21, 127), 1), ((1, 2, 35, 129), 1), ((1, 2, 18, 225), 1),
@@ -118,6 +118,10 @@ RAGGED_SHAPES = [
     ((1, 1, 5, 3000), 0), ((1, 1, 3, 4099), 0), ((1, 1, 3, 8100), 0), ((1, 1, 3, 16351), 0), ((1, 1, 2, 16353), 0),
     ((2, 3, 197, 197), 0), ((1, 5, 77, 77), 1), ((3, 2, 61, 250), 1), ((1, 2, 130, 999), 0), ((1, 64, 5, 21), 1),
     ((1, 2, 40, 500), 0), ((1, 2, 9, 1000), 0), ((1, 3, 33, 104), 1), ((1, 2, 21, 2040), 0), ((1, 2, 19, 252), 1),
+    # slabs shorter than a vector (the guard on the tensor's last vectors spans several rows and slabs)
+    ((7, 3, 1, 5), 1), ((2, 2, 2, 3), 1), ((1, 1, 1, 1), 1), ((1, 1, 1, 15), 1), ((3, 1, 1, 17), 1), ((9, 1, 1, 2), 1),
+    # ragged lengths beyond a wave's registers: one block per row
+    ((1, 2, 2, 16401), 0), ((1, 1, 3, 40001), 0), ((1, 1, 2, 65535), 0), ((2, 1, 1, 32777), 0),
 ]
 
 
@@ -184,6 +188,34 @@ def test_softmax_tensors_that_begin_inside_a_vector(oracle, shape, off):
         got16 = buf16[8 + o8:8 + o8 + x.size].view(shape).cpu().numpy().view(np.uint16)
         assert np.array_equal(got16, want16)
         assert bool((buf16[:8 + o8] == 0x5A5A).all()) and bool((buf16[8 + o8 + x.size:] == 0x5A5A).all())
+
+
+@pytest.mark.parametrize("shape,off_in,off_out", [((2, 4, 30, 128), 3, 11), ((1, 3, 33, 100), 7, 0),
+                                                  ((1, 2, 9, 4099), 1, 14), ((1, 1, 2, 20001), 5, 9),
+                                                  ((2, 2, 40, 64), 0, 13), ((1, 2, 3, 16384), 2, 2)])
+def test_softmax_tensors_at_unrelated_offsets(oracle, shape, off_in, off_out):
+    """Input and output begin at unrelated offsets inside a 16-byte line, in the 8-bit and (2-byte
+    aligned) 16-bit output modes; canaries around the outputs."""
+    H, n = shape[1], shape[3]
+    band = 1 if n * 8 <= 32767 else 0
+    table = synth.head_params(H, n, band, seed=n + H)
+    x = mixed_logits(shape, seed=sum(shape) + off_in)
+    print(f"case offsets shape={shape} in={off_in} out={off_out}", flush=True)
+    buf_in = torch.zeros(x.size + 64, dtype=torch.int8, device="cuda")
+    buf_in[off_in:off_in + x.size] = torch.from_numpy(x).cuda().view(-1)
+    t_in = buf_in[off_in:off_in + x.size].view(shape)
+    for mode, T, recip in ((0, 255, 0), (2, 255, 1)) + (((1, 32767, 0), (3, 32767, 1)) if band == 1 else ()):
+        want, rc = oracle.softmax(x, table, band, mode=mode, threads=THREADS)
+        assert rc == 0
+        canary = 0x5A if T == 255 else 0x5A5A
+        buf = torch.full((x.size + 64,), canary, dtype=torch.uint8 if T == 255 else torch.int16, device="cuda")
+        t_out = buf[off_out:off_out + x.size].view(shape)
+        binding.calibrated_softmax_i8_ex(t_in, table, band, out_scale_T=T, reciprocal=recip, out=t_out)
+        torch.cuda.synchronize()
+        got = t_out.cpu().numpy()
+        got = got.view(np.uint16) if T == 32767 else got
+        assert np.array_equal(got, want), f"mode {mode}"
+        assert bool((buf[:off_out] == canary).all()) and bool((buf[off_out + x.size:] == canary).all())
 
 
 def test_empty_tensors_and_size_limits(oracle):
@@ -285,7 +317,7 @@ MODE_SHAPES = [
     ((1, 2, 5, 100), 1), ((1, 1, 4, 17), 1), ((1, 2, 3, 1), 1), ((1, 1, 2, 20000), 1),
     ((1, 2, 5, 1024), 0), ((1, 2, 3, 4096), 0), ((1, 1, 3, 255), 0),
     ((1, 2, 2, 32752), 1), ((1, 1, 3, 16400), 1), ((1, 1, 2, 40000), 0),
-    # ragged lengths: masked-ends kernel in every mode (8-byte input vectors in the 16-bit modes)
+    # ragged lengths in every mode (8-byte input vectors in the 16-bit modes)
     ((2, 3, 197, 197), 1), ((1, 2, 40, 500), 1), ((1, 2, 33, 24), 1), ((1, 2, 9, 1000), 1), ((1, 2, 7, 8200), 1),
     ((1, 3, 70, 7), 1), ((1, 2, 21, 127), 1), ((1, 2, 50, 9), 1), ((1, 1, 3, 16351), 1), ((1, 2, 5, 2047), 1),
     ((1, 2, 130, 129), 0), ((1, 2, 19, 72), 1), ((1, 1, 5, 16376), 1),
