@@ -555,6 +555,20 @@ def test_attention_streaming_shapes(oracle, Bt, H, Lq, Lk, d, band):
     check_attention(q, k, v, table, rq, band, oracle, "streaming")
 
 
+def test_attention_streaming_benchmark_shape_and_long_three_pass(oracle):
+    """The streaming shape the benchmark times, [4,12,2048,2048,64] (two-pass kernel), at full size
+    with the benchmark's own inputs, and three-pass cases beyond 4096 keys with several query tiles."""
+    g = np.random.default_rng(7)
+    Bs, Hs, Ls, ds = 4, 12, 2048, 64
+    q, k, v = (g.integers(-64, 64, size=(Bs, Hs, Ls, ds), dtype=np.int8) for _ in range(3))
+    check_attention(q, k, v, synth.head_params(Hs, Ls, synth.BAND_U8, seed=11), synth.requant_params(Hs, seed=11),
+                    synth.BAND_U8, oracle, "benchmark streaming shape")
+    for Bt, H, Lq, Lk, d in ((1, 2, 256, 4096, 64), (1, 2, 320, 4160, 128), (1, 1, 257, 5000, 64)):
+        q, k, v = rect_qkv(Lq + Lk, Bt, H, Lq, Lk, d)
+        check_attention(q, k, v, synth.head_params(H, Lk, 0, seed=Lk), synth.requant_params(H, seed=Lk), 0, oracle,
+                        "three-pass")
+
+
 def test_attention_streaming_rescale_kinds_and_extremes(oracle):
     """Every rescale form of the streaming kernel, full-range inputs, d = 128 (|acc| up to 2^21)."""
     g = np.random.default_rng(12)
