@@ -279,10 +279,14 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
     const bool near_end = RAGGED && over_read > 0 && rows_behind_slab * (uint64_t)n < (uint64_t)over_read;
 
     uint32_t d[R][V][DW];
+    uint32_t row_off[R];   // element offset of each batch's row from that of the wave's first row
+#pragma unroll
+    for (int j = 0; j < R; ++j) row_off[j] = (uint32_t)(j * kRowsPerBatch) * (uint32_t)n;
+    const size_t first_elem = (slab + row0) * (size_t)n + (size_t)sub * kVecBytes;   // the lane's first vector
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const int row = row0 + j * kRowsPerBatch;
-        const int8_t *src = logits + (slab + row) * (size_t)n;
+        const int8_t *src = logits + first_elem + row_off[j] - sub * kVecBytes;
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             const int vi = v * G + sub;
@@ -318,7 +322,7 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
     };
     auto emit = [&](int j, const RowOutput<MODE> &ro) {
         const int row = row0 + j * kRowsPerBatch;
-        uint8_t *dst = out + (slab + row) * (size_t)n * kOutBytes;
+        uint8_t *dst = out + (first_elem + row_off[j] - sub * kVecBytes) * kOutBytes;
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             const int vi = v * G + sub;

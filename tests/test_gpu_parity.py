@@ -599,6 +599,24 @@ def test_attention_streaming_equals_resident_definition(oracle):
     assert torch.equal(o_str[:, :, :128], o_res) and torch.equal(o_str[:, :, 128], o_res[:, :, 0])
 
 
+@pytest.mark.parametrize("Bt,H", [(257, 2), (65, 8)])
+def test_attention_many_items_every_rescale_form(oracle, Bt, H):
+    """Square blocks of 256 keys, more (batch, head) items than two per compute unit: probabilities
+    below and above 127 and every rescale form, full-range inputs."""
+    g = np.random.default_rng(Bt)
+    shape = (Bt, H, 256, 64)
+    q, k, v = (g.integers(-128, 128, size=shape, dtype=np.int8) for _ in range(3))
+    strict = synth.head_params(H, 256, 1, seed=Bt)                       # B <= 127: P <= 127 for every row
+    wide = synth.head_params(H, 256, 0, seed=Bt)
+    wide[0] = (32640, 127, 127)                                          # one dominant key takes P to 255
+    assert binding.validate_params(wide, 256, 0) == (0, -1)
+    for table, band in ((strict, 1), (wide, 0)):
+        for rq in ([[100 + h, 16] for h in range(H)], [[900 + h, 20] for h in range(H)],
+                   [[4096 - h, 24 - (h % 3)] for h in range(H)]):
+            check_attention(q, k, v, table, np.array(rq, np.int32), band, oracle,
+                            f"items={Bt * H} band={band} rq={rq[0]}")
+
+
 def test_attention_full_size(oracle):
     w = synth.make_workload("fused_attention")
     check_attention(w["q"], w["k"], w["v"], w["table"], w["requant"], w["band"], oracle, "full")
