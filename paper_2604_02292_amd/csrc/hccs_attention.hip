@@ -210,6 +210,311 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
     }
 }
 
+// ---------------------------------------------------------------------------
+// The block of 256 keys in another form: K and V go straight from memory into LDS
+// (global_load_lds_dwordx4: no staging registers, no staging instructions), V while the first
+// contraction already runs.
+//
+// Both K and V are row-major in LDS (64 bytes per key), as the loads deliver them: an instruction
+// of a wave moves 16 keys, lane l bringing 16 bytes of key l/4.  Which 16 bytes is permuted per
+// key (position p holds chunk p ^ f(key)), so that the operand reads of the matrix unit spread
+// over the LDS banks without padding:
+//   K, f = (key >> 2) & 3: the first contraction reads, per 16 lanes, one chunk of 16 consecutive
+//      keys; their positions 4*key + (chunk ^ f) are 16 different bank groups.
+//   V, f = ((key >> 4) + (key >> 2)) & 3: the second contraction takes its operand through the
+//      transposing read (ds_read_b64_tr_b8), which touches 32 keys per instruction.
+// The second contraction runs transposed (O^T tile = V^T . P^T) like in the streaming kernels, so a
+// lane ends with four consecutive columns of one query per accumulator.
+//
+// The matrix unit multiplies signed bytes and P is unsigned: this kernel is launched only when
+// the host can show P <= 127 for every row the table allows (true for every table of the band of
+// Eq. (11) at 256 keys and more), and P goes in as it is; other tables take the kernel above.
+// ---------------------------------------------------------------------------
+typedef const __attribute__((address_space(1))) void *global_void_ptr;
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+// 16 bytes per lane from global memory into LDS: lane l's bytes land at lds_wave_base + 16*l
+// (the LDS address is wave-uniform, the global address per lane).
+// Written out as an instruction, so that the compiler keeps no record of it: every wait for these
+// loads is placed by hand (s_waitcnt vmcnt and a barrier), where the compiler's own bookkeeping of
+// loads into LDS would also wait for loads that are meant to stay in flight.  M0 carries the LDS
+// address.
+__device__ __forceinline__ void load_to_lds16(const void *global_lane, void *lds_wave_base)
+{
+    const int lds_addr = __builtin_amdgcn_readfirstlane((int)(uintptr_t)(lds_void_ptr)lds_wave_base);
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"   // M0 is reserved; nothing else in these kernels uses it
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(global_lane)
+                 : "memory", "m0");
+#pragma clang diagnostic pop
+}
+
+// Four scores (two 16-bit pairs) -> four bytes P: byte 2 of s*(2*rho) is (s*rho) >> 15.
+__device__ __forceinline__ uint32_t probabilities_plain(uint32_t s01, uint32_t s23, uint32_t rho2)
+{
+    const uint32_t e0 = mad_u32_u16_lo(s01, rho2, 0u), e1 = mad_u32_u16_hi(s01, rho2, 0u);
+    const uint32_t e2 = mad_u32_u16_lo(s23, rho2, 0u), e3 = mad_u32_u16_hi(s23, rho2, 0u);
+    const uint32_t h01 = __builtin_amdgcn_perm(e1, e0, 0x00000602u);
+    const uint32_t h23 = __builtin_amdgcn_perm(e3, e2, 0x00000602u);
+    return __builtin_amdgcn_perm(h23, h01, 0x05040100u);
+}
+
+// One instruction moves 16 rows (1 KiB): lane l brings chunk (l & 3) ^ f(row) of row 16u + l/4 to
+// position l & 3 of that row.  The waves of a block share the NT instructions of an item evenly.
+template <int NT, int WAVES>
+__device__ __forceinline__ void k_rows_to_lds(const int8_t *k_item, uint8_t *k_lds, int wave, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < NT / WAVES; ++i) {
+        const int u = wave + i * WAVES;
+        const int row = 16 * u + (lane >> 2), pos = lane & 3;
+        load_to_lds16(k_item + row * 64 + 16 * (pos ^ ((row >> 2) & 3)), k_lds + u * 1024);
+    }
+}
+template <int NT, int WAVES>
+__device__ __forceinline__ void v_rows_to_lds(const int8_t *v_item, uint8_t *v_lds, int wave, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < NT / WAVES; ++i) {
+        const int u = wave + i * WAVES;
+        const int key = 16 * u + (lane >> 2), pos = lane & 3;
+        load_to_lds16(v_item + key * 64 + 16 * (pos ^ (((key >> 4) + (key >> 2)) & 3)), v_lds + u * 1024);
+    }
+}
+
+// Where a lane finds its operands in LDS.
+struct OperandOffsets {
+    int k;      // K operand of key tile t at t*1024 + k: key 16t + qi, chunk g
+    int v[4];   // V operand, chunk n16, of 64-key group T: first read at T*4096 + v[n16], second at
+                // T*4096 + 2048 + v[n16 ^ 2]
+};
+__device__ __forceinline__ OperandOffsets operand_offsets(int lane)
+{
+    const int qi = lane & 15, g = lane >> 4;
+    OperandOffsets off;
+    off.k = qi * 64 + 16 * (g ^ ((qi >> 2) & 3));
+    // The transposing read: in each group of 16 lanes, lane pair j points at the 16 bytes (chunk n16)
+    // of the key of contraction slot j, the lane's half of them; lane i gets column i.  Slot j of lane
+    // group g is key 16*(j >> 2) + 4g + (j & 3) of the 64-key group (first read; the second read is
+    // 32 keys further, slots 8..15, and its chunk permutation is the first's ^ 2).
+    const int slot = qi >> 1;
+    const int v_key = 16 * (slot >> 2) + 4 * g + (slot & 3);
+    const int v_f = ((slot >> 2) + g) & 3;
+#pragma unroll
+    for (int n16 = 0; n16 < 4; ++n16) off.v[n16] = v_key * 64 + 16 * (n16 ^ v_f) + 8 * (qi & 1);
+    return off;
+}
+
+// Block-wide barrier for data that loads bring into LDS.  Every wave first waits (s_waitcnt vmcnt)
+// for its own loads; the barrier then tells it that everybody else's have landed too.  No release
+// fence: it would wait for every load in flight, also for those meant to overlap with arithmetic,
+// and the waves write LDS by no other means.  The acquire fence keeps later LDS reads behind the
+// barrier.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+// every vector-memory operation of this wave has completed: vmcnt(0), other counters untouched
+__device__ __forceinline__ void wait_vector_memory() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+struct HeadRule {
+    int B, S, D, mult, shift, lim_lo, lim_hi;
+};
+__device__ __forceinline__ HeadRule head_rule(const HeadTable &table, const RequantTable &requant, int head)
+{
+    const int4 hp = table.e[head], rq = requant.e[head];
+    return {hp.x, hp.y, hp.z, rq.x, rq.y, rq.z, rq.w};
+}
+
+// First half of a query tile: A^T tiles = K_tile . Q^T rescaled to 16-bit pairs tile by tile (the K
+// operand of a tile is read from LDS one tile ahead of the contraction that uses it), row maximum,
+// window clamp, sum and scores (Eq. (2), (3), (5)).  Leaves the scores in xp and 2*rho (Eq. (8)).
+template <int NT, int RQ>
+__device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, const v4i &qop, const HeadRule &r,
+                                               short2_t (&xp)[NT][2], uint32_t &rho2)
+{
+    constexpr int L = NT * 16;
+    const int round_c = 1 << (r.shift - 1);
+    short2_t mx2 = {-32768, -32768};
+    auto k_operand = [&](int t) { return *(const v4i *)(k_lds + t * 1024 + k_off); };
+    v4i acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(k_operand(0), qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
+    v4i knext = k_operand(1);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        v4i acc_next = acc;
+        if (t + 1 < NT) acc_next = __builtin_amdgcn_mfma_i32_16x16x64_i8(knext, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
+        if (t + 2 < NT) knext = k_operand(t + 2);
+        rescale_tile<RQ>(acc, r.mult, r.shift, round_c, r.lim_lo, r.lim_hi, xp[t][0], xp[t][1]);
+        mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(xp[t][0], xp[t][1]));
+        acc = acc_next;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    int mx = max((int)mx2.x, (int)mx2.y);
+    mx = max(mx, xor16(mx));
+    mx = max(mx, xor32(mx));
+    const int m = clamp_i32(mx, -128, 127);   // saturation is monotone: max of clamped = clamp of max
+
+    const short lo = (short)max(m - r.D, -128);
+    const short2_t lo2 = {lo, lo}, hi2 = {127, 127};
+    const ushort2_t s2 = {(unsigned short)r.S, (unsigned short)r.S};
+    const unsigned short cc = (unsigned short)(r.B - r.S * m);
+    const ushort2_t c2 = {cc, cc};
+    short2_t sum2 = {0, 0};
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const short2_t xc = __builtin_elementwise_min(__builtin_elementwise_max(xp[t][h], lo2), hi2);
+            sum2 += xc;                            // at most 64 values of magnitude <= 128 per half
+            xp[t][h] = __builtin_bit_cast(short2_t, __builtin_bit_cast(ushort2_t, xc) * s2 + c2);
+        }
+    }
+    int sx = (int)sum2.x + (int)sum2.y;
+    sx += xor16(sx);
+    sx += xor32(sx);
+    const uint32_t Z = (uint32_t)(L * r.B - r.S * (L * m - sx));
+    rho2 = reciprocal_u8(Z) * 2u;                 // <= 65280: fits 16 bits
+}
+
+// Second half: O^T tile = V^T . P^T.  Lane (g, qi) ends with columns 16*n16 + 4g .. +3 of query qi.
+template <int NT>
+__device__ __forceinline__ void weighted_values_of_tile(const uint8_t *v_lds, const int (&v_off)[4],
+                                                        const short2_t (&xp)[NT][2], uint32_t rho2, v4i (&oacc)[4])
+{
+#pragma unroll
+    for (int n16 = 0; n16 < 4; ++n16) oacc[n16] = (v4i){0, 0, 0, 0};
+#pragma unroll
+    for (int T = 0; T < NT / 4; ++T) {
+        v4i vop[4];
+#pragma unroll
+        for (int n16 = 0; n16 < 4; ++n16) {
+            const v2i a = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(v_lds + T * 4096 + v_off[n16]));
+            const v2i b = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(v_lds + T * 4096 + 2048 + v_off[n16 ^ 2]));
+            vop[n16] = (v4i){a[0], a[1], b[0], b[1]};
+        }
+        v4i pop;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            const uint32_t s01 = __builtin_bit_cast(uint32_t, xp[T * 4 + tt][0]);
+            const uint32_t s23 = __builtin_bit_cast(uint32_t, xp[T * 4 + tt][1]);
+            pop[tt] = (int)probabilities_plain(s01, s23, rho2);
+        }
+#pragma unroll
+        for (int n16 = 0; n16 < 4; ++n16)
+            oacc[n16] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop[n16], pop, oacc[n16], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Rows of query tile rt of an item.  As the contraction leaves them, the four lanes (g = 0..3) of a
+// query hold 64 consecutive bytes of its row per accumulator, and a store of one accumulator would
+// write half a 128-byte line of 16 rows: memory takes such halves at little more than half the
+// rate of whole lines.  So neighbouring queries (lanes qi, qi ^ 1) first trade accumulators: the even
+// lane keeps chunk `pair` of both rows, the odd lane chunk `pair + 1`, and each store instruction
+// then writes whole lines of 8 rows.
+template <int NT>
+__device__ __forceinline__ void store_tile(int32_t *o, int item, int rt, int lane, const v4i (&oacc)[4])
+{
+    const int qi = lane & 15, g = lane >> 4;
+    const bool odd = qi & 1;
+    int32_t *dst = o + (size_t)item * (NT * 16) * 64 + (size_t)(rt * 16 + (qi & ~1)) * 64 + 16 * (qi & 1) + 4 * g;
+#pragma unroll
+    for (int pair = 0; pair < 4; pair += 2) {
+        v4i upper, lower;   // rows 2p and 2p + 1 of the lane pair
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int theirs_lo = neighbour_lane(oacc[pair][c]), theirs_hi = neighbour_lane(oacc[pair + 1][c]);
+            upper[c] = odd ? theirs_hi : oacc[pair][c];
+            lower[c] = odd ? oacc[pair + 1][c] : theirs_lo;
+        }
+        __builtin_nontemporal_store(upper, (v4i *)(dst + 16 * pair));
+        __builtin_nontemporal_store(lower, (v4i *)(dst + 64 + 16 * pair));
+    }
+}
+
+// One block per (batch, head) item, NT / WAVES query tiles per wave.  The first contraction starts
+// when K has landed; V is asked for then and lands during it.  (Measured against blocks that take a
+// half or a quarter of an item's queries, and against blocks that stay and take item after item
+// with the next item's loads in flight: at 768 items this form was the fastest.)
+template <int NT, int RQ, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 6) void hccs_attention_direct_kernel(
+    const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v, int32_t *__restrict__ o,
+    int H, HeadTable table, RequantTable requant)
+{
+    constexpr int KV = NT * 16 * 64;       // bytes of K (or V) of one item
+    constexpr int kTiles = NT / WAVES;     // query tiles per wave
+    static_assert(NT % WAVES == 0, "equal shares of tiles and of loads");
+    __shared__ __attribute__((aligned(16))) uint8_t k_lds[KV];
+    __shared__ __attribute__((aligned(16))) uint8_t v_lds[KV];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int qi = lane & 15, g = lane >> 4;
+    const int item = (int)blockIdx.x;
+    const size_t base = (size_t)item * KV;
+
+    k_rows_to_lds<NT, WAVES>(k + base, k_lds, wave, lane);
+    // the Q operands of the wave's tiles: query 16*rt + qi, bytes 16g .. 16g+15
+    v4i qops[kTiles];
+#pragma unroll
+    for (int i = 0; i < kTiles; ++i)
+        qops[i] = *(const v4i *)(q + base + ((wave + i * WAVES) * 16 + qi) * 64 + 16 * g);
+    const HeadRule rule = head_rule(table, requant, item % H);
+    const OperandOffsets off = operand_offsets(lane);
+
+    wait_vector_memory();
+    // The Q registers count as arrived from here on: without this the compiler would wait for them
+    // at their first use, which comes after the V loads, and its wait would cover those too.
+#pragma unroll
+    for (int i = 0; i < kTiles; ++i) asm volatile("" : "+v"(qops[i]));
+    lds_barrier();   // K is in
+    v_rows_to_lds<NT, WAVES>(v + base, v_lds, wave, lane);
+
+#pragma unroll
+    for (int i = 0; i < kTiles; ++i) {
+        short2_t xp[NT][2];
+        uint32_t rho2;
+        scores_of_tile<NT, RQ>(k_lds, off.k, qops[i], rule, xp, rho2);
+        if (i == 0) {   // the wave's first tile: V must have landed by now
+            wait_vector_memory();
+            lds_barrier();
+        }
+        v4i oacc[4];
+        weighted_values_of_tile<NT>(v_lds, off.v, xp, rho2, oacc);
+        store_tile<NT>(o, item, wave + i * WAVES, lane, oacc);
+    }
+}
+
+// P <= 127 for every row the table allows: the largest probability of a row is that of its maximum,
+// (B*rho) >> 15, and rho = floor(255*2^15 / Z) is largest for the smallest row sum a head can have,
+// Z = B + (n-1)*(B - S*Dmax) (one element at the maximum, all others clamped).
+static bool probabilities_fit_signed(const HeadTable &tab, int H, int n)
+{
+    for (int h = 0; h < H; ++h) {
+        const int64_t B = tab.e[h].x, S = tab.e[h].y, D = tab.e[h].z;
+        const int64_t zmin = B + (int64_t)(n - 1) * (B - S * D);
+        const int64_t rho = (int64_t)kRecipNumerator / (zmin > 0 ? zmin : 1);
+        if (((B * rho) >> 15) > 127) return false;
+    }
+    return true;
+}
+
+template <int NT>
+static hipError_t launch_direct_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
+                                   const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
+{
+    constexpr int WAVES = 8;
+    const dim3 grid((uint32_t)items), block(64 * WAVES);
+    if (kind == kRescaleHigh16)
+        return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
+    if (kind == kRescaleShift)
+        return launch(hccs_attention_direct_kernel<NT, kRescaleShift, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
+    return launch(hccs_attention_direct_kernel<NT, kRescalePreclamp, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
+}
+
 template <int NT>
 static hipError_t launch_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t blocks, int H,
                             const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
@@ -231,6 +536,7 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
     const int64_t blocks = Bt * H;
+    if (L == 256 && probabilities_fit_signed(tab, H, L)) return launch_direct_nt<16>(q, k, v, o, blocks, H, tab, rq, kind, st);
     switch (L / 16) {
         case 4: return launch_nt<4>(q, k, v, o, blocks, H, tab, rq, kind, st);
         case 8: return launch_nt<8>(q, k, v, o, blocks, H, tab, rq, kind, st);

@@ -33,6 +33,9 @@ __device__ __forceinline__ uint32_t sat_pk_u8_i16(uint32_t v)
     return d;
 }
 
+// the value the lane next door (lane ^ 1) holds: DPP quad_perm [1,0,3,2]
+__device__ __forceinline__ int neighbour_lane(int x) { return __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true); }
+
 constexpr int kKStride = 80;   // bytes per K row in LDS: 64 + 16 of padding against bank conflicts
 
 // How the int32 accumulator becomes a 16-bit logit (before the int8 saturation):
