@@ -251,16 +251,6 @@ __device__ __forceinline__ void load_to_lds16(const void *global_lane, void *lds
 #pragma clang diagnostic pop
 }
 
-// Four scores (two 16-bit pairs) -> four bytes P: byte 2 of s*(2*rho) is (s*rho) >> 15.
-__device__ __forceinline__ uint32_t probabilities_plain(uint32_t s01, uint32_t s23, uint32_t rho2)
-{
-    const uint32_t e0 = mad_u32_u16_lo(s01, rho2, 0u), e1 = mad_u32_u16_hi(s01, rho2, 0u);
-    const uint32_t e2 = mad_u32_u16_lo(s23, rho2, 0u), e3 = mad_u32_u16_hi(s23, rho2, 0u);
-    const uint32_t h01 = __builtin_amdgcn_perm(e1, e0, 0x00000602u);
-    const uint32_t h23 = __builtin_amdgcn_perm(e3, e2, 0x00000602u);
-    return __builtin_amdgcn_perm(h23, h01, 0x05040100u);
-}
-
 // One instruction moves 16 rows (1 KiB): lane l brings chunk (l & 3) ^ f(row) of row 16u + l/4 to
 // position l & 3 of that row.  The waves of a block share the NT instructions of an item evenly.
 template <int NT, int WAVES>
@@ -486,20 +476,6 @@ __global__ __launch_bounds__(64 * WAVES, 6) void hccs_attention_direct_kernel(
         weighted_values_of_tile<NT>(v_lds, off.v, xp, rho2, oacc);
         store_tile<NT>(o, item, wave + i * WAVES, lane, oacc);
     }
-}
-
-// P <= 127 for every row the table allows: the largest probability of a row is that of its maximum,
-// (B*rho) >> 15, and rho = floor(255*2^15 / Z) is largest for the smallest row sum a head can have,
-// Z = B + (n-1)*(B - S*Dmax) (one element at the maximum, all others clamped).
-static bool probabilities_fit_signed(const HeadTable &tab, int H, int n)
-{
-    for (int h = 0; h < H; ++h) {
-        const int64_t B = tab.e[h].x, S = tab.e[h].y, D = tab.e[h].z;
-        const int64_t zmin = B + (int64_t)(n - 1) * (B - S * D);
-        const int64_t rho = (int64_t)kRecipNumerator / (zmin > 0 ? zmin : 1);
-        if (((B * rho) >> 15) > 127) return false;
-    }
-    return true;
 }
 
 template <int NT>

@@ -93,6 +93,16 @@ __device__ __forceinline__ uint32_t probabilities_minus_128(uint32_t s01, uint32
     return __builtin_amdgcn_perm(h23, h01, 0x05040100u);
 }
 
+// Four scores (two 16-bit pairs) -> four bytes P: byte 2 of s*(2*rho) is (s*rho) >> 15.
+__device__ __forceinline__ uint32_t probabilities_plain(uint32_t s01, uint32_t s23, uint32_t rho2)
+{
+    const uint32_t e0 = mad_u32_u16_lo(s01, rho2, 0u), e1 = mad_u32_u16_hi(s01, rho2, 0u);
+    const uint32_t e2 = mad_u32_u16_lo(s23, rho2, 0u), e3 = mad_u32_u16_hi(s23, rho2, 0u);
+    const uint32_t h01 = __builtin_amdgcn_perm(e1, e0, 0x00000602u);
+    const uint32_t h23 = __builtin_amdgcn_perm(e3, e2, 0x00000602u);
+    return __builtin_amdgcn_perm(h23, h01, 0x05040100u);
+}
+
 // 4x4 byte transpose: r[k] holds 4 columns of key k; w[c] receives the 4 keys of column c.
 __device__ __forceinline__ void transpose4x4(const uint32_t (&r)[4], uint32_t (&w)[4])
 {
@@ -152,6 +162,20 @@ inline int choose_rescale(const RequantTable &in, int H, int64_t acc_bound, Requ
         preclamp_limits(in.e[h].x, in.e[h].y, acc_bound, out.e[h].z, out.e[h].w);
     }
     return high16 ? kRescaleHigh16 : (preclamp ? kRescalePreclamp : kRescaleShift);
+}
+
+// P <= 127 for every row the table allows: the largest probability of a row is that of its maximum,
+// (B*rho) >> 15, and rho = floor(255*2^15 / Z) is largest for the smallest row sum a head can have,
+// Z = B + (n-1)*(B - S*Dmax) (one element at the maximum, all others clamped).
+inline bool probabilities_fit_signed(const HeadTable &tab, int H, int n)
+{
+    for (int h = 0; h < H; ++h) {
+        const int64_t B = tab.e[h].x, S = tab.e[h].y, D = tab.e[h].z;
+        const int64_t zmin = B + (int64_t)(n - 1) * (B - S * D);
+        const int64_t rho = (int64_t)kRecipNumerator / (zmin > 0 ? zmin : 1);
+        if (((B * rho) >> 15) > 127) return false;
+    }
+    return true;
 }
 
 }  // namespace hccs

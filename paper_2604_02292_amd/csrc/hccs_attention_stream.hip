@@ -18,7 +18,7 @@ namespace hccs {
 
 constexpr int kGroupsPerChunk = 2;   // the two-pass kernel stages 128 keys per chunk
 
-template <int ND, int RQ>   // head size d = 64*ND
+template <int ND, int RQ, bool PS>   // head size d = 64*ND; PS: every P <= 127, goes in as it is
 __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t *__restrict__ q,
                                                                     const int8_t *__restrict__ k,
                                                                     const int8_t *__restrict__ v,
@@ -197,12 +197,13 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
                 s01 &= m01;
                 s23 &= m23;
             }
-            pop[tt] = (int)probabilities_minus_128(s01, s23, rho2);
+            pop[tt] = (int)(PS ? probabilities_plain(s01, s23, rho2) : probabilities_minus_128(s01, s23, rho2));
         }
         // V operand through the transposing LDS read (see the two-pass kernel below): lane pair j
         // of a 16-lane group points at the key of contraction slot j, the lane receives its column.
         // The contraction runs transposed, O^T tile = V^T . P^T, with V^T as the first operand.
-        // P = (P - 128) + 64 + 64: the offset goes through the matrix unit as well.
+        // Unless every P is known to be <= 127: P = (P - 128) + 64 + 64, the offset goes through the
+        // matrix unit as well.
         const v4i c64 = {0x40404040, 0x40404040, 0x40404040, 0x40404040};
 #pragma unroll
         for (int n16 = 0; n16 < 4 * ND; ++n16) {
@@ -212,8 +213,10 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
             const v4i vop = {lo[0], lo[1], hi[0], hi[1]};
             v4i &acc = oacc[n16 / 4][n16 % 4];
             acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, pop, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+            if constexpr (!PS) {
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+            }
         }
     });
 
@@ -245,10 +248,11 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 // rescales of different tiles interleave); the one chunk that may be partial is handled once,
 // after them, with registers of its own.
 // The matrix unit multiplies signed bytes, P is unsigned: it gets P - 128, and the missing
-// 128 = 64 + 64 as two more contractions of a constant operand with the same V operand.
+// 128 = 64 + 64 as two more contractions of a constant operand with the same V operand, unless the
+// host has shown that no P of this table exceeds 127 (PS): then P goes in as it is.
 // ---------------------------------------------------------------------------
-template <int NCMAX, int ND, int RQ, int GPC>
-__global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_stream2_kernel(
+template <int NCMAX, int ND, int RQ, int GPC, bool PS, int KS>
+__global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void hccs_attention_stream2_kernel(
     const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v,
     int32_t *__restrict__ o, int H, int Lq, int Lk, uint32_t qtiles, HeadTable table, RequantTable requant)
 {
@@ -260,10 +264,15 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     constexpr int NCH = NCMAX / GPC;         // chunks of whole keys at most
     constexpr int KU = ND * GPC;             // staging units per thread (K: 16-byte pieces; V: 4x4 byte blocks)
     static_assert(NCMAX % GPC == 0, "whole chunks");
-    __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][CK * KSTR];   // pass 1: K chunks; pass 2: V chunks
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[KS][2][CK * KSTR];   // pass 1: K chunks; pass 2: V chunks
+    __shared__ int exchange[KS][4][16];   // KS == 2: row maxima and clamped sums of the two key halves
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // KS == 2: eight waves, wave w works on query tile w & 3 and on key half w >> 2 (Lk/2 keys, a
+    // whole number of chunks: the host sees to that); the four waves of a half stage its chunks.
+    const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3, half = (int)(threadIdx.x >> 8);
+    const int tid = threadIdx.x & 255;    // thread number among the waves that share chunks
     const int qi = lane & 15, g = lane >> 4;
+    uint8_t(*lds_k)[CK * KSTR] = lds_all[half];
     // logical block number: all query tiles of an item on one die, so its K and V stay in that L2
     const uint32_t logical = die_major_block(blockIdx.x, gridDim.x);
     const int item = (int)(logical / qtiles);
@@ -273,12 +282,14 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     const int mult = requant.e[head].x, shift = requant.e[head].y;
     const int round_c = 1 << (shift - 1);
     const int lim_lo = requant.e[head].z, lim_hi = requant.e[head].w;   // accumulator saturation bounds
-    const int8_t *kb = k + (size_t)item * Lk * DH;
-    const int8_t *vb = v + (size_t)item * Lk * DH;
+    const int Lk_all = Lk;               // keys of the row; Lk from here on: keys of this wave's share
+    if constexpr (KS == 2) Lk = Lk / 2;
+    const int8_t *kb = k + ((size_t)item * Lk_all + (size_t)half * Lk) * DH;
+    const int8_t *vb = v + ((size_t)item * Lk_all + (size_t)half * Lk) * DH;
     const int tile = (int)(logical % qtiles) * 4 + wave;
     const bool active = tile * 16 < Lq;
     const int nfull = Lk / CK;
-    const bool tail = (Lk % CK) != 0;
+    const bool tail = KS == 1 && (Lk % CK) != 0;
     const int nchunks = nfull + (tail ? 1 : 0);
     const int tail_buf = nfull & 1;      // the chunk after the whole ones was staged by their last iteration
 
@@ -323,11 +334,12 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     };
 
     // ---- pass 1: logits as offset-binary bytes, running maximum --------------------------------
-    uint32_t xb[NCMAX * 4], xt[TPC];
+    constexpr int TT = KS == 1 ? TPC : 0;   // tiles of the partial chunk (none when the keys are split)
+    uint32_t xb[NCMAX * 4], xt[TT + 1];
 #pragma unroll
     for (int i = 0; i < NCMAX * 4; ++i) xb[i] = 0;
 #pragma unroll
-    for (int i = 0; i < TPC; ++i) xt[i] = 0;
+    for (int i = 0; i < TT; ++i) xt[i] = 0;
     short2_t mx2 = {-32768, -32768};
     // tile tt of the chunk in `buf`: logits -> running maximum, bytes u = clamp(x, -128, 127) + 128
     auto tile_bytes = [&](const uint8_t *buf, int tt, auto masked, int key0) -> uint32_t {
@@ -380,13 +392,19 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     if (tail) {
         if (active) {
 #pragma unroll
-            for (int tt = 0; tt < TPC; ++tt) xt[tt] = tile_bytes(lds_k[tail_buf], tt, std::true_type{}, nfull * CK);
+            for (int tt = 0; tt < TT; ++tt) xt[tt] = tile_bytes(lds_k[tail_buf], tt, std::true_type{}, nfull * CK);
         }
         __syncthreads();                     // the buffers are refilled with V next
     }
     int mx = max((int)mx2.x, (int)mx2.y);
     mx = max(mx, xor16(mx));
     mx = max(mx, xor32(mx));
+    if constexpr (KS == 2) {   // the row's maximum is the larger of the two halves'
+        if (g == 0) exchange[half][wave][qi] = mx;
+        __syncthreads();
+        mx = max(mx, exchange[half ^ 1][wave][qi]);
+        __syncthreads();       // the array is used again for the sums
+    }
     const uint32_t mu = (uint32_t)clamp_i32(mx, 0, 255);   // saturation is monotone; mx carries the +128
 
     // ---- HCCS on the bytes: distances, clamped sum, row constants -------------------------------
@@ -400,7 +418,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
         acc_abs = __builtin_amdgcn_sad_u8(dl, D4, acc_abs);
     }
 #pragma unroll
-    for (int i = 0; i < TPC; ++i) {
+    for (int i = 0; i < TT; ++i) {
         const uint32_t dl = mu4 - xt[i];
         xt[i] = dl;
         acc_d = __builtin_amdgcn_sad_u8(dl, 0u, acc_d);
@@ -409,9 +427,14 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     int tsum = (int)acc_d - (int)acc_abs;
     tsum += xor16(tsum);
     tsum += xor32(tsum);
-    constexpr int kSlots = NCMAX * 64 + CK;    // every slot that is not a key holds u = 0
-    const int sum_clamped = (tsum + kSlots * D) / 2 - (kSlots - Lk) * (int)min(mu, (uint32_t)D);
-    const uint32_t Z = active ? (uint32_t)(Lk * B - S * sum_clamped) : 256u;
+    constexpr int kSlots = NCMAX * 64 + TT * 16;    // every slot that is not a key holds u = 0
+    int sum_clamped = (tsum + kSlots * D) / 2 - (kSlots - Lk) * (int)min(mu, (uint32_t)D);
+    if constexpr (KS == 2) {   // Eq. (5) runs over the whole row: both halves' sums
+        if (g == 0) exchange[half][wave][qi] = sum_clamped;
+        __syncthreads();
+        sum_clamped += exchange[half ^ 1][wave][qi];
+    }
+    const uint32_t Z = active ? (uint32_t)(Lk_all * B - S * sum_clamped) : 256u;
     const RowAffine ra = row_affine(Z, B, S, D);
 
     // ---- pass 2: O = P.V -----------------------------------------------------------------------
@@ -436,7 +459,7 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
         for (int T = 0; T < GPC; ++T) {
             v4i pop;
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(dist[T * 4 + tt], ra) ^ 0x80808080u);
+            for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(dist[T * 4 + tt], ra) ^ (PS ? 0u : 0x80808080u));
 #pragma unroll
             for (int n16 = 0; n16 < 4 * ND; ++n16) {
                 const uint8_t *at = buf + 64 * T * KSTR + v_lane_off + 16 * n16;
@@ -445,8 +468,10 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
                 const v4i vop = {lo[0], lo[1], hi[0], hi[1]};
                 v4i &acc = oacc[n16 / 4][n16 % 4];
                 acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, pop, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+                if constexpr (!PS) {
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+                }
             }
         }
     };
@@ -463,7 +488,25 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
         }
         __builtin_amdgcn_sched_barrier(0);
     }
-    if (tail && active) chunk_pv(lds_k[tail_buf], xt);   // V rows past the end were staged as zero
+    if constexpr (KS == 1) {
+        if (tail && active) chunk_pv(lds_k[tail_buf], xt);   // V rows past the end were staged as zero
+    }
+
+    if constexpr (KS == 2) {
+        // O is the sum of the two halves' results: the second half hands its accumulators over
+        // through LDS (lane-major, 4*ND*4 dwords per lane; the chunk buffers are free by now)
+        int32_t *hand = (int32_t *)&lds_all[0][0][0] + (wave * 64 + lane) * 4;
+        static_assert(sizeof(lds_all) >= (size_t)4 * ND * 4 * 256 * 4, "room for four waves' accumulators");
+        __syncthreads();       // everybody is done with the last chunk
+        if (half == 1) {
+#pragma unroll
+            for (int n16 = 0; n16 < 4 * ND; ++n16) *(v4i *)(hand + n16 * 1024) = oacc[n16 / 4][n16 % 4];
+        }
+        __syncthreads();
+        if (half == 1) return;
+#pragma unroll
+        for (int n16 = 0; n16 < 4 * ND; ++n16) oacc[n16 / 4][n16 % 4] += *(const v4i *)(hand + n16 * 1024);
+    }
 
     // the contraction ran transposed (V^T . P^T), so lane (g, qi) holds columns
     // 16*n16 + 4g .. +3 of query qi: 16 contiguous bytes per lane
@@ -478,24 +521,24 @@ __global__ __launch_bounds__(256, NCMAX <= 16 ? 3 : 2) void hccs_attention_strea
     }
 }
 
-template <int NCMAX, int ND, int GPC>
+template <int NCMAX, int ND, int GPC, bool PS, int KS = 1>
 static hipError_t launch_stream2(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
                                  int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
                                  hipStream_t st)
 {
     const uint32_t qtiles = (uint32_t)((Lq + 63) / 64);
-    const dim3 grid((uint32_t)(qtiles * items)), block(256);
+    const dim3 grid((uint32_t)(qtiles * items)), block(256 * KS);
     if (kind == kRescaleHigh16)
-        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16, GPC>, grid, block, st, q, k, v, o, H, Lq,
-                      Lk, qtiles, tab, rq);
+        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16, GPC, PS, KS>, grid, block, st, q, k, v, o, H,
+                      Lq, Lk, qtiles, tab, rq);
     if (kind == kRescaleShift)
-        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift, GPC>, grid, block, st, q, k, v, o, H, Lq,
-                      Lk, qtiles, tab, rq);
-    return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp, GPC>, grid, block, st, q, k, v, o, H, Lq,
+        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift, GPC, PS, KS>, grid, block, st, q, k, v, o, H,
+                      Lq, Lk, qtiles, tab, rq);
+    return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp, GPC, PS, KS>, grid, block, st, q, k, v, o, H, Lq,
                   Lk, qtiles, tab, rq);
 }
 
-template <int ND>
+template <int ND, bool PS>
 static hipError_t launch_stream_nd(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
                                    int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
                                    hipStream_t st)
@@ -503,13 +546,28 @@ static hipError_t launch_stream_nd(const int8_t *q, const int8_t *k, const int8_
     const uint32_t qtiles = (uint32_t)((Lq + 63) / 64);
     const dim3 grid((uint32_t)(qtiles * items)), block(256);
     if (kind == kRescaleHigh16)
-        return launch(hccs_attention_stream_kernel<ND, kRescaleHigh16>, grid, block, st, q, k, v, o, H, Lq, Lk, qtiles,
-                      tab, rq);
+        return launch(hccs_attention_stream_kernel<ND, kRescaleHigh16, PS>, grid, block, st, q, k, v, o, H, Lq, Lk,
+                      qtiles, tab, rq);
     if (kind == kRescaleShift)
-        return launch(hccs_attention_stream_kernel<ND, kRescaleShift>, grid, block, st, q, k, v, o, H, Lq, Lk, qtiles,
-                      tab, rq);
-    return launch(hccs_attention_stream_kernel<ND, kRescalePreclamp>, grid, block, st, q, k, v, o, H, Lq, Lk, qtiles,
-                  tab, rq);
+        return launch(hccs_attention_stream_kernel<ND, kRescaleShift, PS>, grid, block, st, q, k, v, o, H, Lq, Lk,
+                      qtiles, tab, rq);
+    return launch(hccs_attention_stream_kernel<ND, kRescalePreclamp, PS>, grid, block, st, q, k, v, o, H, Lq, Lk,
+                  qtiles, tab, rq);
+}
+
+template <int ND, bool PS>
+static hipError_t launch_stream_for(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
+                                    int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
+                                    hipStream_t st)
+{
+    // up to 2048 keys a query tile's logits fit its registers as bytes: Q.K^T once, two passes
+    if (Lk <= 1024) return launch_stream2<16, ND, kGroupsPerChunk, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    // 1024 < Lk <= 2048 in two halves of whole chunks: each half's logits take half the registers,
+    // and twice as many waves fit a compute unit
+    if (Lk <= 2048 && Lk % (2 * 64 * kGroupsPerChunk) == 0)
+        return launch_stream2<16, ND, kGroupsPerChunk, PS, 2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    if (Lk <= 2048) return launch_stream2<32, ND, kGroupsPerChunk, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    return launch_stream_nd<ND, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
 }
 
 hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H,
@@ -521,15 +579,12 @@ hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_
     const int kind = choose_rescale(rq_in, H, (int64_t)d << 14, rq, Lk <= 2048 ? (int64_t)128 << 16 : 0);
     const int64_t items = Bt * H;
     if (d != 64 && d != 128) return hipErrorInvalidValue;
-    // up to 2048 keys a query tile's logits fit its registers as bytes: Q.K^T once, two passes
-    if (Lk <= 1024)
-        return d == 64 ? launch_stream2<16, 1, kGroupsPerChunk>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-                       : launch_stream2<16, 2, kGroupsPerChunk>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
-    if (Lk <= 2048)
-        return d == 64 ? launch_stream2<32, 1, kGroupsPerChunk>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-                       : launch_stream2<32, 2, kGroupsPerChunk>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
-    return d == 64 ? launch_stream_nd<1>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-                   : launch_stream_nd<2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    const bool ps = probabilities_fit_signed(tab, H, Lk);
+    if (d == 64)
+        return ps ? launch_stream_for<1, true>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                  : launch_stream_for<1, false>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    return ps ? launch_stream_for<2, true>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+              : launch_stream_for<2, false>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
 }
 
 }  // namespace hccs

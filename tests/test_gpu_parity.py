@@ -544,6 +544,8 @@ STREAM_SHAPES = [  # (Bt, H, Lq, Lk, d, band)
     # block counts that are no multiple of the number of dies (block renumbering), whole and partial 128-key chunks
     (3, 3, 200, 96, 64, 1), (1, 5, 150, 130, 64, 1), (1, 11, 65, 128, 64, 1), (1, 3, 129, 384, 128, 1),
     (1, 1, 300, 2200, 64, 0),
+    # 1024 < Lk <= 2048 in whole pairs of chunks: the keys of a row split over two waves
+    (1, 2, 70, 1280, 64, 0), (1, 1, 40, 1536, 128, 0), (2, 1, 130, 1792, 64, 0), (1, 1, 17, 2048, 128, 0),
 ]
 
 
@@ -585,6 +587,29 @@ def test_attention_streaming_rescale_kinds_and_extremes(oracle):
                [[4096, 23], [4096, 12], [2047, 16]],     # accumulator saturation needed
                [[4096, 24], [1, 24], [2049, 24]]):       # the top of the shift range
         check_attention(q, k, v, table, np.array(rq, np.int32), 0, oracle, f"rescale {rq}")
+
+
+@pytest.mark.parametrize("Lq,Lk,d", [(40, 2048, 64), (24, 1000, 128), (33, 2500, 64), (20, 2300, 128), (17, 300, 64)])
+def test_attention_streaming_probabilities_above_127(oracle, Lq, Lk, d):
+    """Tables that allow P > 127 (the kernels then feed P - 128 and add the offset back), with rows
+    that reach it: one key far above all others, which sit at the window's edge."""
+    g = np.random.default_rng(Lk + d)
+    H = 2
+    q = g.integers(40, 100, size=(1, H, Lq, d), dtype=np.int8)
+    k = g.integers(-1, 2, size=(1, H, Lk, d), dtype=np.int8)
+    v = g.integers(-128, 128, size=(1, H, Lk, d), dtype=np.int8)
+    k[0, :, Lk // 3] = 127                                # the dominant key
+    k[0, 1, Lk - 1] = 127                                 # a second one for head 1
+    cap = (255 << 15) // Lk
+    S, D = 32, 100
+    table = np.array([[S * D + 1, S, D], [min(cap, 32767), S, D]], np.int32)   # floor 1, and the band's largest base
+    assert binding.validate_params(table, Lk, 0) == (0, -1)
+    rq = np.array([[40, 16], [3, 12]], np.int32)
+    x, rc = oracle.requant_logits(q, k, rq)
+    assert rc == 0
+    p, rc = oracle.softmax(x, table, 0, threads=THREADS)
+    assert rc == 0 and p[0, 0].max() > 127                # the case does reach beyond the signed range
+    check_attention(q, k, v, table, rq, 0, oracle, f"P above 127, Lk={Lk} d={d}")
 
 
 def test_attention_streaming_equals_resident_definition(oracle):
