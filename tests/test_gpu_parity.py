@@ -642,6 +642,31 @@ def test_attention_many_items_every_rescale_form(oracle, Bt, H):
                             f"items={Bt * H} band={band} rq={rq[0]}")
 
 
+@pytest.mark.parametrize("L,params,p_top", [(256, (763, 38, 20), 127), (256, (261, 13, 20), 128), (256, (502, 25, 20), 126),
+                                            (1280, (1281, 64, 20), 127), (1280, (1301, 65, 20), 128),
+                                            (2304, (2301, 115, 20), 127), (2304, (2341, 117, 20), 128)])
+def test_attention_largest_probability_at_the_signed_limit(oracle, L, params, p_top):
+    """Tables whose largest possible probability is just below, at and just above 127 (the fused
+    kernels feed P to the signed matrix unit as it is only when the table proves P <= 127), with
+    rows that attain it: one key at the maximum, every other key beyond the window.  256 keys take
+    the resident kernels, 1280 the two-pass streaming kernel with split keys, 2304 the three-pass one."""
+    g = np.random.default_rng(p_top + L)
+    H, d = 2, 64
+    Bt, Lq = (3, L) if L == 256 else (1, 48)
+    q = g.integers(40, 100, size=(Bt, H, Lq, d), dtype=np.int8)
+    k = g.integers(-1, 2, size=(Bt, H, L, d), dtype=np.int8)
+    v = g.integers(-128, 128, size=(Bt, H, L, d), dtype=np.int8)
+    k[:, :, 77] = 127                                     # the dominant key
+    table = np.array([params, params], np.int32)
+    assert binding.validate_params(table, L, 0) == (0, -1)
+    rq = np.array([[40, 16], [40, 16]], np.int32)
+    x, rc = oracle.requant_logits(q, k, rq)
+    assert rc == 0
+    p, rc = oracle.softmax(x, table, 0, threads=THREADS)
+    assert rc == 0 and int(p.max()) == p_top              # the bound is attained
+    check_attention(q, k, v, table, rq, 0, oracle, f"largest P = {p_top}, {L} keys")
+
+
 def test_attention_full_size(oracle):
     w = synth.make_workload("fused_attention")
     check_attention(w["q"], w["k"], w["v"], w["table"], w["requant"], w["band"], oracle, "full")
