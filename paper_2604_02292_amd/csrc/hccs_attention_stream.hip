@@ -46,7 +46,9 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     const int8_t *kb = k + (size_t)item * Lk * DH;
     const int8_t *vb = v + (size_t)item * Lk * DH;
     const int tile = (int)(logical % qtiles) * 4 + wave;
-    const bool active = tile * 16 < Lq;      // a wave without queries still stages and synchronises
+    // A wave whose queries do not exist works on the last query row instead (the Q operand below is
+    // clamped to it): no branch around the arithmetic, only its result is not stored.
+    const bool active = tile * 16 < Lq;
     const int nchunks = (Lk + 63) / 64;
 
     // Q operand: row clamped into range for the tail tile (those rows are never stored)
@@ -62,16 +64,26 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     u32x4 kreg[ND], vreg[ND];
     // K rows past the end are read from the last row instead (their logits are masked anyway);
     // V rows past the end must be zero, which only the last, partial chunk has to check.
+    // A whole chunk is one contiguous block of 64*DH bytes: thread t takes bytes 16t .. 16t+15 of each
+    // 4 KiB of it (block address wave-uniform, the thread's offset a constant).
     auto load_chunk = [&](int chunk, bool with_v) {
         const int key0 = chunk * 64;
-        const bool whole = key0 + 64 <= Lk;
+        if (key0 + 64 <= Lk) {
+            const size_t at = (size_t)key0 * DH;
+#pragma unroll
+            for (int i = 0; i < ND; ++i) {
+                kreg[i] = *(const u32x4 *)(kb + at + (uint32_t)(tid * 16 + i * 4096));
+                if (with_v) vreg[i] = *(const u32x4 *)(vb + at + (uint32_t)(tid * 16 + i * 4096));
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
             const int c = tid + i * 256;
             const int key = key0 + c / KPARTS;
             kreg[i] = *(const u32x4 *)(kb + (size_t)min(key, Lk - 1) * DH + (c % KPARTS) * 16);
             if (with_v) {
-                if (whole || key < Lk)
+                if (key < Lk)
                     vreg[i] = *(const u32x4 *)(vb + (size_t)key * DH + (c % KPARTS) * 16);
                 else
                     vreg[i] = (u32x4){0, 0, 0, 0};
@@ -110,12 +122,12 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
         __syncthreads();
         for (int c = 0; c < nfull; ++c) {
             if (c + 1 < nchunks) load_chunk(c + 1, with_v);
-            if (active) body(c & 1, c * 64, std::false_type{});
+            body(c & 1, c * 64, std::false_type{});
             if (c + 1 < nchunks) store_chunk((c + 1) & 1, with_v);
             __syncthreads();
         }
         if (tail) {
-            if (active) body(nfull & 1, nfull * 64, std::true_type{});
+            body(nfull & 1, nfull * 64, std::true_type{});
             __syncthreads();
         }
     };
@@ -168,7 +180,7 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     sx += xor32(sx);
     // Z = sum (B - S*(m - x')) = Lk*B - S*(Lk*m - sum x')      (Eq. (3), (5))
     const uint32_t Z = (uint32_t)(Lk * B - S * (Lk * m - sx));
-    const uint32_t rho2 = (active ? reciprocal_u8(Z) : 1u) * 2u;
+    const uint32_t rho2 = reciprocal_u8(Z) * 2u;
     const ushort2_t s2 = {(unsigned short)S, (unsigned short)S};
     const unsigned short cc = (unsigned short)(B - S * m);
     const ushort2_t c2 = {cc, cc};
@@ -251,8 +263,8 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 // 128 = 64 + 64 as two more contractions of a constant operand with the same V operand, unless the
 // host has shown that no P of this table exceeds 127 (PS): then P goes in as it is.
 // ---------------------------------------------------------------------------
-template <int NCMAX, int ND, int RQ, int GPC, bool PS, int KS>
-__global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void hccs_attention_stream2_kernel(
+template <int NCMAX, int ND, int RQ, int GPC, bool PS, int KS, bool KT>
+__global__ __launch_bounds__(256 * KS, KS > 1 ? 4 : (NCMAX <= 16 ? 3 : 2)) void hccs_attention_stream2_kernel(
     const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v,
     int32_t *__restrict__ o, int H, int Lq, int Lk, uint32_t qtiles, HeadTable table, RequantTable requant)
 {
@@ -265,11 +277,14 @@ __global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void
     constexpr int KU = ND * GPC;             // staging units per thread (K: 16-byte pieces; V: 4x4 byte blocks)
     static_assert(NCMAX % GPC == 0, "whole chunks");
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[KS][2][CK * KSTR];   // pass 1: K chunks; pass 2: V chunks
-    __shared__ int exchange[KS][4][16];   // KS == 2: row maxima and clamped sums of the two key halves
+    __shared__ int exchange[KS][4][16];   // KS > 1: row maxima and clamped sums of the key shares
 
-    // KS == 2: eight waves, wave w works on query tile w & 3 and on key half w >> 2 (Lk/2 keys, a
-    // whole number of chunks: the host sees to that); the four waves of a half stage its chunks.
-    const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3, half = (int)(threadIdx.x >> 8);
+    // KS = 2 or 4: 4*KS waves, wave w works on query tile w & 3 and on key share w >> 2; the four
+    // waves of a share stage its chunks.  Every share has the same number of whole chunks, and with
+    // KT one more, partial chunk of fewer than CK keys (possibly none): the host sees to that, so all
+    // waves of the block meet at the same barriers.
+    const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3;
+    const int half = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 8));   // wave-uniform: the share's bounds stay scalar
     const int tid = threadIdx.x & 255;    // thread number among the waves that share chunks
     const int qi = lane & 15, g = lane >> 4;
     uint8_t(*lds_k)[CK * KSTR] = lds_all[half];
@@ -283,13 +298,21 @@ __global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void
     const int round_c = 1 << (shift - 1);
     const int lim_lo = requant.e[head].z, lim_hi = requant.e[head].w;   // accumulator saturation bounds
     const int Lk_all = Lk;               // keys of the row; Lk from here on: keys of this wave's share
-    if constexpr (KS == 2) Lk = Lk / 2;
-    const int8_t *kb = k + ((size_t)item * Lk_all + (size_t)half * Lk) * DH;
-    const int8_t *vb = v + ((size_t)item * Lk_all + (size_t)half * Lk) * DH;
+    int first_key = 0;
+    if constexpr (KS > 1) {
+        // what is left beyond KS equal sets of whole chunks is dealt out evenly, the first shares
+        // taking one key more
+        const int whole = Lk_all / (KS * CK) * CK, rest = Lk_all - KS * whole;
+        const int each = rest / KS, more = rest % KS;
+        Lk = whole + each + (half < more ? 1 : 0);
+        first_key = half * (whole + each) + min(half, more);
+    }
+    const int8_t *kb = k + ((size_t)item * Lk_all + (size_t)first_key) * DH;
+    const int8_t *vb = v + ((size_t)item * Lk_all + (size_t)first_key) * DH;
     const int tile = (int)(logical % qtiles) * 4 + wave;
-    const bool active = tile * 16 < Lq;
+    const bool active = tile * 16 < Lq;   // otherwise the wave works on the last query row and stores nothing
     const int nfull = Lk / CK;
-    const bool tail = KS == 1 && (Lk % CK) != 0;
+    const bool tail = KS == 1 ? (Lk % CK) != 0 : KT;
     const int nchunks = nfull + (tail ? 1 : 0);
     const int tail_buf = nfull & 1;      // the chunk after the whole ones was staged by their last iteration
 
@@ -303,12 +326,20 @@ __global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void
 
     u32x4 kreg[KU];
     // K rows past the end are read from the last row instead: their logits are masked anyway
+    // A whole chunk is one contiguous block of CK*DH bytes: thread t takes bytes 16t .. 16t+15 of
+    // each 4 KiB of it (block address wave-uniform, the thread's offset a constant).
     auto load_k = [&](int chunk) {
+        if (chunk * CK + CK <= Lk) {
+            const int8_t *block = kb + (size_t)chunk * (CK * DH);
 #pragma unroll
-        for (int i = 0; i < KU; ++i) {
-            const int c = tid + i * 256;
-            const int key = min(chunk * CK + c / KPARTS, Lk - 1);
-            kreg[i] = *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16);
+            for (int i = 0; i < KU; ++i) kreg[i] = *(const u32x4 *)(block + (uint32_t)(tid * 16 + i * 4096));
+        } else {
+#pragma unroll
+            for (int i = 0; i < KU; ++i) {
+                const int c = tid + i * 256;
+                const int key = min(chunk * CK + c / KPARTS, Lk - 1);
+                kreg[i] = *(const u32x4 *)(kb + (size_t)key * DH + (c % KPARTS) * 16);
+            }
         }
     };
     auto store_k = [&](int buf) {
@@ -321,20 +352,25 @@ __global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void
     // V is staged row-major like K (rows past the end as zeros, which only the last, partial chunk
     // has to check); its operands are formed by the transposing LDS read, see chunk_pv.
     auto load_v = [&](int chunk) {
-        const bool whole = chunk * CK + CK <= Lk;
+        if (chunk * CK + CK <= Lk) {
+            const int8_t *block = vb + (size_t)chunk * (CK * DH);
 #pragma unroll
-        for (int i = 0; i < KU; ++i) {
-            const int c = tid + i * 256;
-            const int key = chunk * CK + c / KPARTS;
-            if (whole || key < Lk)
-                kreg[i] = *(const u32x4 *)(vb + (size_t)key * DH + (c % KPARTS) * 16);
-            else
-                kreg[i] = (u32x4){0, 0, 0, 0};
+            for (int i = 0; i < KU; ++i) kreg[i] = *(const u32x4 *)(block + (uint32_t)(tid * 16 + i * 4096));
+        } else {
+#pragma unroll
+            for (int i = 0; i < KU; ++i) {
+                const int c = tid + i * 256;
+                const int key = chunk * CK + c / KPARTS;
+                if (key < Lk)
+                    kreg[i] = *(const u32x4 *)(vb + (size_t)key * DH + (c % KPARTS) * 16);
+                else
+                    kreg[i] = (u32x4){0, 0, 0, 0};
+            }
         }
     };
 
     // ---- pass 1: logits as offset-binary bytes, running maximum --------------------------------
-    constexpr int TT = KS == 1 ? TPC : 0;   // tiles of the partial chunk (none when the keys are split)
+    constexpr int TT = (KS == 1 || KT) ? TPC : 0;   // tiles of the partial chunk
     uint32_t xb[NCMAX * 4], xt[TT + 1];
 #pragma unroll
     for (int i = 0; i < NCMAX * 4; ++i) xb[i] = 0;
@@ -380,29 +416,26 @@ __global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void
     for (int c = 0; c < NCH; ++c) {
         if (c < nfull) {
             if (c + 1 < nchunks) load_k(c + 1);
-            if (active) {
 #pragma unroll
-                for (int tt = 0; tt < TPC; ++tt) xb[c * TPC + tt] = tile_bytes(lds_k[c & 1], tt, std::false_type{}, 0);
-            }
+            for (int tt = 0; tt < TPC; ++tt) xb[c * TPC + tt] = tile_bytes(lds_k[c & 1], tt, std::false_type{}, 0);
             if (c + 1 < nchunks) store_k((c + 1) & 1);
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);   // keep the unrolled chunks in order: registers, not latency, are scarce
     }
     if (tail) {
-        if (active) {
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) xt[tt] = tile_bytes(lds_k[tail_buf], tt, std::true_type{}, nfull * CK);
-        }
+        for (int tt = 0; tt < TT; ++tt) xt[tt] = tile_bytes(lds_k[tail_buf], tt, std::true_type{}, nfull * CK);
         __syncthreads();                     // the buffers are refilled with V next
     }
     int mx = max((int)mx2.x, (int)mx2.y);
     mx = max(mx, xor16(mx));
     mx = max(mx, xor32(mx));
-    if constexpr (KS == 2) {   // the row's maximum is the larger of the two halves'
+    if constexpr (KS > 1) {   // the row's maximum is the largest of the shares'
         if (g == 0) exchange[half][wave][qi] = mx;
         __syncthreads();
-        mx = max(mx, exchange[half ^ 1][wave][qi]);
+#pragma unroll
+        for (int other = 1; other < KS; ++other) mx = max(mx, exchange[(half + other) % KS][wave][qi]);
         __syncthreads();       // the array is used again for the sums
     }
     const uint32_t mu = (uint32_t)clamp_i32(mx, 0, 255);   // saturation is monotone; mx carries the +128
@@ -429,12 +462,13 @@ __global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void
     tsum += xor32(tsum);
     constexpr int kSlots = NCMAX * 64 + TT * 16;    // every slot that is not a key holds u = 0
     int sum_clamped = (tsum + kSlots * D) / 2 - (kSlots - Lk) * (int)min(mu, (uint32_t)D);
-    if constexpr (KS == 2) {   // Eq. (5) runs over the whole row: both halves' sums
+    if constexpr (KS > 1) {   // Eq. (5) runs over the whole row: every share's sum
         if (g == 0) exchange[half][wave][qi] = sum_clamped;
         __syncthreads();
-        sum_clamped += exchange[half ^ 1][wave][qi];
+#pragma unroll
+        for (int other = 1; other < KS; ++other) sum_clamped += exchange[(half + other) % KS][wave][qi];
     }
-    const uint32_t Z = active ? (uint32_t)(Lk_all * B - S * sum_clamped) : 256u;
+    const uint32_t Z = (uint32_t)(Lk_all * B - S * sum_clamped);
     const RowAffine ra = row_affine(Z, B, S, D);
 
     // ---- pass 2: O = P.V -----------------------------------------------------------------------
@@ -482,30 +516,35 @@ __global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void
     for (int c = 0; c < NCH; ++c) {
         if (c < nfull) {
             if (c + 1 < nchunks) load_v(c + 1);
-            if (active) chunk_pv(lds_k[c & 1], &xb[c * TPC]);
+            chunk_pv(lds_k[c & 1], &xb[c * TPC]);
             if (c + 1 < nchunks) store_k((c + 1) & 1);
             __syncthreads();
         }
         __builtin_amdgcn_sched_barrier(0);
     }
-    if constexpr (KS == 1) {
-        if (tail && active) chunk_pv(lds_k[tail_buf], xt);   // V rows past the end were staged as zero
+    if constexpr (TT > 0) {
+        if (tail) chunk_pv(lds_k[tail_buf], xt);   // V rows past the end were staged as zero
     }
 
-    if constexpr (KS == 2) {
-        // O is the sum of the two halves' results: the second half hands its accumulators over
+    if constexpr (KS > 1) {
+        // O is the sum of the shares' results: all but the first hand their accumulators over
         // through LDS (lane-major, 4*ND*4 dwords per lane; the chunk buffers are free by now)
+        constexpr int kHandDwords = 4 * ND * 4 * 256;   // of one share
         int32_t *hand = (int32_t *)&lds_all[0][0][0] + (wave * 64 + lane) * 4;
-        static_assert(sizeof(lds_all) >= (size_t)4 * ND * 4 * 256 * 4, "room for four waves' accumulators");
+        static_assert(sizeof(lds_all) >= (size_t)(KS - 1) * kHandDwords * 4, "room for the other shares' accumulators");
         __syncthreads();       // everybody is done with the last chunk
-        if (half == 1) {
+        if (half > 0) {
 #pragma unroll
-            for (int n16 = 0; n16 < 4 * ND; ++n16) *(v4i *)(hand + n16 * 1024) = oacc[n16 / 4][n16 % 4];
+            for (int n16 = 0; n16 < 4 * ND; ++n16)
+                *(v4i *)(hand + (half - 1) * kHandDwords + n16 * 1024) = oacc[n16 / 4][n16 % 4];
         }
         __syncthreads();
-        if (half == 1) return;
+        if (half > 0) return;
 #pragma unroll
-        for (int n16 = 0; n16 < 4 * ND; ++n16) oacc[n16 / 4][n16 % 4] += *(const v4i *)(hand + n16 * 1024);
+        for (int other = 1; other < KS; ++other)
+#pragma unroll
+            for (int n16 = 0; n16 < 4 * ND; ++n16)
+                oacc[n16 / 4][n16 % 4] += *(const v4i *)(hand + (other - 1) * kHandDwords + n16 * 1024);
     }
 
     // the contraction ran transposed (V^T . P^T), so lane (g, qi) holds columns
@@ -521,7 +560,7 @@ __global__ __launch_bounds__(256 * KS, KS == 2 ? 4 : (NCMAX <= 16 ? 3 : 2)) void
     }
 }
 
-template <int NCMAX, int ND, int GPC, bool PS, int KS = 1>
+template <int NCMAX, int ND, int GPC, bool PS, int KS = 1, bool KT = false>
 static hipError_t launch_stream2(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
                                  int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
                                  hipStream_t st)
@@ -529,12 +568,12 @@ static hipError_t launch_stream2(const int8_t *q, const int8_t *k, const int8_t 
     const uint32_t qtiles = (uint32_t)((Lq + 63) / 64);
     const dim3 grid((uint32_t)(qtiles * items)), block(256 * KS);
     if (kind == kRescaleHigh16)
-        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16, GPC, PS, KS>, grid, block, st, q, k, v, o, H,
+        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleHigh16, GPC, PS, KS, KT>, grid, block, st, q, k, v, o, H,
                       Lq, Lk, qtiles, tab, rq);
     if (kind == kRescaleShift)
-        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift, GPC, PS, KS>, grid, block, st, q, k, v, o, H,
+        return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescaleShift, GPC, PS, KS, KT>, grid, block, st, q, k, v, o, H,
                       Lq, Lk, qtiles, tab, rq);
-    return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp, GPC, PS, KS>, grid, block, st, q, k, v, o, H, Lq,
+    return launch(hccs_attention_stream2_kernel<NCMAX, ND, kRescalePreclamp, GPC, PS, KS, KT>, grid, block, st, q, k, v, o, H, Lq,
                   Lk, qtiles, tab, rq);
 }
 
@@ -555,36 +594,63 @@ static hipError_t launch_stream_nd(const int8_t *q, const int8_t *k, const int8_
                   qtiles, tab, rq);
 }
 
+// How the two-pass kernel takes a row: 1 = one wave per query tile holds all its logits (up to 2048
+// keys), 2 or 4 = the keys in that many shares on different waves (each share's logits take that
+// much less of the registers, so more waves fit a compute unit; head size 64 only: at 128 the
+// wider accumulators do not fit the smaller register budget, measured [2,8,2048,2048,128] 42.7
+// against 38.3 us), 0 = the row goes to the three-pass kernel.  Shares are equal sets of whole
+// chunks plus an even part of the rest, which must stay below a chunk for every share
+// (`partial` says whether there is such a rest).
+static int key_shares(int Lk, int d, bool &partial)
+{
+    constexpr int kChunk = 64 * kGroupsPerChunk;
+    partial = false;
+    if (Lk <= 1024) return 1;
+    const int shares = Lk <= 2048 ? 2 : 4;
+    const int rest = Lk % (shares * kChunk);
+    if (d == 64 && Lk <= 4096 && rest <= shares * (kChunk - 1)) {
+        partial = rest != 0;
+        return shares;
+    }
+    return Lk <= 2048 ? 1 : 0;
+}
+
 template <int ND, bool PS>
 static hipError_t launch_stream_for(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
-                                    int Lq, int Lk, const HeadTable &tab, const RequantTable &rq, int kind,
-                                    hipStream_t st)
+                                    int Lq, int Lk, int shares, bool partial, const HeadTable &tab,
+                                    const RequantTable &rq, int kind, hipStream_t st)
 {
-    // up to 2048 keys a query tile's logits fit its registers as bytes: Q.K^T once, two passes
-    if (Lk <= 1024) return launch_stream2<16, ND, kGroupsPerChunk, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
-    // 1024 < Lk <= 2048 in two halves of whole chunks: each half's logits take half the registers,
-    // and twice as many waves fit a compute unit
-    if (Lk <= 2048 && Lk % (2 * 64 * kGroupsPerChunk) == 0)
-        return launch_stream2<16, ND, kGroupsPerChunk, PS, 2>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
-    if (Lk <= 2048) return launch_stream2<32, ND, kGroupsPerChunk, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
-    return launch_stream_nd<ND, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    constexpr int G = kGroupsPerChunk;
+    if (shares == 0) return launch_stream_nd<ND, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    if constexpr (ND == 1) {
+        if (shares == 4)
+            return partial ? launch_stream2<16, ND, G, PS, 4, true>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                           : launch_stream2<16, ND, G, PS, 4, false>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+        if (shares == 2)
+            return partial ? launch_stream2<16, ND, G, PS, 2, true>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
+                           : launch_stream2<16, ND, G, PS, 2, false>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    }
+    if (Lk <= 1024) return launch_stream2<16, ND, G, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+    return launch_stream2<32, ND, G, PS>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
 }
 
 hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H,
                                    int Lq, int Lk, int d, const HeadTable &tab, const RequantTable &rq_in,
                                    hipStream_t st)
 {
+    if (d != 64 && d != 128) return hipErrorInvalidValue;
+    bool partial;
+    const int shares = key_shares(Lk, d, partial);
     RequantTable rq;
     // |acc| <= d*128*128; the two-pass kernel adds 128 << 16 to the rounding constant
-    const int kind = choose_rescale(rq_in, H, (int64_t)d << 14, rq, Lk <= 2048 ? (int64_t)128 << 16 : 0);
+    const int kind = choose_rescale(rq_in, H, (int64_t)d << 14, rq, shares > 0 ? (int64_t)128 << 16 : 0);
     const int64_t items = Bt * H;
-    if (d != 64 && d != 128) return hipErrorInvalidValue;
     const bool ps = probabilities_fit_signed(tab, H, Lk);
     if (d == 64)
-        return ps ? launch_stream_for<1, true>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-                  : launch_stream_for<1, false>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
-    return ps ? launch_stream_for<2, true>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st)
-              : launch_stream_for<2, false>(q, k, v, o, items, H, Lq, Lk, tab, rq, kind, st);
+        return ps ? launch_stream_for<1, true>(q, k, v, o, items, H, Lq, Lk, shares, partial, tab, rq, kind, st)
+                  : launch_stream_for<1, false>(q, k, v, o, items, H, Lq, Lk, shares, partial, tab, rq, kind, st);
+    return ps ? launch_stream_for<2, true>(q, k, v, o, items, H, Lq, Lk, shares, partial, tab, rq, kind, st)
+              : launch_stream_for<2, false>(q, k, v, o, items, H, Lq, Lk, shares, partial, tab, rq, kind, st);
 }
 
 }  // namespace hccs

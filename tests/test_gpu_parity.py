@@ -546,6 +546,12 @@ STREAM_SHAPES = [  # (Bt, H, Lq, Lk, d, band)
     (1, 1, 300, 2200, 64, 0),
     # 1024 < Lk <= 2048 in whole pairs of chunks: the keys of a row split over two waves
     (1, 2, 70, 1280, 64, 0), (1, 1, 40, 1536, 128, 0), (2, 1, 130, 1792, 64, 0), (1, 1, 17, 2048, 128, 0),
+    # 2048 < Lk <= 4096 in whole sets of four chunks: four waves per row, two passes
+    (1, 2, 70, 2560, 64, 0), (1, 1, 130, 3072, 64, 0), (2, 1, 33, 3584, 64, 0), (1, 1, 64, 4096, 64, 0),    # shares that end in a partial chunk: the largest rests that still split (254 and 508 keys beyond whole
+    # chunk sets), a rest of one key (three of four shares get an empty partial chunk), and the lengths
+    # just beyond, which fall back to one wave per row (1279) and to three passes (4095)
+    (1, 1, 20, 2046, 64, 0), (1, 2, 18, 1279, 64, 0), (1, 1, 24, 4092, 64, 0), (1, 1, 17, 4095, 64, 0),
+    (2, 1, 40, 3001, 64, 0), (1, 1, 33, 2561, 64, 0), (1, 2, 21, 1025, 64, 1),
 ]
 
 
@@ -644,12 +650,14 @@ def test_attention_many_items_every_rescale_form(oracle, Bt, H):
 
 @pytest.mark.parametrize("L,params,p_top", [(256, (763, 38, 20), 127), (256, (261, 13, 20), 128), (256, (502, 25, 20), 126),
                                             (1280, (1281, 64, 20), 127), (1280, (1301, 65, 20), 128),
-                                            (2304, (2301, 115, 20), 127), (2304, (2341, 117, 20), 128)])
+                                            (2304, (2301, 115, 20), 127), (2304, (2341, 117, 20), 128),
+                                            (2560, (2551, 85, 30), 127), (2560, (2611, 87, 30), 128)])
 def test_attention_largest_probability_at_the_signed_limit(oracle, L, params, p_top):
     """Tables whose largest possible probability is just below, at and just above 127 (the fused
     kernels feed P to the signed matrix unit as it is only when the table proves P <= 127), with
     rows that attain it: one key at the maximum, every other key beyond the window.  256 keys take
-    the resident kernels, 1280 the two-pass streaming kernel with split keys, 2304 the three-pass one."""
+    the resident kernels, 1280 and 2560 the two-pass streaming kernel with the keys in two and four
+    shares, 2304 the three-pass one."""
     g = np.random.default_rng(p_top + L)
     H, d = 2, 64
     Bt, Lq = (3, L) if L == 256 else (1, 48)
