@@ -211,9 +211,8 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
 }
 
 // ---------------------------------------------------------------------------
-// The block of 256 keys in another form: K and V go straight from memory into LDS
-// (global_load_lds_dwordx4: no staging registers, no staging instructions), V while the first
-// contraction already runs.
+// The block in another form: K and V go straight from memory into LDS (global_load_lds_dwordx4: no
+// staging registers, no staging instructions), V while the first contraction already runs.
 //
 // Both K and V are row-major in LDS (64 bytes per key), as the loads deliver them: an instruction
 // of a wave moves 16 keys, lane l bringing 16 bytes of key l/4.  Which 16 bytes is permuted per
@@ -229,6 +228,9 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
 // The matrix unit multiplies signed bytes and P is unsigned: this kernel is launched only when
 // the host can show P <= 127 for every row the table allows (true for every table of the band of
 // Eq. (11) at 256 keys and more), and P goes in as it is; other tables take the kernel above.
+// Measured against it, same tables, about 88 MB of traffic each: L = 64 16.8 against 17.0 us, 128 16.4
+// against 18.3, 192 19.9 against 21.1, 256 19.3 against 20.8, 320 27.3 against 27.2, 384 30.8 against
+// 34.6, 512 35.0 against 41.8.
 // ---------------------------------------------------------------------------
 typedef const __attribute__((address_space(1))) void *global_void_ptr;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
@@ -431,7 +433,7 @@ __device__ __forceinline__ void store_tile(int32_t *o, int item, int rt, int lan
 // half or a quarter of an item's queries, and against blocks that stay and take item after item
 // with the next item's loads in flight: at 768 items this form was the fastest.)
 template <int NT, int RQ, int WAVES>
-__global__ __launch_bounds__(64 * WAVES, 6) void hccs_attention_direct_kernel(
+__global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention_direct_kernel(
     const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v, int32_t *__restrict__ o,
     int H, HeadTable table, RequantTable requant)
 {
@@ -482,7 +484,8 @@ template <int NT>
 static hipError_t launch_direct_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
                                    const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
 {
-    constexpr int WAVES = 8;
+    // as many waves as divide the query tiles evenly, at most 8
+    constexpr int WAVES = NT % 8 == 0 ? 8 : (NT % 6 == 0 ? 6 : (NT % 5 == 0 ? 5 : 4));
     const dim3 grid((uint32_t)items), block(64 * WAVES);
     if (kind == kRescaleHigh16)
         return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
@@ -512,7 +515,18 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
     const int64_t blocks = Bt * H;
-    if (L == 256 && probabilities_fit_signed(tab, H, L)) return launch_direct_nt<16>(q, k, v, o, blocks, H, tab, rq, kind, st);
+    if (probabilities_fit_signed(tab, H, L)) {
+        switch (L / 16) {
+            case 4: return launch_direct_nt<4>(q, k, v, o, blocks, H, tab, rq, kind, st);
+            case 8: return launch_direct_nt<8>(q, k, v, o, blocks, H, tab, rq, kind, st);
+            case 12: return launch_direct_nt<12>(q, k, v, o, blocks, H, tab, rq, kind, st);
+            case 16: return launch_direct_nt<16>(q, k, v, o, blocks, H, tab, rq, kind, st);
+            case 20: return launch_direct_nt<20>(q, k, v, o, blocks, H, tab, rq, kind, st);
+            case 24: return launch_direct_nt<24>(q, k, v, o, blocks, H, tab, rq, kind, st);
+            case 32: return launch_direct_nt<32>(q, k, v, o, blocks, H, tab, rq, kind, st);
+            default: break;   // 448 keys (7 waves of 4 tiles) measured slower than the kernel above: 31.4 against 29.1 us
+        }
+    }
     switch (L / 16) {
         case 4: return launch_nt<4>(q, k, v, o, blocks, H, tab, rq, kind, st);
         case 8: return launch_nt<8>(q, k, v, o, blocks, H, tab, rq, kind, st);
