@@ -355,12 +355,21 @@ __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, 
     const ushort2_t s2 = {(unsigned short)r.S, (unsigned short)r.S};
     const unsigned short cc = (unsigned short)(r.B - r.S * m);
     const ushort2_t c2 = {cc, cc};
+    // The int8 saturation from above matters only for a query whose largest logit exceeds 127; the
+    // tile takes that pass only if one of its 16 queries has such a logit.
+    if (__builtin_amdgcn_ballot_w64(mx > 127) != 0) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            xp[t][0] = __builtin_elementwise_min(xp[t][0], hi2);
+            xp[t][1] = __builtin_elementwise_min(xp[t][1], hi2);
+        }
+    }
     short2_t sum2 = {0, 0};
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const short2_t xc = __builtin_elementwise_min(__builtin_elementwise_max(xp[t][h], lo2), hi2);
+            const short2_t xc = __builtin_elementwise_max(xp[t][h], lo2);   // the window's lower edge, >= -128
             sum2 += xc;                            // at most 64 values of magnitude <= 128 per half
             xp[t][h] = __builtin_bit_cast(short2_t, __builtin_bit_cast(ushort2_t, xc) * s2 + c2);
         }
