@@ -755,11 +755,15 @@ def test_softmax_random_sweep(oracle):
 
 def test_attention_random_sweep(oracle):
     """200 seeded random fused blocks: resident and streaming shapes, both head sizes, every rescale form."""
-    g = np.random.default_rng(20260428)
-    for case in range(200):
+    attention_sweep(oracle, 20260428, 200)
+
+
+def attention_sweep(oracle, seed, cases):
+    g = np.random.default_rng(seed)
+    for case in range(cases):
         Bt, H = int(g.integers(1, 3)), int(g.integers(1, 5))
         d = 64 if g.integers(3) else 128
-        pick = int(g.integers(4))
+        pick = int(g.integers(5))
         if pick == 0:                                    # resident: square, multiple of 64, d = 64
             Lq = Lk = 64 * int(g.integers(1, 9))
             d = 64
@@ -767,8 +771,10 @@ def test_attention_random_sweep(oracle):
             Lq, Lk = int(g.integers(1, 200)), int(g.integers(1, 700))
         elif pick == 2:
             Lq, Lk = int(g.integers(1, 100)), int(g.integers(900, 2300))
-        else:
+        elif pick == 3:
             Lq, Lk = int(g.integers(1, 40)), 64 * int(g.integers(1, 40))
+        else:                                            # keys in four shares, and just beyond
+            Lq, Lk = int(g.integers(1, 70)), int(g.integers(2049, 4300))
         band = int(g.integers(2))
         if band == 1 and Lk > 4000:
             band = 0
