@@ -17,7 +17,8 @@ RECIP_EXACT, RECIP_CLB = 0, 1
 
 EXPORTS = ["hccs_validate_params", "hccs_calibrated_softmax_i8", "hccs_calibrated_softmax_i8_ex", "hccs_attention_i8", "hccs_attention_i8_ex",
            "hccs_calibrate_workspace_bytes", "hccs_calibrate_grid", "hccs_calibrate_grid_static",
-           "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_normalise_table_u8", "hccs_copy_bytes", "hccs_status_string"]
+           "hccs_exp_softmax_i8_f32", "hccs_reciprocal_u8", "hccs_normalise_table_u8", "hccs_largest_probability_u8",
+           "hccs_copy_bytes", "hccs_status_string"]
 
 
 class HccsError(RuntimeError):
@@ -63,6 +64,7 @@ def lib():
         L.hccs_exp_softmax_i8_f32.argtypes = [vp, vp, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_float), vp]
         L.hccs_reciprocal_u8.argtypes = [vp, vp, i64, vp]
         L.hccs_copy_bytes.argtypes = [vp, vp, i64, vp]
+        L.hccs_largest_probability_u8.argtypes = [vp, i32, i32, vp]
         L.hccs_normalise_table_u8.argtypes = [vp, vp, i64, vp]
         L.hccs_status_string.argtypes = [i32]
         L.hccs_status_string.restype = ctypes.c_char_p
@@ -312,6 +314,16 @@ def normalise_table_u8(bsdz, stream=None):
     out = torch.empty((bsdz.shape[0], 256), dtype=torch.uint8, device=bsdz.device)
     _check(lib().hccs_normalise_table_u8(ctypes.c_void_p(bsdz.data_ptr()), ctypes.c_void_p(out.data_ptr()),
                                          bsdz.shape[0], _stream_handle(stream)))
+    return out
+
+
+def largest_probability_u8(params, n):
+    """Per head, the largest 8-bit probability a row of n keys can get under (B, S, Dmax) (host only)."""
+    table = np.ascontiguousarray(params, dtype=np.int32)
+    assert table.ndim == 2 and table.shape[1] == 3
+    out = np.zeros(table.shape[0], np.int32)
+    _check(lib().hccs_largest_probability_u8(table.ctypes.data_as(ctypes.c_void_p), table.shape[0], int(n),
+                                             out.ctypes.data_as(ctypes.c_void_p)))
     return out
 
 

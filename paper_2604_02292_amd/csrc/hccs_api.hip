@@ -227,6 +227,16 @@ int hccs_normalise_table_u8(const int32_t *bsdz_dev, uint8_t *out_dev, int64_t c
     return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;
 }
 
+int hccs_largest_probability_u8(const int32_t *params_host, int32_t H, int32_t n, int32_t *bound_host)
+{
+    if (!params_host || !bound_host) return HCCS_E_NULL;
+    if (H < 1 || H > HCCS_MAX_HEADS || n < 1) return HCCS_E_SHAPE;
+    for (int h = 0; h < H; ++h)
+        bound_host[h] = (int32_t)hccs::largest_probability(params_host[3 * h], params_host[3 * h + 1],
+                                                           params_host[3 * h + 2], n);
+    return HCCS_OK;
+}
+
 int hccs_copy_bytes(const void *src_dev, void *dst_dev, int64_t bytes, void *hip_stream)
 {
     if (bytes < 0 || bytes % 16 != 0) return HCCS_E_SHAPE;

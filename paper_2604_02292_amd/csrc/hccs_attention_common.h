@@ -164,18 +164,4 @@ inline int choose_rescale(const RequantTable &in, int H, int64_t acc_bound, Requ
     return high16 ? kRescaleHigh16 : (preclamp ? kRescalePreclamp : kRescaleShift);
 }
 
-// P <= 127 for every row the table allows: the largest probability of a row is that of its maximum,
-// (B*rho) >> 15, and rho = floor(255*2^15 / Z) is largest for the smallest row sum a head can have,
-// Z = B + (n-1)*(B - S*Dmax) (one element at the maximum, all others clamped).
-inline bool probabilities_fit_signed(const HeadTable &tab, int H, int n)
-{
-    for (int h = 0; h < H; ++h) {
-        const int64_t B = tab.e[h].x, S = tab.e[h].y, D = tab.e[h].z;
-        const int64_t zmin = B + (int64_t)(n - 1) * (B - S * D);
-        const int64_t rho = (int64_t)kRecipNumerator / (zmin > 0 ? zmin : 1);
-        if (((B * rho) >> 15) > 127) return false;
-    }
-    return true;
-}
-
 }  // namespace hccs

@@ -293,4 +293,20 @@ inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipSt
     return launch_impl(kernel, grid, block, st, std::index_sequence_for<Params...>{}, std::forward<Args>(args)...);
 }
 
+// P <= 127 for every row the table allows: the largest probability of a row is that of its maximum,
+// (B*rho) >> 15, and rho = floor(255*2^15 / Z) is largest for the smallest row sum a head can have,
+// Z = B + (n-1)*(B - S*Dmax) (one element at the maximum, all others clamped).
+inline int64_t largest_probability(int64_t B, int64_t S, int64_t D, int64_t n)
+{
+    const int64_t zmin = B + (n - 1) * (B - S * D);
+    const int64_t rho = (int64_t)kRecipNumerator / (zmin > 0 ? zmin : 1);
+    return (B * rho) >> 15;
+}
+inline bool probabilities_fit_signed(const HeadTable &tab, int H, int n)
+{
+    for (int h = 0; h < H; ++h)
+        if (largest_probability(tab.e[h].x, tab.e[h].y, tab.e[h].z, n) > 127) return false;
+    return true;
+}
+
 }  // namespace hccs

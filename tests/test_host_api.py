@@ -203,6 +203,42 @@ def test_other_entry_points_reject_bad_arguments(lib):
     assert lib.hccs_exp_softmax_i8_f32(vp(4096), vp(8192), 1, 1, 4, 100, sc, None) == -2
 
 
+def test_largest_probability_bound_is_attained_and_never_exceeded(lib, oracle):
+    """The host-side bound that decides whether the fused kernels feed P to the signed matrix unit
+    as it is: per head the probability of a row's maximum when every other key lies beyond the
+    window.  Against the oracle: such a row attains the bound exactly, and no other row exceeds it."""
+    g = np.random.default_rng(5)
+    for n, band in ((256, 0), (256, 1), (64, 0), (1280, 0), (2304, 0), (17, 0)):
+        tables = [synth.head_params(6, n, band, seed=n + band)]
+        if band == 0:
+            cap = (255 << 15) // n
+            tables.append(np.array([[min(cap, 32767), 0, 0], [min(cap, 3000), 20, 100], [-(-256 // n) + 3 * 40, 3, 40]],
+                                   np.int32))
+        if n == 256 and band == 0:
+            tables.append(np.array([[763, 38, 20], [261, 13, 20], [502, 25, 20]], np.int32))   # bounds 127, 128, 126
+        for table in tables:
+            assert binding.validate_params(table, n, band) == (0, -1)
+            H = table.shape[0]
+            bound = binding.largest_probability_u8(table, n)
+            # one key at 127, the others 128 + Dmax and more below it (clamped whatever Dmax is)
+            worst = np.full((1, H, 1, n), -128, np.int8)
+            worst[..., n // 3] = 127
+            p, rc = oracle.softmax(worst, table, band)
+            assert rc == 0
+            assert np.array_equal(p.reshape(H, n).max(axis=1), bound), (n, band, table.tolist(), bound)
+            # random rows, narrow and wide spreads: never above the bound
+            for spread in (3, 40, 128):
+                x = g.integers(-spread, spread, size=(4, H, 64, n)).clip(-128, 127).astype(np.int8)
+                p, rc = oracle.softmax(x, table, band)
+                assert rc == 0
+                assert (p.transpose(1, 0, 2, 3).reshape(H, -1).max(axis=1) <= bound).all()
+    assert lib.hccs_largest_probability_u8(None, 1, 4, None) == -1
+    one = np.zeros(3, np.int32)
+    vp = ctypes.c_void_p
+    assert lib.hccs_largest_probability_u8(one.ctypes.data_as(vp), 0, 4, one.ctypes.data_as(vp)) == -2
+    assert lib.hccs_largest_probability_u8(one.ctypes.data_as(vp), 1, 0, one.ctypes.data_as(vp)) == -2
+
+
 def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
