@@ -386,8 +386,8 @@ def main():
             {"shape": [Ba, Ha, La, da], "logit_rows_per_s": round(Ba * Ha * La / t, 1),
              "algorithmic_int8_ops_per_launch": ops, "int8_TOPs": round(ops / t / 1e12, 2),
              "mfma_utilisation": round(ops / t / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
-             "note": "bound by vector-instruction issue (requantisation and HCCS stage); the matrix unit carries only "
-                     "the two contractions"})
+             "note": "one round of 768 blocks: loads, then arithmetic bound by vector-instruction issue (requantisation "
+                     "and HCCS stage; the matrix unit carries only the two contractions), then the last tile's stores"})
         del q, k, v, o
         torch.cuda.empty_cache()
 
