@@ -411,30 +411,11 @@ __device__ __forceinline__ void weighted_values_of_tile(const uint8_t *v_lds, co
     }
 }
 
-// Rows of query tile rt of an item.  As the contraction leaves them, the four lanes (g = 0..3) of a
-// query hold 64 consecutive bytes of its row per accumulator, and a store of one accumulator would
-// write half a 128-byte line of 16 rows: memory takes such halves at little more than half the
-// rate of whole lines.  So neighbouring queries (lanes qi, qi ^ 1) first trade accumulators: the even
-// lane keeps chunk `pair` of both rows, the odd lane chunk `pair + 1`, and each store instruction
-// then writes whole lines of 8 rows.
+// rows of query tile rt of an item
 template <int NT>
 __device__ __forceinline__ void store_tile(int32_t *o, int item, int rt, int lane, const v4i (&oacc)[4])
 {
-    const int qi = lane & 15, g = lane >> 4;
-    const bool odd = qi & 1;
-    int32_t *dst = o + (size_t)item * (NT * 16) * 64 + (size_t)(rt * 16 + (qi & ~1)) * 64 + 16 * (qi & 1) + 4 * g;
-#pragma unroll
-    for (int pair = 0; pair < 4; pair += 2) {
-        v4i upper, lower;   // rows 2p and 2p + 1 of the lane pair
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int theirs_lo = neighbour_lane(oacc[pair][c]), theirs_hi = neighbour_lane(oacc[pair + 1][c]);
-            upper[c] = odd ? theirs_hi : oacc[pair][c];
-            lower[c] = odd ? oacc[pair + 1][c] : theirs_lo;
-        }
-        __builtin_nontemporal_store(upper, (v4i *)(dst + 16 * pair));
-        __builtin_nontemporal_store(lower, (v4i *)(dst + 64 + 16 * pair));
-    }
+    store_rows_whole_lines<4>(o + ((size_t)item * (NT * 16) + (size_t)rt * 16) * 64, 64, 16, lane, oacc);
 }
 
 // One block per (batch, head) item, NT / WAVES query tiles per wave.  The first contraction starts

@@ -36,6 +36,37 @@ __device__ __forceinline__ uint32_t sat_pk_u8_i16(uint32_t v)
 // the value the lane next door (lane ^ 1) holds: DPP quad_perm [1,0,3,2]
 __device__ __forceinline__ int neighbour_lane(int x) { return __builtin_amdgcn_mov_dpp(x, 0xB1, 0xF, 0xF, true); }
 
+// Stores the 16 rows of a query tile after a transposed second contraction.  As the contraction
+// leaves them, the four lanes (g = 0..3) of a query hold 64 consecutive bytes of its row per
+// accumulator, and a store of one accumulator would write half a 128-byte line of 16 rows: memory
+// takes such halves at little more than half the rate of whole lines (measured 3.5 against 5.9
+// TB/s).  So neighbouring queries (lanes qi, qi ^ 1) first trade accumulators: the even lane keeps
+// chunk `pair` of both rows, the odd lane chunk `pair + 1`, and each store instruction then writes
+// whole lines of 8 rows.  tile_base: the tile's first row; row_ints: row pitch in 32-bit words;
+// rows: how many of the 16 rows exist.  NCH (even): accumulators per lane, 16 columns each.
+template <int NCH>
+__device__ __forceinline__ void store_rows_whole_lines(int32_t *tile_base, int row_ints, int rows, int lane,
+                                                       const v4i (&oacc)[NCH])
+{
+    static_assert(NCH % 2 == 0, "chunks are traded in pairs");
+    const int qi = lane & 15, g = lane >> 4;
+    const bool odd = qi & 1;
+    const int upper_row = qi & ~1;
+    int32_t *dst = tile_base + (size_t)upper_row * row_ints + 16 * (qi & 1) + 4 * g;
+#pragma unroll
+    for (int pair = 0; pair < NCH; pair += 2) {
+        v4i upper, lower;   // rows 2p and 2p + 1 of the lane pair
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int theirs_lo = neighbour_lane(oacc[pair][c]), theirs_hi = neighbour_lane(oacc[pair + 1][c]);
+            upper[c] = odd ? theirs_hi : oacc[pair][c];
+            lower[c] = odd ? oacc[pair + 1][c] : theirs_lo;
+        }
+        if (upper_row < rows) __builtin_nontemporal_store(upper, (v4i *)(dst + 16 * pair));
+        if (upper_row + 1 < rows) __builtin_nontemporal_store(lower, (v4i *)(dst + row_ints + 16 * pair));
+    }
+}
+
 constexpr int kKStride = 80;   // bytes per K row in LDS: 64 + 16 of padding against bank conflicts
 
 // How the int32 accumulator becomes a 16-bit logit (before the int8 saturation):
