@@ -234,11 +234,17 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 
     // ---- store: the contraction ran transposed (V^T . P^T), so lane (g, qi) holds columns
     // 16*n16 + 4g .. +3 of query qi: 16 contiguous bytes per lane
-    if (active) {   // whole 128-byte lines per store instruction, see store_rows_whole_lines
-        v4i flat[4 * ND];
+    // 16 bytes per lane where the contraction left them: these stores hide behind the arithmetic of
+    // other blocks, and trading accumulators for whole-line stores (store_rows_whole_lines) measured
+    // no faster here while costing registers the split kernels do not have
+    if (active) {
+        const int row = tile * 16 + qi;
+        if (row < Lq) {
 #pragma unroll
-        for (int n16 = 0; n16 < 4 * ND; ++n16) flat[n16] = oacc[n16 / 4][n16 % 4];
-        store_rows_whole_lines<4 * ND>(o + ((size_t)item * Lq + (size_t)tile * 16) * DH, DH, Lq - tile * 16, lane, flat);
+            for (int n16 = 0; n16 < 4 * ND; ++n16)
+                __builtin_nontemporal_store(oacc[n16 / 4][n16 % 4],
+                                            (v4i *)(o + ((size_t)item * Lq + row) * DH + 16 * n16 + 4 * g));
+        }
     }
 }
 
@@ -546,11 +552,17 @@ __global__ __launch_bounds__(256 * KS, KS > 1 ? 4 : (NCMAX <= 16 ? 3 : 2)) void 
 
     // the contraction ran transposed (V^T . P^T), so lane (g, qi) holds columns
     // 16*n16 + 4g .. +3 of query qi: 16 contiguous bytes per lane
-    if (active) {   // whole 128-byte lines per store instruction, see store_rows_whole_lines
-        v4i flat[4 * ND];
+    // 16 bytes per lane where the contraction left them: these stores hide behind the arithmetic of
+    // other blocks, and trading accumulators for whole-line stores (store_rows_whole_lines) measured
+    // no faster here while costing registers the split kernels do not have
+    if (active) {
+        const int row = tile * 16 + qi;
+        if (row < Lq) {
 #pragma unroll
-        for (int n16 = 0; n16 < 4 * ND; ++n16) flat[n16] = oacc[n16 / 4][n16 % 4];
-        store_rows_whole_lines<4 * ND>(o + ((size_t)item * Lq + (size_t)tile * 16) * DH, DH, Lq - tile * 16, lane, flat);
+            for (int n16 = 0; n16 < 4 * ND; ++n16)
+                __builtin_nontemporal_store(oacc[n16 / 4][n16 % 4],
+                                            (v4i *)(o + ((size_t)item * Lq + row) * DH + 16 * n16 + 4 * g));
+        }
     }
 }
 
