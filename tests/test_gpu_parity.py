@@ -160,7 +160,7 @@ def test_softmax_u8_ragged_lengths(oracle, shape, band):
                                        ((1, 2, 40, 64), 8), ((1, 2, 9, 4099), 3), ((3, 2, 50, 7), 1)])
 def test_softmax_tensors_that_begin_inside_a_vector(oracle, shape, off):
     """Input and output begin the same number of elements behind a 16-byte boundary (a slice of
-    a larger tensor): the masked-ends vector kernel takes them; canaries around the output."""
+    a larger tensor): vectors are read and written where they lie; canaries around the output."""
     H, n = shape[1], shape[3]
     band = 1 if n * 8 <= 32767 else 0
     table = synth.head_params(H, n, band, seed=n + H)
