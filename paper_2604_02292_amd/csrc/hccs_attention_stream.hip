@@ -2,15 +2,19 @@
 // queries, any key length, head size 64 or 128.  K and V stream through LDS in chunks (64 keys
 // in the three-pass kernel, 128 in the two-pass one), so neither the logits of a row nor K and V
 // have to fit anywhere.  HCCS needs the row maximum before the clamped sum and the sum before
-// the first output, and its floors rule out rescaling partial results, so Q.K^T is recomputed
-// three times: pass A finds the maximum, pass B the sum Z, pass C the probabilities and
-// O = P.V.  Same arithmetic per element as the resident kernel (hccs_attention_common.h).
+// the first output, and its floors rule out rescaling partial results.  Up to 4096 keys the
+// logits of a query tile are kept as bytes in the registers of one, two or four waves and
+// Q.K^T is computed once (two passes, second kernel below); beyond that Q.K^T is recomputed
+// three times (first kernel): pass A finds the maximum, pass B the sum Z, pass C the
+// probabilities and O = P.V.  Same arithmetic per element as the resident kernels
+// (hccs_attention_common.h).
 //
 // One block per (query tile of 64, batch*head) on a one-dimensional grid, block numbers remapped
-// so that the tiles of one (batch, head) share a die's L2; a wave owns 16 queries.  A chunk is double-buffered: the
-// global loads of chunk c+1 are issued before chunk c is computed and written to the other LDS
-// buffer afterwards, one barrier per chunk.  K and V are both staged row-major with padded
-// rows; V's operands are formed by the transposing LDS read.
+// so that the tiles of one (batch, head) share a die's L2; a wave owns 16 queries (and, in the
+// two-pass kernel, a share of the keys).  A chunk is double-buffered: the global loads of chunk
+// c+1 are issued before chunk c is computed and written to the other LDS buffer afterwards, one
+// barrier per chunk.  K and V are both staged row-major with padded rows; V's operands are
+// formed by the transposing LDS read.
 #include "hccs_attention_common.h"
 #include <type_traits>
 
@@ -262,6 +266,12 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 // branch-free path, so that the tiles of a chunk overlap (operand reads, contractions and
 // rescales of different tiles interleave); the one chunk that may be partial is handled once,
 // after them, with registers of its own.
+//
+// KS = 2 or 4: the keys of a row are dealt out to KS waves (blocks of 4*KS waves: 4 query tiles
+// x KS shares, each share staging its own chunks).  A wave then holds 1/KS of the logits, more
+// waves fit a compute unit, and rows up to 4096 keys fit two passes.  The shares exchange
+// their row maxima and clamped sums through LDS and hand their accumulators to the first share
+// at the end.
 // The matrix unit multiplies signed bytes, P is unsigned: it gets P - 128, and the missing
 // 128 = 64 + 64 as two more contractions of a constant operand with the same V operand, unless the
 // host has shown that no P of this table exceeds 127 (PS): then P goes in as it is.
