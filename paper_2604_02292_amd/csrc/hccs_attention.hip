@@ -3,6 +3,10 @@
 // path of Sec. III-B, n = L), O = P.V (int8 MFMA).  Logits and probabilities stay
 // in registers; K and V are staged once per (batch, head) in LDS.
 //
+// Two kernels: the first takes every table (probabilities up to 255); the second, further down,
+// brings K and V straight into LDS and feeds P to the matrix unit unsigned, for tables whose
+// probabilities provably stay below 128.  What follows describes the first.
+//
 // The matrix unit is used for the two dense contractions only.  Both use
 // v_mfma_i32_16x16x64_i8, whose operand layout on a 64-lane wave is
 //   A (16 x 64): lane l holds row l%16, columns 16*(l/16) .. +15   (16 bytes)
