@@ -424,6 +424,150 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
     }
 }
 
+// ---------------------------------------------------------------------------
+// Short rows of any length through LDS (8-bit outputs; both tensors begin on a 16-byte boundary;
+// 16 < n, n not a multiple of 16, and the block's rows fit its LDS buffers; Lq >= 64/G).
+//
+// The tensor is contiguous even where its rows are not vector-aligned, so a block takes the byte
+// range of its WPB*64/G consecutive rows, widened to 16-byte boundaries, as whole aligned vectors
+// into LDS: every global access of the block is one contiguous run of full vectors, whatever
+// the row length.  The lanes then read their rows out of LDS at the bytes where they lie (LDS takes
+// 16-byte accesses at any byte address, as global memory does), which frees the lane layout
+// from the memory access pattern: G lanes hold V vectors of a row each, so the per-row work
+// (reductions, reciprocal, constants) is spread over 16*V elements per lane, not 16, while no
+// global access is narrower for it.  The results go back through LDS the same way: the last
+// vector of every row is written first, whole (its slots past the row's end land on the first bytes
+// of the next row), then, after a barrier, all the other vectors (which put the right bytes
+// there); then the block stores the range as whole aligned vectors, and the bytes of its first and
+// last vector that belong to its rows one by one (the rest of those two vectors belongs to the
+// neighbouring blocks' rows).  In-place use stays safe: a block reads bytes of other blocks' rows
+// only into slots it masks or never looks at, and writes only bytes of its own rows.
+// Rows are numbered through the whole tensor and a block's rows may belong to two heads, a wave's
+// too (never three: Lq >= 64/G): a lane picks its row's constants from the two candidates of its wave.
+// ---------------------------------------------------------------------------
+template <int G, int V, int WPB, int MODE>
+__global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t *__restrict__ logits,
+                                                                    uint8_t *__restrict__ out, uint32_t total_rows,
+                                                                    int n, FastDiv by_Lq, FastDiv by_H, HeadTable table)
+{
+    static_assert((MODE & 1) == 0, "8-bit outputs: input and output ranges coincide");
+    constexpr int kRowsPerWave = 64 / G, kRowsPerBlock = WPB * kRowsPerWave;
+    constexpr int kPaddedLen = G * V * 16;
+    constexpr int kThreads = 64 * WPB;
+    // The block's range (up to 15 bytes ahead of the first row + the rows, n <= kPaddedLen - 1 each) has
+    // at most V vectors per thread; a last vector may reach 16 bytes past it.
+    static_assert(kRowsPerBlock >= 15, "one spare byte per row covers the bytes ahead of the first row");
+    constexpr int kPasses = V;
+    constexpr int kStageBytes = kRowsPerBlock * kPaddedLen + 32;
+    __shared__ __attribute__((aligned(16))) uint8_t stage_in[kStageBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t stage_out[kStageBytes];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sub = lane % G, grp = lane / G;
+    const uint32_t block_row0 = blockIdx.x * (uint32_t)kRowsPerBlock;
+    const int rows_here = (int)min((uint32_t)kRowsPerBlock, total_rows - block_row0);
+    const uint64_t start = (uint64_t)block_row0 * (uint64_t)n;          // first byte of the block's rows
+    const uint64_t first_vec = start & ~(uint64_t)15;                    // ... widened to a vector boundary
+    const int lead = (int)(start - first_vec);                           // bytes of the first vector ahead of the rows
+    const int span = lead + rows_here * n;                               // bytes from first_vec to the end of the rows
+    const int nchunks = (span + 15) >> 4;
+    const uint64_t total = (uint64_t)total_rows * (uint64_t)n;
+
+    // ---- the block's vectors -> LDS
+    {
+        u32x4 w[kPasses];
+        if (first_vec + (uint64_t)nchunks * 16 <= total) {
+#pragma unroll
+            for (int i = 0; i < kPasses; ++i) {
+                const int c = i * kThreads + tid;
+                if (c < nchunks) w[i] = load_stream(logits + first_vec + (size_t)c * 16);
+            }
+        } else {   // the tensor ends inside the last vector: that one is read byte by byte
+#pragma unroll
+            for (int i = 0; i < kPasses; ++i) {
+                const int c = i * kThreads + tid;
+                if (c < nchunks) {
+                    const uint64_t at = first_vec + (uint64_t)c * 16;
+                    if (at + 16 <= total) {
+                        w[i] = load_stream(logits + at);
+                    } else {
+                        uint32_t t[4];
+                        load_vector_bytes<4>(logits + at, (int)(total - at), t);
+                        w[i] = (u32x4){t[0], t[1], t[2], t[3]};
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kPasses; ++i) {
+            const int c = i * kThreads + tid;
+            if (c < nchunks) *(u32x4 *)(stage_in + c * 16) = w[i];
+        }
+    }
+    __syncthreads();
+
+    // ---- the head of the lane's row
+    const uint32_t wave_row0 = block_row0 + (uint32_t)(wave * kRowsPerWave);
+    const uint32_t slab0 = by_Lq.quotient(wave_row0);
+    const uint32_t head0 = slab0 - by_H.quotient(slab0) * by_H.divisor;
+    const uint32_t head1 = head0 + 1 == by_H.divisor ? 0u : head0 + 1;
+    const int change = (int)((slab0 + 1) * by_Lq.divisor - wave_row0);   // the wave's first row (counted from its own first) of the next head
+    const int4 hp0 = table.e[head0], hp1 = table.e[head1];
+    const bool next_head = grp >= change;
+    const int B = next_head ? hp1.x : hp0.x, S = next_head ? hp1.y : hp0.y, D = next_head ? hp1.z : hp0.z;
+
+    // ---- the lane's vectors of its row
+    const int nvec = (n + 15) >> 4;
+    const RowTail<4> tail(n, nvec);
+    const int row_in_block = wave * kRowsPerWave + grp;
+    const bool row_exists = row_in_block < rows_here;
+    const int row_at = lead + row_in_block * n + sub * 16;   // LDS byte of the lane's first vector
+    uint32_t d[V][4];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const int vi = v * G + sub;
+        if (row_exists && vi < nvec) {
+            const u32x4 t = *(const u32x4_any *)(stage_in + row_at + v * (G * 16));
+            d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
+            if (vi == tail.last_vec) tail.pad(d[v]);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) d[v][c] = kPadWord;
+        }
+    }
+
+    const int m = group_max<G>(lane_max(d));
+    const int t = group_sum<G>(lane_distances(d, m, D));
+    const RowOutput<MODE> ro((uint32_t)(n * B - S * clamped_sum(t, kPaddedLen, n, (uint32_t)(m + 128), D)), B, S, D);
+    u32x4 o[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) o[v] = ro.vector(d[v]);
+
+    // ---- results -> LDS: last vectors first, whole; then the others
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+        if (row_exists && v * G + sub == tail.last_vec) *(u32x4_any *)(stage_out + row_at + v * (G * 16)) = o[v];
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+        if (row_exists && v * G + sub < tail.last_vec) *(u32x4_any *)(stage_out + row_at + v * (G * 16)) = o[v];
+    __syncthreads();
+
+    // ---- LDS -> the block's vectors; of the first and the last one only the bytes of the block's rows
+#pragma unroll
+    for (int i = 0; i < kPasses; ++i) {
+        const int c = i * kThreads + tid;
+        if (c * 16 >= lead && c * 16 + 16 <= span) store_stream(out + first_vec + (size_t)c * 16, *(const u32x4 *)(stage_out + c * 16));
+    }
+    if (wave == 0 && lane < 32) {
+        const int c = lane < 16 ? 0 : nchunks - 1;
+        const int at = c * 16 + (lane & 15);
+        const bool whole = c * 16 >= lead && c * 16 + 16 <= span;
+        if (!whole && at >= lead && at < span) __builtin_nontemporal_store(stage_out[at], out + first_vec + at);
+    }
+}
+
 __global__ void reciprocal_kernel(const uint32_t *z, uint32_t *rho, int64_t count)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -507,12 +651,35 @@ static hipError_t launch_shape(const int8_t *x, uint8_t *p, int64_t Bt, int H, i
     return launch(hccs_row_block_kernel<16, MODE, RAGGED>, grid, dim3(256), st, x, p, Lq, Lk, last_slab, place, tab);
 }
 
+// Rows through LDS: G lanes x V vectors per row, blocks of WPB waves.  The caller keeps n below 16*G*V
+// and Lq at 64/G or more.
+// Measured on [64,12,197,197]: 8 lanes x 2 vectors per row in blocks of 2 waves 13.4 us; blocks of 1, 4, 8
+// waves 13.6, 13.7, 15.4; 16 lanes x 1 vector 15.9-17.8; 4 lanes x 4 vectors 18.2-20.1.
+template <int G, int V, int WPB, int MODE>
+static hipError_t launch_staged(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
+                                hipStream_t st)
+{
+    constexpr int kRowsPerBlock = WPB * (64 / G);
+    const int64_t rows = Bt * H * Lq;
+    return launch(hccs_rows_staged_kernel<G, V, WPB, MODE>, dim3((uint32_t)((rows + kRowsPerBlock - 1) / kRowsPerBlock)),
+                  dim3(64 * WPB), st, x, p, (uint32_t)rows, Lk, make_fast_div((uint32_t)Lq), make_fast_div((uint32_t)H), tab);
+}
+
 template <int MODE>
 static hipError_t launch_mode(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
                               bool aligned, hipStream_t st)
 {
     // aligned vectors when both tensors begin on a 16-byte boundary and rows are whole vectors
     if (aligned && Lk % ((MODE & 1) ? 8 : 16) == 0) return launch_shape<MODE, false>(x, p, Bt, H, Lq, Lk, tab, st);
+    if constexpr ((MODE & 1) == 0) {
+        // short rows of other lengths in tensors that begin on a 16-byte boundary: through LDS
+        // ([64,12,197,n], against the register kernel with vectors at any address: n = 77 8.3 against 9.5 us, 100 8.4 / 9.0,
+        // 120 8.5 / 9.6, 150 12.6 / 14.5, 197 13.5 / 15.2, 230 14.4 / 15.8, 250 15.1 / 16.4; no gain up to 64)
+        if (aligned && Lq >= 16) {
+            if (Lk > 64 && Lk < 128) return launch_staged<4, 2, 2, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
+            if (Lk > 128 && Lk < 256) return launch_staged<8, 2, 2, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
+        }
+    }
     return launch_shape<MODE, true>(x, p, Bt, H, Lq, Lk, tab, st);
 }
 
