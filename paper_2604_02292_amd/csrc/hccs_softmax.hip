@@ -426,24 +426,25 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
 
 // ---------------------------------------------------------------------------
 // Short rows of any length through LDS (8-bit outputs; both tensors begin on a 16-byte boundary;
-// 16 < n, n not a multiple of 16, and the block's rows fit its LDS buffers; Lq >= 64/G).
+// 16 < n < 16*G*V; Lq >= 64/G).
 //
-// The tensor is contiguous even where its rows are not vector-aligned, so a block takes the byte
-// range of its WPB*64/G consecutive rows, widened to 16-byte boundaries, as whole aligned vectors
-// into LDS: every global access of the block is one contiguous run of full vectors, whatever
-// the row length.  The lanes then read their rows out of LDS at the bytes where they lie (LDS takes
-// 16-byte accesses at any byte address, as global memory does), which frees the lane layout
+// The tensor is contiguous even where its rows are not vector-aligned, and 16 consecutive rows
+// are a whole number of vectors whatever n is.  A block takes WPB*64/G rows, a multiple of 16:
+// its byte range begins on a vector boundary and, except at the tensor's end, ends on one, and it
+// goes into LDS as whole aligned vectors: every global access of the block is one contiguous run
+// of full vectors.  The lanes then read their rows out of LDS at the bytes where they lie (LDS
+// takes 16-byte accesses at any byte address, as global memory does), which frees the lane layout
 // from the memory access pattern: G lanes hold V vectors of a row each, so the per-row work
 // (reductions, reciprocal, constants) is spread over 16*V elements per lane, not 16, while no
-// global access is narrower for it.  The results go back through LDS the same way: the last
-// vector of every row is written first, whole (its slots past the row's end land on the first bytes
-// of the next row), then, after a barrier, all the other vectors (which put the right bytes
-// there); then the block stores the range as whole aligned vectors, and the bytes of its first and
-// last vector that belong to its rows one by one (the rest of those two vectors belongs to the
-// neighbouring blocks' rows).  In-place use stays safe: a block reads bytes of other blocks' rows
-// only into slots it masks or never looks at, and writes only bytes of its own rows.
-// Rows are numbered through the whole tensor and a block's rows may belong to two heads, a wave's
-// too (never three: Lq >= 64/G): a lane picks its row's constants from the two candidates of its wave.
+// global access gets narrower for it.  The results go back through LDS the same way: the last
+// vector of every row is written first, whole (its slots past the row's end land on the first
+// bytes of the next row), then, after a barrier, all the other vectors (which put the right bytes
+// there); then the block stores its range as whole aligned vectors.  Only the block that holds
+// the tensor's last rows may end inside a vector: it reads and writes that vector's bytes one by one.
+// In-place use is safe: a block reads and writes the bytes of its own rows only.
+// Rows are numbered through the whole tensor, so the rows of a block may belong to two heads, those of
+// a wave too (never three: Lq >= 64/G): a lane picks its row's constants from the two candidates of
+// its wave.
 // ---------------------------------------------------------------------------
 template <int G, int V, int WPB, int MODE>
 __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t *__restrict__ logits,
@@ -452,13 +453,11 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
 {
     static_assert((MODE & 1) == 0, "8-bit outputs: input and output ranges coincide");
     constexpr int kRowsPerWave = 64 / G, kRowsPerBlock = WPB * kRowsPerWave;
+    static_assert(kRowsPerBlock % 16 == 0, "a block's first row begins on a vector boundary");
     constexpr int kPaddedLen = G * V * 16;
     constexpr int kThreads = 64 * WPB;
-    // The block's range (up to 15 bytes ahead of the first row + the rows, n <= kPaddedLen - 1 each) has
-    // at most V vectors per thread; a last vector may reach 16 bytes past it.
-    static_assert(kRowsPerBlock >= 15, "one spare byte per row covers the bytes ahead of the first row");
-    constexpr int kPasses = V;
-    constexpr int kStageBytes = kRowsPerBlock * kPaddedLen + 32;
+    // the block's rows (n < kPaddedLen) are at most V vectors per thread; a last vector may reach 16 bytes past them
+    constexpr int kStageBytes = kRowsPerBlock * kPaddedLen + 16;
     __shared__ __attribute__((aligned(16))) uint8_t stage_in[kStageBytes];
     __shared__ __attribute__((aligned(16))) uint8_t stage_out[kStageBytes];
 
@@ -467,43 +466,26 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
     const int sub = lane % G, grp = lane / G;
     const uint32_t block_row0 = blockIdx.x * (uint32_t)kRowsPerBlock;
     const int rows_here = (int)min((uint32_t)kRowsPerBlock, total_rows - block_row0);
-    const uint64_t start = (uint64_t)block_row0 * (uint64_t)n;          // first byte of the block's rows
-    const uint64_t first_vec = start & ~(uint64_t)15;                    // ... widened to a vector boundary
-    const int lead = (int)(start - first_vec);                           // bytes of the first vector ahead of the rows
-    const int span = lead + rows_here * n;                               // bytes from first_vec to the end of the rows
-    const int nchunks = (span + 15) >> 4;
-    const uint64_t total = (uint64_t)total_rows * (uint64_t)n;
+    const size_t start = (size_t)block_row0 * (size_t)n;   // first byte of the block's rows, a multiple of 16
+    const int span = rows_here * n;                         // bytes of the block's rows
+    const int whole = span >> 4, rest = span & 15;          // whole vectors, bytes of the tensor's last, partial vector
+    const int8_t *src = logits + start;
+    uint8_t *dst = out + start;
 
     // ---- the block's vectors -> LDS
     {
-        u32x4 w[kPasses];
-        if (first_vec + (uint64_t)nchunks * 16 <= total) {
+        u32x4 w[V];
 #pragma unroll
-            for (int i = 0; i < kPasses; ++i) {
-                const int c = i * kThreads + tid;
-                if (c < nchunks) w[i] = load_stream(logits + first_vec + (size_t)c * 16);
-            }
-        } else {   // the tensor ends inside the last vector: that one is read byte by byte
-#pragma unroll
-            for (int i = 0; i < kPasses; ++i) {
-                const int c = i * kThreads + tid;
-                if (c < nchunks) {
-                    const uint64_t at = first_vec + (uint64_t)c * 16;
-                    if (at + 16 <= total) {
-                        w[i] = load_stream(logits + at);
-                    } else {
-                        uint32_t t[4];
-                        load_vector_bytes<4>(logits + at, (int)(total - at), t);
-                        w[i] = (u32x4){t[0], t[1], t[2], t[3]};
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < kPasses; ++i) {
+        for (int i = 0; i < V; ++i) {
             const int c = i * kThreads + tid;
-            if (c < nchunks) *(u32x4 *)(stage_in + c * 16) = w[i];
+            if (c < whole) w[i] = load_stream(src + c * 16);
         }
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            const int c = i * kThreads + tid;
+            if (c < whole) *(u32x4 *)(stage_in + c * 16) = w[i];
+        }
+        if (tid < rest) stage_in[whole * 16 + tid] = (uint8_t)src[whole * 16 + tid];
     }
     __syncthreads();
 
@@ -522,7 +504,7 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
     const RowTail<4> tail(n, nvec);
     const int row_in_block = wave * kRowsPerWave + grp;
     const bool row_exists = row_in_block < rows_here;
-    const int row_at = lead + row_in_block * n + sub * 16;   // LDS byte of the lane's first vector
+    const int row_at = row_in_block * n + sub * 16;   // LDS byte of the lane's first vector
     uint32_t d[V][4];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
@@ -554,18 +536,13 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
         if (row_exists && v * G + sub < tail.last_vec) *(u32x4_any *)(stage_out + row_at + v * (G * 16)) = o[v];
     __syncthreads();
 
-    // ---- LDS -> the block's vectors; of the first and the last one only the bytes of the block's rows
+    // ---- LDS -> the block's vectors
 #pragma unroll
-    for (int i = 0; i < kPasses; ++i) {
+    for (int i = 0; i < V; ++i) {
         const int c = i * kThreads + tid;
-        if (c * 16 >= lead && c * 16 + 16 <= span) store_stream(out + first_vec + (size_t)c * 16, *(const u32x4 *)(stage_out + c * 16));
+        if (c < whole) store_stream(dst + c * 16, *(const u32x4 *)(stage_out + c * 16));
     }
-    if (wave == 0 && lane < 32) {
-        const int c = lane < 16 ? 0 : nchunks - 1;
-        const int at = c * 16 + (lane & 15);
-        const bool whole = c * 16 >= lead && c * 16 + 16 <= span;
-        if (!whole && at >= lead && at < span) __builtin_nontemporal_store(stage_out[at], out + first_vec + at);
-    }
+    if (tid < rest) __builtin_nontemporal_store(stage_out[whole * 16 + tid], dst + whole * 16 + tid);
 }
 
 __global__ void reciprocal_kernel(const uint32_t *z, uint32_t *rho, int64_t count)
