@@ -426,26 +426,49 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
 
 // ---------------------------------------------------------------------------
 // Short rows of any length through LDS (8-bit outputs; both tensors begin on a 16-byte boundary;
-// 16 < n < 16*G*V; Lq >= 64/G).
+// 16 < n <= 16*G*V - 15; Lq >= 64/G).
 //
 // The tensor is contiguous even where its rows are not vector-aligned, and 16 consecutive rows
 // are a whole number of vectors whatever n is.  A block takes WPB*64/G rows, a multiple of 16:
 // its byte range begins on a vector boundary and, except at the tensor's end, ends on one, and it
 // goes into LDS as whole aligned vectors: every global access of the block is one contiguous run
-// of full vectors.  The lanes then read their rows out of LDS at the bytes where they lie (LDS
-// takes 16-byte accesses at any byte address, as global memory does), which frees the lane layout
-// from the memory access pattern: G lanes hold V vectors of a row each, so the per-row work
-// (reductions, reciprocal, constants) is spread over 16*V elements per lane, not 16, while no
-// global access gets narrower for it.  The results go back through LDS the same way: the last
-// vector of every row is written first, whole (its slots past the row's end land on the first
-// bytes of the next row), then, after a barrier, all the other vectors (which put the right bytes
-// there); then the block stores its range as whole aligned vectors.  Only the block that holds
-// the tensor's last rows may end inside a vector: it reads and writes that vector's bytes one by one.
+// of full vectors.  That frees the lane layout from the memory access pattern: G lanes hold V
+// vectors of a row each, so the per-row work (reductions, reciprocal, constants) is spread over
+// 16*V elements per lane, not 16, while no global access gets narrower for it.
+// LDS serves a 16-byte access that is not 16-byte aligned one lane per cycle (64 cycles per wave
+// instruction against 6 for reads and 14 for writes when aligned, measured), so the lanes do not
+// read their rows where they begin: a lane takes the aligned vectors of the block's range that its
+// row touches, and replaces the bytes of the first and the last of them that belong to the
+// neighbouring rows with padding (byte masks from a small table in LDS).  A vector that two
+// rows share is thus read by a lane of each.  On the way back the lane with a row's last vector
+// writes it first, whole; after a barrier the lane with the next row's first vector reads it back,
+// puts its own bytes in and writes it again, and all other vectors are written; after another
+// barrier the block stores its range as whole aligned vectors.  Only the block that holds the
+// tensor's last rows may end inside a vector: it reads and writes that vector's bytes one by one.
 // In-place use is safe: a block reads and writes the bytes of its own rows only.
 // Rows are numbered through the whole tensor, so the rows of a block may belong to two heads, those of
 // a wave too (never three: Lq >= 64/G): a lane picks its row's constants from the two candidates of
 // its wave.
 // ---------------------------------------------------------------------------
+// Byte masks of a 16-byte vector, as four dwords: entry k of the first half has ones in bytes k..15
+// (k = 0..15), entry k of the second half in bytes 0..k-1 (k = 0..16).
+struct ByteMasks {
+    uint32_t w[33][4];
+};
+constexpr ByteMasks make_byte_masks()
+{
+    ByteMasks t{};
+    for (int k = 0; k <= 16; ++k)
+        for (int c = 0; c < 4; ++c) {
+            const int left = k - 4 * c;
+            const uint32_t below = left >= 4 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << (8 * left)) - 1u));
+            if (k < 16) t.w[k][c] = ~below;
+            t.w[16 + k][c] = below;
+        }
+    return t;
+}
+__device__ const ByteMasks kByteMasks = make_byte_masks();
+
 template <int G, int V, int WPB, int MODE>
 __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t *__restrict__ logits,
                                                                     uint8_t *__restrict__ out, uint32_t total_rows,
@@ -454,17 +477,25 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
     static_assert((MODE & 1) == 0, "8-bit outputs: input and output ranges coincide");
     constexpr int kRowsPerWave = 64 / G, kRowsPerBlock = WPB * kRowsPerWave;
     static_assert(kRowsPerBlock % 16 == 0, "a block's first row begins on a vector boundary");
-    constexpr int kPaddedLen = G * V * 16;
+    constexpr int kSlots = G * V * 16;   // byte slots of a row's lanes; n + 15 <= kSlots
     constexpr int kThreads = 64 * WPB;
-    // the block's rows (n < kPaddedLen) are at most V vectors per thread; a last vector may reach 16 bytes past them
-    constexpr int kStageBytes = kRowsPerBlock * kPaddedLen + 16;
-    __shared__ __attribute__((aligned(16))) uint8_t stage_in[kStageBytes];
-    __shared__ __attribute__((aligned(16))) uint8_t stage_out[kStageBytes];
+    static_assert(kThreads >= 33, "one thread per mask table entry");
+    constexpr int kStageVectors = kRowsPerBlock * G * V;   // V per thread; the block's rows are fewer
+    __shared__ u32x4 stage_in[kStageVectors + G * V];     // lanes past their row's end read (and mask) what follows
+    __shared__ u32x4 stage_out[kStageVectors];
+    __shared__ u32x4 keep[33];   // [k]: ones in bytes k..15 (k = 0..15); [16 + k]: ones in bytes 0..k-1 (k = 0..16)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int sub = lane % G, grp = lane / G;
-    const uint32_t block_row0 = blockIdx.x * (uint32_t)kRowsPerBlock;
+    // Workgroups go to the 8 dies round-robin.  Neighbouring blocks share the 128-byte lines their
+    // ranges meet in, so of every 64 consecutive blocks each die takes 8 neighbours, which lets its L2 put such a
+    // line together; the blocks behind the last full 64 keep their numbers.
+    const uint32_t in_full_groups = gridDim.x & ~63u;
+    const uint32_t block_no = blockIdx.x < in_full_groups
+                                  ? (blockIdx.x & ~63u) + (blockIdx.x & 7u) * 8u + ((blockIdx.x >> 3) & 7u)
+                                  : blockIdx.x;
+    const uint32_t block_row0 = block_no * (uint32_t)kRowsPerBlock;
     const int rows_here = (int)min((uint32_t)kRowsPerBlock, total_rows - block_row0);
     const size_t start = (size_t)block_row0 * (size_t)n;   // first byte of the block's rows, a multiple of 16
     const int span = rows_here * n;                         // bytes of the block's rows
@@ -472,7 +503,7 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
     const int8_t *src = logits + start;
     uint8_t *dst = out + start;
 
-    // ---- the block's vectors -> LDS
+    // ---- the block's vectors -> LDS; the byte masks
     {
         u32x4 w[V];
 #pragma unroll
@@ -480,12 +511,17 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
             const int c = i * kThreads + tid;
             if (c < whole) w[i] = load_stream(src + c * 16);
         }
+        if (tid < 33) keep[tid] = *(const u32x4 *)kByteMasks.w[tid];
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             const int c = i * kThreads + tid;
-            if (c < whole) *(u32x4 *)(stage_in + c * 16) = w[i];
+            if (c < whole) stage_in[c] = w[i];
         }
-        if (tid < rest) stage_in[whole * 16 + tid] = (uint8_t)src[whole * 16 + tid];
+        if (rest != 0 && tid == 0) {   // the tensor ends inside this vector: its bytes one by one
+            uint32_t t[4];
+            load_vector_bytes<4>(src + whole * 16, rest, t);
+            stage_in[whole] = (u32x4){t[0], t[1], t[2], t[3]};
+        }
     }
     __syncthreads();
 
@@ -499,50 +535,59 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
     const bool next_head = grp >= change;
     const int B = next_head ? hp1.x : hp0.x, S = next_head ? hp1.y : hp0.y, D = next_head ? hp1.z : hp0.z;
 
-    // ---- the lane's vectors of its row
-    const int nvec = (n + 15) >> 4;
-    const RowTail<4> tail(n, nvec);
+    // ---- the lane's vectors of its row: vector first + v*G + sub of the block's range; the bytes of other
+    // rows in it, and all of it if the row ends before it, become padding
     const int row_in_block = wave * kRowsPerWave + grp;
     const bool row_exists = row_in_block < rows_here;
-    const int row_at = row_in_block * n + sub * 16;   // LDS byte of the lane's first vector
+    const int row_begin = (int)__umul24((uint32_t)row_in_block, (uint32_t)n), row_last = row_begin + n - 1;   // bytes of the block's range
+    const int first = row_begin >> 4, last = row_last >> 4;
+    const u32x4 from = keep[sub == 0 ? (row_begin & 15) : 0];
     uint32_t d[V][4];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int vi = v * G + sub;
-        if (row_exists && vi < nvec) {
-            const u32x4 t = *(const u32x4_any *)(stage_in + row_at + v * (G * 16));
-            d[v][0] = t[0], d[v][1] = t[1], d[v][2] = t[2], d[v][3] = t[3];
-            if (vi == tail.last_vec) tail.pad(d[v]);
-        } else {
+        const int c = first + v * G + sub;
+        const int bytes = !row_exists || c > last ? 0 : (c == last ? (row_last & 15) + 1 : 16);
+        u32x4 mine = keep[16 + bytes];
+        if (v == 0) mine &= from;
+        const u32x4 t = stage_in[c];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) d[v][c] = kPadWord;
-        }
+        for (int e = 0; e < 4; ++e) d[v][e] = (t[e] & mine[e]) | (kPadWord & ~mine[e]);
     }
 
     const int m = group_max<G>(lane_max(d));
     const int t = group_sum<G>(lane_distances(d, m, D));
-    const RowOutput<MODE> ro((uint32_t)(n * B - S * clamped_sum(t, kPaddedLen, n, (uint32_t)(m + 128), D)), B, S, D);
+    const RowOutput<MODE> ro((uint32_t)(n * B - S * clamped_sum(t, kSlots, n, (uint32_t)(m + 128), D)), B, S, D);
     u32x4 o[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) o[v] = ro.vector(d[v]);
 
-    // ---- results -> LDS: last vectors first, whole; then the others
+    // ---- results -> LDS: each row's last vector first, whole
 #pragma unroll
     for (int v = 0; v < V; ++v)
-        if (row_exists && v * G + sub == tail.last_vec) *(u32x4_any *)(stage_out + row_at + v * (G * 16)) = o[v];
+        if (row_exists && first + v * G + sub == last) stage_out[last] = o[v];
     __syncthreads();
+    // then the others; a first vector that begins with the previous row's last bytes keeps those
 #pragma unroll
-    for (int v = 0; v < V; ++v)
-        if (row_exists && v * G + sub < tail.last_vec) *(u32x4_any *)(stage_out + row_at + v * (G * 16)) = o[v];
+    for (int v = 0; v < V; ++v) {
+        const int c = first + v * G + sub;
+        if (row_exists && c < last) {
+            u32x4 r = o[v];
+            if (v == 0 && sub == 0 && (row_begin & 15) != 0) {
+                const u32x4 theirs = stage_out[c];
+                r = (r & from) | (theirs & ~from);
+            }
+            stage_out[c] = r;
+        }
+    }
     __syncthreads();
 
     // ---- LDS -> the block's vectors
 #pragma unroll
     for (int i = 0; i < V; ++i) {
         const int c = i * kThreads + tid;
-        if (c < whole) store_stream(dst + c * 16, *(const u32x4 *)(stage_out + c * 16));
+        if (c < whole) store_stream(dst + c * 16, stage_out[c]);
     }
-    if (tid < rest) __builtin_nontemporal_store(stage_out[whole * 16 + tid], dst + whole * 16 + tid);
+    if (tid < rest) __builtin_nontemporal_store(((const uint8_t *)stage_out)[whole * 16 + tid], dst + whole * 16 + tid);
 }
 
 __global__ void reciprocal_kernel(const uint32_t *z, uint32_t *rho, int64_t count)
@@ -628,10 +673,9 @@ static hipError_t launch_shape(const int8_t *x, uint8_t *p, int64_t Bt, int H, i
     return launch(hccs_row_block_kernel<16, MODE, RAGGED>, grid, dim3(256), st, x, p, Lq, Lk, last_slab, place, tab);
 }
 
-// Rows through LDS: G lanes x V vectors per row, blocks of WPB waves.  The caller keeps n below 16*G*V
-// and Lq at 64/G or more.
-// Measured on [64,12,197,197]: 8 lanes x 2 vectors per row in blocks of 2 waves 13.4 us; blocks of 1, 4, 8
-// waves 13.6, 13.7, 15.4; 16 lanes x 1 vector 15.9-17.8; 4 lanes x 4 vectors 18.2-20.1.
+// Rows through LDS: G lanes x V vectors per row, blocks of WPB waves.  The caller keeps n + 15 within 16*G*V
+// and Lq at 64/G or more.  Measured on [64,12,197,197]: 8 lanes x 2 vectors per row in blocks of 2 waves 13.3 us;
+// blocks of 1, 4, 8 waves 13.6, 13.7, 15.4; 16 lanes x 1 vector 15.6; 4 lanes x 4 vectors 18.9; 8 x 3 19.3.
 template <int G, int V, int WPB, int MODE>
 static hipError_t launch_staged(const int8_t *x, uint8_t *p, int64_t Bt, int H, int Lq, int Lk, const HeadTable &tab,
                                 hipStream_t st)
@@ -649,12 +693,17 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int64_t Bt, int H, in
     // aligned vectors when both tensors begin on a 16-byte boundary and rows are whole vectors
     if (aligned && Lk % ((MODE & 1) ? 8 : 16) == 0) return launch_shape<MODE, false>(x, p, Bt, H, Lq, Lk, tab, st);
     if constexpr ((MODE & 1) == 0) {
-        // short rows of other lengths in tensors that begin on a 16-byte boundary: through LDS
-        // ([64,12,197,n], against the register kernel with vectors at any address: n = 77 8.3 against 9.5 us, 100 8.4 / 9.0,
-        // 120 8.5 / 9.6, 150 12.6 / 14.5, 197 13.5 / 15.2, 230 14.4 / 15.8, 250 15.1 / 16.4; no gain up to 64)
+        // Rows of other lengths in tensors that begin on a 16-byte boundary go through LDS where that measured
+        // faster than vectors at any address ([64,12,197,n] in us, through LDS / at any address: n = 70 7.9 / 8.8,
+        // 100 8.1 / 9.1, 113 8.6 / 9.5, 150 12.2 / 14.4, 197 13.3 / 15.1, 241 14.8 / 15.6, 270 20.1 / 20.5,
+        // 300 20.5 / 22.2, 380 21.9 / 28.5, 450 24.5 / 30.8, 497 27.2 / 33.6, 785 42.2 / 43.2, 900 45.7 / 48.5,
+        // 1000 49.0 / 53.8; slower or equal in the gaps: 120 11.6 / 9.6, 250 19.9 / 16.4, 520 37.7 / 33.4,
+        // 700 39.9 / 38.9).  The time of a lane layout hardly depends on n, so each serves the lengths that fill it.
         if (aligned && Lq >= 16) {
-            if (Lk > 64 && Lk < 128) return launch_staged<4, 2, 2, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
-            if (Lk > 128 && Lk < 256) return launch_staged<8, 2, 2, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
+            if (Lk > 64 && Lk <= 113) return launch_staged<4, 2, 2, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
+            if (Lk > 128 && Lk <= 241) return launch_staged<8, 2, 2, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
+            if (Lk > 256 && Lk <= 497) return launch_staged<16, 2, 4, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
+            if (Lk > 768 && Lk <= 1009) return launch_staged<32, 2, 8, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
         }
     }
     return launch_shape<MODE, true>(x, p, Bt, H, Lq, Lk, tab, st);

@@ -118,10 +118,12 @@ RAGGED_SHAPES = [
     ((1, 1, 5, 3000), 0), ((1, 1, 3, 4099), 0), ((1, 1, 3, 8100), 0), ((1, 1, 3, 16351), 0), ((1, 1, 2, 16353), 0),
     ((2, 3, 197, 197), 0), ((1, 5, 77, 77), 1), ((3, 2, 61, 250), 1), ((1, 2, 130, 999), 0), ((1, 64, 5, 21), 1),
     ((1, 2, 40, 500), 0), ((1, 2, 9, 1000), 0), ((1, 3, 33, 104), 1), ((1, 2, 21, 2040), 0), ((1, 2, 19, 252), 1),
-    # short rows through LDS (both lane layouts): a head change inside every wave, every block, or rarely; one row
-    # in the last block; the shortest and the longest length of each layout; lengths just outside
-    ((2, 5, 16, 100), 1), ((3, 7, 17, 255), 1), ((1, 4, 23, 65), 1), ((5, 3, 65, 127), 1), ((1, 1, 129, 129), 1),
+    # rows through LDS (every lane layout): a head change inside every wave, every block, or rarely; one row in
+    # the last block; the shortest and the longest length of each layout; lengths just outside
+    ((2, 5, 16, 100), 1), ((3, 7, 17, 241), 1), ((1, 4, 23, 65), 1), ((5, 3, 65, 113), 1), ((1, 1, 129, 129), 1),
     ((1, 2, 64, 199), 1), ((4, 64, 16, 145), 1), ((2, 5, 16, 37), 1), ((1, 1, 129, 63), 1), ((2, 3, 15, 150), 1),
+    ((2, 3, 33, 257), 1), ((1, 2, 50, 300), 1), ((3, 2, 16, 497), 1), ((1, 2, 21, 498), 1), ((2, 2, 19, 769), 0),
+    ((1, 3, 35, 800), 0), ((2, 2, 16, 1009), 0), ((1, 2, 17, 1010), 0), ((1, 2, 40, 114), 1), ((1, 2, 40, 242), 1),
     # slabs shorter than a vector (the guard on the tensor's last vectors spans several rows and slabs)
     ((7, 3, 1, 5), 1), ((2, 2, 2, 3), 1), ((1, 1, 1, 1), 1), ((1, 1, 1, 15), 1), ((3, 1, 1, 17), 1), ((9, 1, 1, 2), 1),
     # ragged lengths beyond a wave's registers: one block per row
