@@ -551,7 +551,10 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
         if (v == 0) mine &= from;
         const u32x4 t = stage_in[c];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) d[v][e] = (t[e] & mine[e]) | (kPadWord & ~mine[e]);
+        for (int e = 0; e < 4; ++e) {
+            d[v][e] = (t[e] & mine[e]) | (kPadWord & ~mine[e]);
+            asm("" : "+v"(d[v][e]));   // one value: the compiler would otherwise derive a second masked form for the distances
+        }
     }
 
     const int m = group_max<G>(lane_max(d));
