@@ -424,8 +424,27 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
     }
 }
 
+// Byte masks of a 16-byte vector, as four dwords: entry k of the first half has ones in bytes k..15
+// (k = 0..15), entry k of the second half in bytes 0..k-1 (k = 0..16).
+struct ByteMasks {
+    uint32_t w[33][4];
+};
+constexpr ByteMasks make_byte_masks()
+{
+    ByteMasks t{};
+    for (int k = 0; k <= 16; ++k)
+        for (int c = 0; c < 4; ++c) {
+            const int left = k - 4 * c;
+            const uint32_t below = left >= 4 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << (8 * left)) - 1u));
+            if (k < 16) t.w[k][c] = ~below;
+            t.w[16 + k][c] = below;
+        }
+    return t;
+}
+__device__ const ByteMasks kByteMasks = make_byte_masks();
+
 // ---------------------------------------------------------------------------
-// Short rows of any length through LDS (8-bit outputs; both tensors begin on a 16-byte boundary;
+// Rows of any length through LDS (8-bit outputs; both tensors begin on a 16-byte boundary;
 // 16 < n <= 16*G*V - 15; Lq >= 64/G).
 //
 // The tensor is contiguous even where its rows are not vector-aligned, and 16 consecutive rows
@@ -450,25 +469,6 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
 // a wave too (never three: Lq >= 64/G): a lane picks its row's constants from the two candidates of
 // its wave.
 // ---------------------------------------------------------------------------
-// Byte masks of a 16-byte vector, as four dwords: entry k of the first half has ones in bytes k..15
-// (k = 0..15), entry k of the second half in bytes 0..k-1 (k = 0..16).
-struct ByteMasks {
-    uint32_t w[33][4];
-};
-constexpr ByteMasks make_byte_masks()
-{
-    ByteMasks t{};
-    for (int k = 0; k <= 16; ++k)
-        for (int c = 0; c < 4; ++c) {
-            const int left = k - 4 * c;
-            const uint32_t below = left >= 4 ? 0xffffffffu : (left <= 0 ? 0u : ((1u << (8 * left)) - 1u));
-            if (k < 16) t.w[k][c] = ~below;
-            t.w[16 + k][c] = below;
-        }
-    return t;
-}
-__device__ const ByteMasks kByteMasks = make_byte_masks();
-
 template <int G, int V, int WPB, int MODE>
 __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t *__restrict__ logits,
                                                                     uint8_t *__restrict__ out, uint32_t total_rows,
