@@ -279,18 +279,26 @@ inline BlockPlace place_blocks(int64_t tiles, int H, int64_t Bt, dim3 &grid)
 // Launches `kernel` and returns the status of this launch alone (an error left behind by an
 // earlier, unrelated runtime call is neither reported nor cleared here).
 template <typename... Params, typename... Args, size_t... I>
-inline hipError_t launch_impl(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t st,
+inline hipError_t launch_impl(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st,
                               std::index_sequence<I...>, Args &&...args)
 {
     std::tuple<Params...> held(static_cast<Params>(std::forward<Args>(args))...);
     void *ptrs[] = {(void *)&std::get<I>(held)...};
-    return hipLaunchKernel((const void *)kernel, grid, block, ptrs, 0, st);
+    return hipLaunchKernel((const void *)kernel, grid, block, ptrs, lds_bytes, st);
 }
 template <typename... Params, typename... Args>
 inline hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t st, Args &&...args)
 {
     static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
-    return launch_impl(kernel, grid, block, st, std::index_sequence_for<Params...>{}, std::forward<Args>(args)...);
+    return launch_impl(kernel, grid, block, 0, st, std::index_sequence_for<Params...>{}, std::forward<Args>(args)...);
+}
+// The same with `lds_bytes` of LDS per block that the kernel does not touch: fewer blocks fit a compute unit at once.
+template <typename... Params, typename... Args>
+inline hipError_t launch_fewer(void (*kernel)(Params...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st,
+                               Args &&...args)
+{
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    return launch_impl(kernel, grid, block, lds_bytes, st, std::index_sequence_for<Params...>{}, std::forward<Args>(args)...);
 }
 
 // P <= 127 for every row the table allows: the largest probability of a row is that of its maximum,

@@ -356,20 +356,21 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_kernel(const int8_t *__res
 }
 
 // ---------------------------------------------------------------------------
-// One block (four waves) per row, for rows beyond a wave's registers (16384 < Lk <= 65536):
-// thread t holds vectors t, t + 256, ...; the maximum and the sum cross waves through LDS.
+// One block of WAVES waves per row, for rows of more than 4096 bytes (256 vectors): thread t holds vectors
+// t, t + 64*WAVES, ...; the maximum and the sum cross waves through LDS.
 // Same arithmetic, the same padding rule and the same RAGGED forms as the kernel above.
 // ---------------------------------------------------------------------------
-template <int V, int MODE, bool RAGGED>
-__global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__restrict__ logits,
+template <int V, int WAVES, int MODE, bool RAGGED>
+__global__ __launch_bounds__(64 * WAVES) void hccs_row_block_kernel(const int8_t *__restrict__ logits,
                                                              uint8_t *__restrict__ out, int Lq, int n,
                                                              uint32_t last_slab, BlockPlace place, HeadTable table)
 {
     constexpr int kOutBytes = (MODE & 1) ? 2 : 1;
     constexpr int DW = 4 / kOutBytes;
     constexpr int kVecBytes = DW * 4;
-    constexpr int kPaddedLen = 256 * V * kVecBytes;
-    __shared__ int red[2][4];
+    constexpr int kThreads = 64 * WAVES;
+    constexpr int kPaddedLen = kThreads * V * kVecBytes;
+    __shared__ int red[2][WAVES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t tile, head, slab_no;   // one block per row: the tile is the row inside the slab
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
     uint32_t d[V][DW];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int vi = v * 256 + tid;
+        const int vi = v * kThreads + tid;
         if (vi < nvec) {
             if (RAGGED && last_row && vi == tail.last_vec)
                 load_vector_bytes<DW>(src + vi * kVecBytes, tail.tail_elems, d[v]);
@@ -401,19 +402,23 @@ __global__ __launch_bounds__(256) void hccs_row_block_kernel(const int8_t *__res
     int m = group_max<64>(lane_max(d));
     if (lane == 0) red[0][wave] = m;
     __syncthreads();
-    m = max(max(red[0][0], red[0][1]), max(red[0][2], red[0][3]));
+    m = red[0][0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) m = max(m, red[0][w]);
     const uint32_t mu = (uint32_t)(m + 128);
 
     int t = group_sum<64>(lane_distances(d, m, D));
     if (lane == 0) red[1][wave] = t;
     __syncthreads();
-    t = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    t = red[1][0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) t += red[1][w];
     const int sum_clamped = clamped_sum(t, kPaddedLen, n, mu, D);
     const uint32_t Z = (uint32_t)(n * B - S * sum_clamped);
     const RowOutput<MODE> ro(Z, B, S, D);
 #pragma unroll
     for (int v = 0; v < V; ++v) {
-        const int vi = v * 256 + tid;
+        const int vi = v * kThreads + tid;
         const u32x4 o = ro.vector(d[v]);
         if (vi < nvec) {
             if (RAGGED && vi == tail.last_vec && tail.tail_elems < kVecBytes)
@@ -637,8 +642,14 @@ static hipError_t launch_rows(const int8_t *x, uint8_t *p, int64_t Bt, int H, in
     constexpr int kRowsPerBlock = WPB * R * (64 / G);
     dim3 grid;
     const BlockPlace place = place_blocks((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt, grid);
-    return launch(hccs_rows_kernel<G, V, R, WPB, MODE, RAGGED>, grid, dim3(64 * WPB), st, x, p, Lq, n,
-                  (uint32_t)(Bt * H - 1), place, tab);
+    // Rows of 2049..4096 bytes, a wave each with four vectors per lane in flight: with all eight blocks a compute
+    // unit can hold, 128 KiB per unit are under way and memory serves them more slowly than 64 KiB (a plain copy shows
+    // the same: 0.76 of peak with 128 KiB per unit in flight, 0.79-0.82 with 32-64 KiB).  32 KiB of untouched LDS per block leave
+    // four blocks per unit: [4,16,4096,4096] 333 against 343 us, [4,16,1024,4096] 82.1 against 83.7 us; no gain at the
+    // other row lengths (2048: 173 against 167 us with four blocks; 8192, 16384: equal).
+    constexpr size_t kHeldBack = (G == 64 && V == 4 && (MODE & 1) == 0 && !RAGGED) ? (32u << 10) : 0;
+    return launch_fewer(hccs_rows_kernel<G, V, R, WPB, MODE, RAGGED>, grid, dim3(64 * WPB), kHeldBack, st, x, p, Lq, n,
+                        (uint32_t)(Bt * H - 1), place, tab);
 }
 
 template <int MODE, bool RAGGED>
@@ -647,10 +658,13 @@ static hipError_t launch_shape(const int8_t *x, uint8_t *p, int64_t Bt, int H, i
 {
     constexpr int VB = (MODE & 1) ? 8 : 16;   // input bytes per vector
     const int nvec = (Lk + VB - 1) / VB;
-    if (Lk <= 16384) {                        // a wave holds the row
+    // Whole aligned rows of 3968..4096 bytes run 2-3 % faster as blocks of two waves than as a wave each
+    // ([4,16,4096,4096] 328 against 334 us, 3968 bytes 320 against 329; 3840 bytes 321 against 318: the wave form).
+    const bool two_waves = !RAGGED && (MODE & 1) == 0 && nvec >= 248;
+    if (nvec <= 256 && !two_waves) {          // a wave holds the row
         // Lane-group width G: a power of two that covers the row with one or two vectors
         // per lane, so that each load/store instruction touches G contiguous vectors of a
-        // row; beyond 128 vectors the row takes V vectors per lane of a whole wave.  Few rows
+        // row; beyond 128 vectors the row takes four vectors per lane of a whole wave.  Few rows
         // in flight per wave (R) and many waves measured faster than the reverse; with vectors
         // at any address one row batch per wave measured best ([64,12,197,197]: 15.3 against
         // 16.0 us, [256,8,128,250]: 26.2 against 29.4 us).
@@ -661,19 +675,26 @@ static hipError_t launch_shape(const int8_t *x, uint8_t *p, int64_t Bt, int H, i
         if (nvec <= 32) return launch_rows<16, 2, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
         if (nvec <= 64) return launch_rows<32, 2, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);   // measured against <64,1,2>: up to 20 % faster below 48 vectors, equal at 64
         if (nvec <= 128) return launch_rows<64, 2, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
-        if (nvec <= 256) return launch_rows<64, 4, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
-        if (nvec <= 512) return launch_rows<64, 8, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
-        if (nvec <= 1024) return launch_rows<64, 16, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
-        return launch_rows<64, 32, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);   // 16-bit modes, 8192 < Lk <= 16384
+        return launch_rows<64, 4, 1, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
     }
-    // 16384 < Lk <= 65536: one block per row, the row in the block's registers
+    // Longer rows: one block per row, two vectors per thread (four beyond 2048 vectors) and as many waves as
+    // that takes.  Measured against a wave per row with 8, 16 or 32 vectors per lane, and, beyond 16 KiB, against
+    // four waves with 8 or 16 vectors per thread (fraction of 8 TB/s, that form / this one): 4112 bytes 0.66 / 0.73,
+    // 6000 0.70 / 0.74, 8192 0.77 / 0.80, 10240 0.77 / 0.79, 12000 0.72 / 0.73, 16384 0.74 / 0.80, 20000 0.70 / 0.76,
+    // 32768 0.78 / 0.78, 50000 0.70 / 0.75, 65536 0.70 / 0.72: about 64 KiB per compute unit are in flight at full occupancy.
     dim3 grid;
     const BlockPlace place = place_blocks(Lq, H, Bt, grid);
     const uint32_t last_slab = (uint32_t)(Bt * H - 1);
+    if (nvec <= 256)
+        return launch(hccs_row_block_kernel<2, 2, MODE, RAGGED>, grid, dim3(128), st, x, p, Lq, Lk, last_slab, place, tab);
+    if (nvec <= 512)
+        return launch(hccs_row_block_kernel<2, 4, MODE, RAGGED>, grid, dim3(256), st, x, p, Lq, Lk, last_slab, place, tab);
+    if (nvec <= 1024)
+        return launch(hccs_row_block_kernel<2, 8, MODE, RAGGED>, grid, dim3(512), st, x, p, Lq, Lk, last_slab, place, tab);
     if (nvec <= 2048)
-        return launch(hccs_row_block_kernel<8, MODE, RAGGED>, grid, dim3(256), st, x, p, Lq, Lk, last_slab, place, tab);
+        return launch(hccs_row_block_kernel<2, 16, MODE, RAGGED>, grid, dim3(1024), st, x, p, Lq, Lk, last_slab, place, tab);
     // at most 4096 vectors: Lk <= 65536 in the 8-bit modes, and the 16-bit modes need Lk*B <= 32767
-    return launch(hccs_row_block_kernel<16, MODE, RAGGED>, grid, dim3(256), st, x, p, Lq, Lk, last_slab, place, tab);
+    return launch(hccs_row_block_kernel<4, 16, MODE, RAGGED>, grid, dim3(1024), st, x, p, Lq, Lk, last_slab, place, tab);
 }
 
 // Rows through LDS: G lanes x V vectors per row, blocks of WPB waves.  The caller keeps n + 15 within 16*G*V

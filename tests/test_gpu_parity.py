@@ -59,6 +59,8 @@ SHAPES = [
     ((1, 1, 1, 65536), 0), ((1, 2, 2, 16400), 0),
     # one block per row: multiples of 16 beyond 16384
     ((1, 2, 3, 32768), 0), ((2, 1, 2, 40000), 0), ((1, 1, 5, 65520), 0),
+    # either side of the lengths at which the row kernels change form
+    ((1, 2, 5, 3952), 0), ((1, 2, 5, 3968), 0), ((1, 2, 3, 4112), 0), ((1, 1, 3, 8208), 0), ((1, 1, 2, 32784), 0),
 ]
 
 
