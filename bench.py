@@ -37,7 +37,7 @@ KERNEL_SOURCES = ["paper_2604_02292_amd/csrc/hccs_softmax.hip", "paper_2604_0229
 
 # the row kernel each stand-alone workload is dispatched to (hccs_softmax.hip, launch_mode)
 ROW_KERNELS = {"pr1_ref": "hccs_rows_kernel<4,1,1,1,0,false>", "edge_encoder": "hccs_rows_kernel<8,1,1,1,0,false>",
-               "stress_rows": "hccs_rows_kernel<32,1,1,1,0,false>", "long_row": "hccs_row_block_kernel<2,2,0,false>",
+               "stress_rows": "hccs_rows_kernel<16,2,1,4,0,false>", "long_row": "hccs_row_block_kernel<2,2,0,false>",
                "ragged_rows": "hccs_rows_staged_kernel<8,2,2,0>"}
 HEADLINE = "long_row"
 

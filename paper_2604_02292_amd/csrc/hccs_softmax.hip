@@ -668,18 +668,16 @@ static hipError_t launch_shape(const int8_t *x, uint8_t *p, int64_t Bt, int H, i
         // in flight per wave (R) and many waves measured faster than the reverse; with vectors
         // at any address one row batch per wave measured best ([64,12,197,197]: 15.3 against
         // 16.0 us, [256,8,128,250]: 26.2 against 29.4 us).
-        // Whole rows of exactly 4, 8, 16, 32 or 64 vectors fill their lane group with one vector per lane; blocks of
-        // one wave with one row batch then run 2-3 % faster than the forms below (the same in a plain copy: one vector
-        // per thread in blocks of one wave is its fastest form): [256,8,128,128] 12.4 against 12.7 us, [64,12,512,512]
-        // 60.6 against 62.5, [256,8,128,256] 22.0 against 22.7, [16,16,2048,1024] 162.8 against 165.5, [512,8,128,64]
-        // 12.4 against 12.7.  Rows that leave lanes of such a group empty are slower in it (96 bytes 11.1 against 10.8 us,
-        // 160 18.5 against 16.1, 320 50.5 against 43.4, 640 137.7 against 108.0).
-        if constexpr (!RAGGED) {
+        // Whole rows of exactly 4 or 8 vectors fill their lane group with one vector per lane; blocks of one wave
+        // with one row batch then run 2 % faster than the forms below in the 8-bit modes (the same in a plain copy: one
+        // vector per thread in blocks of one wave is its fastest form): [256,8,128,128] 12.4 against 12.7 us,
+        // [512,8,128,64] 12.4 against 12.7.  Not so the 16-bit modes ([256,8,128,128]: 19.0 against 17.9 us), rows that
+        // leave lanes of the group empty (96 bytes 11.1 against 10.8 us), or rows of 16, 32 and 64 vectors: back to back
+        // they gain 2-3 % too ([64,12,512,512] 60.6 against 62.5 us), but a launch on its own, as a profiler times it,
+        // loses as much to its hundreds of thousands of one-wave blocks (64.7 against 62.7 us).
+        if constexpr (!RAGGED && (MODE & 1) == 0) {
             if (nvec == 4) return launch_rows<4, 1, 1, 1, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
             if (nvec == 8) return launch_rows<8, 1, 1, 1, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
-            if (nvec == 16) return launch_rows<16, 1, 1, 1, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
-            if (nvec == 32) return launch_rows<32, 1, 1, 1, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
-            if (nvec == 64) return launch_rows<64, 1, 1, 1, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
         }
         constexpr int R = RAGGED ? 1 : 2;
         if (nvec <= 4) return launch_rows<4, 1, R, 4, MODE, RAGGED>(x, p, Bt, H, Lq, Lk, tab, st);
