@@ -618,18 +618,12 @@ __global__ __launch_bounds__(64) void normalise_table_kernel(const int4 *__restr
     out[i * 64 + threadIdx.x] = normalise4(d0 | ((d0 + 1) << 8) | ((d0 + 2) << 16) | ((d0 + 3) << 24), ra);
 }
 
-__global__ __launch_bounds__(256) void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst,
-                                                   int64_t count)
+// One vector per thread, blocks of one wave: the fastest of the forms measured for a plain copy (1 GiB each way:
+// 0.84 of 8 TB/s against 0.76-0.78 with four vectors per thread in blocks of four waves; 32 MiB each way: 0.71 against 0.68).
+__global__ __launch_bounds__(64) void copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t count)
 {
-    // four vectors per lane, each a fully coalesced 4 KiB block-wide access
-    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
-    u32x4 v[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-        if (base + k * 256 < count) v[k] = load_stream(src + base + k * 256);
-#pragma unroll
-    for (int k = 0; k < 4; ++k)
-        if (base + k * 256 < count) store_stream(dst + base + k * 256, v[k]);
+    const int64_t i = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    if (i < count) store_stream(dst + i, load_stream(src + i));
 }
 
 // ---------------------------------------------------------------------------
@@ -775,8 +769,8 @@ hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st
 {
     const int64_t count = bytes / 16;
     if (count == 0) return hipSuccess;
-    return launch(copy_kernel, dim3((unsigned)((count + 1023) / 1024)), dim3(256), st, (const u32x4 *)src,
-                  (u32x4 *)dst, count);
+    if ((count + 63) / 64 > 0x7fffffff) return hipErrorInvalidValue;
+    return launch(copy_kernel, dim3((unsigned)((count + 63) / 64)), dim3(64), st, (const u32x4 *)src, (u32x4 *)dst, count);
 }
 
 }  // namespace hccs
