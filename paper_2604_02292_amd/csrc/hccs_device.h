@@ -260,18 +260,27 @@ inline FastDiv make_fast_div(uint32_t d)
 // count, below 2^31) and the block number is taken apart by multiply-shift divisions.
 struct BlockPlace {
     FastDiv by_tiles, by_H;
+    // neighbours: workgroups go to the 8 dies round-robin; of every 64 consecutive blocks each die then takes 8
+    // consecutive ones (the blocks behind the last full 64 keep their numbers).  For rows that are no whole
+    // number of 128-byte lines, where consecutive blocks meet inside lines that the die's L2 can then put
+    // together: 2-7 % faster ([4,16,2048,4000] 173 against 180 us, 6000 bytes 257 against 262, 12000 bytes 248
+    // against 266, 50000 bytes 266 against 274); rows of whole lines lose 5-6 % with it ([4,16,4096,4096] 349 against 328 us).
+    uint32_t neighbours;
     __device__ __forceinline__ void locate(uint32_t &tile, uint32_t &head, uint32_t &slab) const
     {
-        slab = by_tiles.quotient(blockIdx.x);
-        tile = blockIdx.x - slab * by_tiles.divisor;
+        uint32_t block = blockIdx.x;
+        if (neighbours && block < (gridDim.x & ~63u)) block = (block & ~63u) + (block & 7u) * 8u + ((block >> 3) & 7u);
+        slab = by_tiles.quotient(block);
+        tile = block - slab * by_tiles.divisor;
         head = slab - by_H.quotient(slab) * by_H.divisor;
     }
 };
 // grid and block placement for `tiles` blocks per slab (tiles*H*Bt < 2^31)
-inline BlockPlace place_blocks(int64_t tiles, int H, int64_t Bt, dim3 &grid)
+inline BlockPlace place_blocks(int64_t tiles, int H, int64_t Bt, dim3 &grid, bool neighbours = false)
 {
     BlockPlace bp;
     bp.by_tiles = make_fast_div((uint32_t)tiles), bp.by_H = make_fast_div((uint32_t)H);
+    bp.neighbours = neighbours ? 1u : 0u;
     grid = dim3((uint32_t)(tiles * H * Bt));
     return bp;
 }

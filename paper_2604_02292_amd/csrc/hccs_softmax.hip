@@ -635,7 +635,10 @@ static hipError_t launch_rows(const int8_t *x, uint8_t *p, int64_t Bt, int H, in
 {
     constexpr int kRowsPerBlock = WPB * R * (64 / G);
     dim3 grid;
-    const BlockPlace place = place_blocks((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt, grid);
+    // neighbouring blocks on one die when they meet inside 128-byte lines, for rows of more than 2048 bytes (shorter
+    // rows lose with it: 2000 bytes 180 against 174 us, 1040 bytes 104 against 102)
+    const BlockPlace place = place_blocks((Lq + kRowsPerBlock - 1) / kRowsPerBlock, H, Bt, grid,
+                                          G == 64 && V == 4 && (kRowsPerBlock * n) % 128 != 0);
     // Rows of 2049..4096 bytes, a wave each with four vectors per lane in flight: with all eight blocks a compute
     // unit can hold, 128 KiB per unit are under way and memory serves them more slowly than 64 KiB (a plain copy shows
     // the same: 0.76 of peak with 128 KiB per unit in flight, 0.79-0.82 with 32-64 KiB).  32 KiB of untouched LDS per block leave
@@ -688,7 +691,7 @@ static hipError_t launch_shape(const int8_t *x, uint8_t *p, int64_t Bt, int H, i
     // 6000 0.70 / 0.74, 8192 0.77 / 0.80, 10240 0.77 / 0.79, 12000 0.72 / 0.73, 16384 0.74 / 0.80, 20000 0.70 / 0.76,
     // 32768 0.78 / 0.78, 50000 0.70 / 0.75, 65536 0.70 / 0.72: about 64 KiB per compute unit are in flight at full occupancy.
     dim3 grid;
-    const BlockPlace place = place_blocks(Lq, H, Bt, grid);
+    const BlockPlace place = place_blocks(Lq, H, Bt, grid, Lk % 128 != 0);
     const uint32_t last_slab = (uint32_t)(Bt * H - 1);
     if (nvec <= 256)
         return launch(hccs_row_block_kernel<2, 2, MODE, RAGGED>, grid, dim3(128), st, x, p, Lq, Lk, last_slab, place, tab);
