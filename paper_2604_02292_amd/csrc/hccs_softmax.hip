@@ -537,8 +537,6 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
     const uint32_t head1 = head0 + 1 == by_H.divisor ? 0u : head0 + 1;
     const int change = (int)((slab0 + 1) * by_Lq.divisor - wave_row0);   // the wave's first row (counted from its own first) of the next head
     const int4 hp0 = table.e[head0], hp1 = table.e[head1];
-    const bool next_head = grp >= change;
-    const int B = next_head ? hp1.x : hp0.x, S = next_head ? hp1.y : hp0.y, D = next_head ? hp1.z : hp0.z;
 
     // ---- the lane's vectors of its row: vector first + v*G + sub of the block's range; the bytes of other
     // rows in it, and all of it if the row ends before it, become padding
@@ -562,12 +560,21 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
         }
     }
 
-    const int m = group_max<G>(lane_max(d));
-    const int t = group_sum<G>(lane_distances(d, m, D));
-    const RowOutput<MODE> ro((uint32_t)(n * B - S * clamped_sum(t, kSlots, n, (uint32_t)(m + 128), D)), B, S, D);
     u32x4 o[V];
+    auto outputs = [&](int B, int S, int D) {
+        const int m = group_max<G>(lane_max(d));
+        const int t = group_sum<G>(lane_distances(d, m, D));
+        const RowOutput<MODE> ro((uint32_t)(n * B - S * clamped_sum(t, kSlots, n, (uint32_t)(m + 128), D)), B, S, D);
 #pragma unroll
-    for (int v = 0; v < V; ++v) o[v] = ro.vector(d[v]);
+        for (int v = 0; v < V; ++v) o[v] = ro.vector(d[v]);
+    };
+    // Most waves lie inside one head: its constants then stay scalar (and what is computed from them alone, too).
+    if (change >= kRowsPerWave) {
+        outputs(hp0.x, hp0.y, hp0.z);
+    } else {
+        const bool next_head = grp >= change;
+        outputs(next_head ? hp1.x : hp0.x, next_head ? hp1.y : hp0.y, next_head ? hp1.z : hp0.z);
+    }
 
     // ---- results -> LDS: each row's last vector first, whole
 #pragma unroll
