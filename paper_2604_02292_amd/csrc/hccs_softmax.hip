@@ -429,6 +429,9 @@ __global__ __launch_bounds__(64 * WAVES) void hccs_row_block_kernel(const int8_t
     }
 }
 
+// min(max(x, 0), 16) (one v_med3_i32)
+__device__ __forceinline__ int clamp_bytes(int x) { return min(max(x, 0), 16); }
+
 // Byte masks of a 16-byte vector, as four dwords: entry k of the first half has ones in bytes k..15
 // (k = 0..15), entry k of the second half in bytes 0..k-1 (k = 0..16).
 struct ByteMasks {
@@ -545,11 +548,12 @@ __global__ __launch_bounds__(64 * WPB) void hccs_rows_staged_kernel(const int8_t
     const int row_begin = (int)__umul24((uint32_t)row_in_block, (uint32_t)n), row_last = row_begin + n - 1;   // bytes of the block's range
     const int first = row_begin >> 4, last = row_last >> 4;
     const u32x4 from = keep[sub == 0 ? (row_begin & 15) : 0];
+    const int row_end = row_exists ? row_last + 1 : 0;
     uint32_t d[V][4];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         const int c = first + v * G + sub;
-        const int bytes = !row_exists || c > last ? 0 : (c == last ? (row_last & 15) + 1 : 16);
+        const int bytes = clamp_bytes(row_end - 16 * c);   // of the row in this vector, counted from the vector's first byte
         u32x4 mine = keep[16 + bytes];
         if (v == 0) mine &= from;
         const u32x4 t = stage_in[c];
