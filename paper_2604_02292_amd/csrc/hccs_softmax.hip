@@ -742,7 +742,8 @@ static hipError_t launch_mode(const int8_t *x, uint8_t *p, int64_t Bt, int H, in
         // 300 20.5 / 22.2, 380 21.9 / 28.5, 450 24.5 / 30.8, 497 27.2 / 33.6, 785 42.2 / 43.2, 900 45.7 / 48.5,
         // 1000 49.0 / 53.8; slower or equal in the gaps: 120 11.6 / 9.6, 250 19.9 / 16.4, 520 37.7 / 33.4,
         // 700 39.9 / 38.9).  The time of a lane layout hardly depends on n, so each serves the lengths that fill it.
-        if (aligned && Lq >= 16) {
+        // (row numbers of the last block's empty waves stay below 2^31: the divisions by Lq and H hold up to there)
+        if (aligned && Lq >= 16 && Bt * H * Lq < 0x7fffff00ll) {
             if (Lk > 64 && Lk <= 113) return launch_staged<4, 2, 2, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
             if (Lk > 128 && Lk <= 241) return launch_staged<8, 2, 2, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
             if (Lk > 256 && Lk <= 497) return launch_staged<16, 2, 4, MODE>(x, p, Bt, H, Lq, Lk, tab, st);
