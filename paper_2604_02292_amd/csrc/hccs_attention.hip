@@ -3,9 +3,10 @@
 // path of Sec. III-B, n = L), O = P.V (int8 MFMA).  Logits and probabilities stay
 // in registers; K and V are staged once per (batch, head) in LDS.
 //
-// Two kernels: the first takes every table (probabilities up to 255); the second, further down,
-// brings K and V straight into LDS and feeds P to the matrix unit unsigned, for tables whose
-// probabilities provably stay below 128.  What follows describes the first.
+// Two kernels: the first takes every table (probabilities up to 255) and blocks of whole 64s of
+// keys; the second, further down, brings K and V straight into LDS and feeds P to the matrix unit
+// unsigned, for tables whose probabilities provably stay below 128, and also takes blocks of any
+// other length up to 512.  What follows describes the first.
 //
 // The matrix unit is used for the two dense contractions only.  Both use
 // v_mfma_i32_16x16x64_i8, whose operand layout on a 64-lane wave is
@@ -259,24 +260,29 @@ __device__ __forceinline__ void load_to_lds16(const void *global_lane, void *lds
 
 // One instruction moves 16 rows (1 KiB): lane l brings chunk (l & 3) ^ f(row) of row 16u + l/4 to
 // position l & 3 of that row.  The waves of a block share the NT instructions of an item evenly.
+// `last` is the last row the item has.  No load leaves the item: the LDS rows of K behind it receive that row again, so
+// their logits repeat the last key's; the rows of V behind it are zero, so those keys add nothing to the output.
 template <int NT, int WAVES>
-__device__ __forceinline__ void k_rows_to_lds(const int8_t *k_item, uint8_t *k_lds, int wave, int lane)
+__device__ __forceinline__ void k_rows_to_lds(const int8_t *k_item, uint8_t *k_lds, int wave, int lane, int last)
 {
 #pragma unroll
     for (int i = 0; i < NT / WAVES; ++i) {
         const int u = wave + i * WAVES;
         const int row = 16 * u + (lane >> 2), pos = lane & 3;
-        load_to_lds16(k_item + row * 64 + 16 * (pos ^ ((row >> 2) & 3)), k_lds + u * 1024);
+        load_to_lds16(k_item + min(row, last) * 64 + 16 * (pos ^ ((row >> 2) & 3)), k_lds + u * 1024);
     }
 }
 template <int NT, int WAVES>
-__device__ __forceinline__ void v_rows_to_lds(const int8_t *v_item, uint8_t *v_lds, int wave, int lane)
+__device__ __forceinline__ void v_rows_to_lds(const int8_t *v_item, uint8_t *v_lds, int wave, int lane, int last)
 {
 #pragma unroll
     for (int i = 0; i < NT / WAVES; ++i) {
         const int u = wave + i * WAVES;
         const int key = 16 * u + (lane >> 2), pos = lane & 3;
-        load_to_lds16(v_item + key * 64 + 16 * (pos ^ (((key >> 4) + (key >> 2)) & 3)), v_lds + u * 1024);
+        if (key <= last)
+            load_to_lds16(v_item + key * 64 + 16 * (pos ^ (((key >> 4) + (key >> 2)) & 3)), v_lds + u * 1024);
+        else   // the 16 bytes the load would have filled
+            *(v4i *)(v_lds + u * 1024 + lane * 16) = (v4i){0, 0, 0, 0};
     }
 }
 
@@ -316,6 +322,8 @@ __device__ __forceinline__ void lds_barrier()
 }
 // every vector-memory operation of this wave has completed: vmcnt(0), other counters untouched
 __device__ __forceinline__ void wait_vector_memory() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// as above, and every LDS operation too: vmcnt(0) lgkmcnt(0)
+__device__ __forceinline__ void wait_memory() { __builtin_amdgcn_s_waitcnt(0x0070); }
 
 struct HeadRule {
     int B, S, D, mult, shift, lim_lo, lim_hi;
@@ -329,11 +337,13 @@ __device__ __forceinline__ HeadRule head_rule(const HeadTable &table, const Requ
 // First half of a query tile: A^T tiles = K_tile . Q^T rescaled to 16-bit pairs tile by tile (the K
 // operand of a tile is read from LDS one tile ahead of the contraction that uses it), row maximum,
 // window clamp, sum and scores (Eq. (2), (3), (5)).  Leaves the scores in xp and 2*rho (Eq. (8)).
-template <int NT, int RQ>
+// PART: the item has L < 16*NT keys and the key slots behind them repeat the last key (see k_rows_to_lds).  Copies
+// of a key leave the maximum as it is; the sum counts the last key's clamped logit 16*NT - L times too often, which
+// the lane that holds the very last slot (always a copy) takes off again; the scores of the copies meet zero rows of V.
+template <int NT, int RQ, bool PART>
 __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, const v4i &qop, const HeadRule &r,
-                                               short2_t (&xp)[NT][2], uint32_t &rho2)
+                                               short2_t (&xp)[NT][2], uint32_t &rho2, int L, int g)
 {
-    constexpr int L = NT * 16;
     const int round_c = 1 << (r.shift - 1);
     short2_t mx2 = {-32768, -32768};
     auto k_operand = [&](int t) { return *(const v4i *)(k_lds + t * 1024 + k_off); };
@@ -368,6 +378,8 @@ __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, 
             xp[t][1] = __builtin_elementwise_min(xp[t][1], hi2);
         }
     }
+    // slot 16*NT - 1 (the lanes g = 3 hold it): with PART a copy of the last key
+    const int last_slot = clamp_i32((int)xp[NT - 1][1].y, (int)lo, 127);
     short2_t sum2 = {0, 0};
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -379,6 +391,7 @@ __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, 
         }
     }
     int sx = (int)sum2.x + (int)sum2.y;
+    if constexpr (PART) sx -= g == 3 ? (16 * NT - L) * last_slot : 0;
     sx += xor16(sx);
     sx += xor32(sx);
     const uint32_t Z = (uint32_t)(L * r.B - r.S * (L * m - sx));
@@ -416,23 +429,26 @@ __device__ __forceinline__ void weighted_values_of_tile(const uint8_t *v_lds, co
 }
 
 // rows of query tile rt of an item
-template <int NT>
-__device__ __forceinline__ void store_tile(int32_t *o, int item, int rt, int lane, const v4i (&oacc)[4])
+__device__ __forceinline__ void store_tile(int32_t *o, int item, int L, int rt, int lane, const v4i (&oacc)[4])
 {
-    store_rows_whole_lines<4>(o + ((size_t)item * (NT * 16) + (size_t)rt * 16) * 64, 64, 16, lane, oacc);
+    store_rows_whole_lines<4>(o + ((size_t)item * L + (size_t)rt * 16) * 64, 64, min(16, L - 16 * rt), lane, oacc);
 }
 
 // One block per (batch, head) item, NT / WAVES query tiles per wave.  The first contraction starts
 // when K has landed; V is asked for then and lands during it.  (Measured against blocks that take a
 // half or a quarter of an item's queries, and against blocks that stay and take item after item
 // with the next item's loads in flight: at 768 items this form was the fastest.)
-template <int NT, int RQ, int WAVES>
+// PART: items of Lrows < 16*NT rows (else Lrows = 16*NT).  The rows of Q and K an item lacks are loaded as copies of
+// its last one and those of V are zero; their query rows are not stored, and a wave whose tile lies behind the
+// item's rows only keeps the barriers.
+template <int NT, int RQ, int WAVES, bool PART>
 __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention_direct_kernel(
     const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v, int32_t *__restrict__ o,
-    int H, HeadTable table, RequantTable requant)
+    int H, int Lrows, HeadTable table, RequantTable requant)
 {
-    constexpr int KV = NT * 16 * 64;       // bytes of K (or V) of one item
+    constexpr int KV = NT * 16 * 64;       // bytes of K (or V) of one item in LDS
     constexpr int kTiles = NT / WAVES;     // query tiles per wave
+    const int L = PART ? Lrows : NT * 16;
     static_assert(NT % WAVES == 0, "equal shares of tiles and of loads");
     __shared__ __attribute__((aligned(16))) uint8_t k_lds[KV];
     __shared__ __attribute__((aligned(16))) uint8_t v_lds[KV];
@@ -440,14 +456,14 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
     const int item = (int)blockIdx.x;
-    const size_t base = (size_t)item * KV;
+    const size_t base = (size_t)item * (size_t)(L * 64);
 
-    k_rows_to_lds<NT, WAVES>(k + base, k_lds, wave, lane);
+    k_rows_to_lds<NT, WAVES>(k + base, k_lds, wave, lane, L - 1);
     // the Q operands of the wave's tiles: query 16*rt + qi, bytes 16g .. 16g+15
     v4i qops[kTiles];
 #pragma unroll
     for (int i = 0; i < kTiles; ++i)
-        qops[i] = *(const v4i *)(q + base + ((wave + i * WAVES) * 16 + qi) * 64 + 16 * g);
+        qops[i] = *(const v4i *)(q + base + min((wave + i * WAVES) * 16 + qi, L - 1) * 64 + 16 * g);
     const HeadRule rule = head_rule(table, requant, item % H);
     const OperandOffsets off = operand_offsets(lane);
 
@@ -457,35 +473,42 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
 #pragma unroll
     for (int i = 0; i < kTiles; ++i) asm volatile("" : "+v"(qops[i]));
     lds_barrier();   // K is in
-    v_rows_to_lds<NT, WAVES>(v + base, v_lds, wave, lane);
+    v_rows_to_lds<NT, WAVES>(v + base, v_lds, wave, lane, L - 1);
 
 #pragma unroll
     for (int i = 0; i < kTiles; ++i) {
+        const int rt = wave + i * WAVES;
+        const bool has_rows = !PART || 16 * rt < L;   // wave-uniform
         short2_t xp[NT][2];
-        uint32_t rho2;
-        scores_of_tile<NT, RQ>(k_lds, off.k, qops[i], rule, xp, rho2);
+        uint32_t rho2 = 0;
+        if (has_rows) scores_of_tile<NT, RQ, PART>(k_lds, off.k, qops[i], rule, xp, rho2, L, g);
         if (i == 0) {   // the wave's first tile: V must have landed by now
-            wait_vector_memory();
+            if constexpr (PART)
+                wait_memory();   // and the zero rows this wave wrote
+            else
+                wait_vector_memory();
             lds_barrier();
         }
-        v4i oacc[4];
-        weighted_values_of_tile<NT>(v_lds, off.v, xp, rho2, oacc);
-        store_tile<NT>(o, item, wave + i * WAVES, lane, oacc);
+        if (has_rows) {
+            v4i oacc[4];
+            weighted_values_of_tile<NT>(v_lds, off.v, xp, rho2, oacc);
+            store_tile(o, item, L, rt, lane, oacc);
+        }
     }
 }
 
-template <int NT>
+template <int NT, bool PART>
 static hipError_t launch_direct_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
-                                   const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
+                                   int L, const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
 {
     // as many waves as divide the query tiles evenly, at most 8
     constexpr int WAVES = NT % 8 == 0 ? 8 : (NT % 6 == 0 ? 6 : (NT % 5 == 0 ? 5 : 4));
     const dim3 grid((uint32_t)items), block(64 * WAVES);
     if (kind == kRescaleHigh16)
-        return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
+        return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES, PART>, grid, block, st, q, k, v, o, H, L, tab, rq);
     if (kind == kRescaleShift)
-        return launch(hccs_attention_direct_kernel<NT, kRescaleShift, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
-    return launch(hccs_attention_direct_kernel<NT, kRescalePreclamp, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
+        return launch(hccs_attention_direct_kernel<NT, kRescaleShift, WAVES, PART>, grid, block, st, q, k, v, o, H, L, tab, rq);
+    return launch(hccs_attention_direct_kernel<NT, kRescalePreclamp, WAVES, PART>, grid, block, st, q, k, v, o, H, L, tab, rq);
 }
 
 template <int NT>
@@ -509,15 +532,28 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
     const int64_t blocks = Bt * H;
+    if (L % 64 != 0) {   // the caller has checked that the probabilities fit: the kernel above takes whole 64s only
+        switch ((L + 63) / 64) {
+            case 1: return launch_direct_nt<4, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 2: return launch_direct_nt<8, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 3: return launch_direct_nt<12, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 4: return launch_direct_nt<16, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 5: return launch_direct_nt<20, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 6: return launch_direct_nt<24, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 7:
+            case 8: return launch_direct_nt<32, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            default: return hipErrorInvalidValue;
+        }
+    }
     if (probabilities_fit_signed(tab, H, L)) {
         switch (L / 16) {
-            case 4: return launch_direct_nt<4>(q, k, v, o, blocks, H, tab, rq, kind, st);
-            case 8: return launch_direct_nt<8>(q, k, v, o, blocks, H, tab, rq, kind, st);
-            case 12: return launch_direct_nt<12>(q, k, v, o, blocks, H, tab, rq, kind, st);
-            case 16: return launch_direct_nt<16>(q, k, v, o, blocks, H, tab, rq, kind, st);
-            case 20: return launch_direct_nt<20>(q, k, v, o, blocks, H, tab, rq, kind, st);
-            case 24: return launch_direct_nt<24>(q, k, v, o, blocks, H, tab, rq, kind, st);
-            case 32: return launch_direct_nt<32>(q, k, v, o, blocks, H, tab, rq, kind, st);
+            case 4: return launch_direct_nt<4, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 8: return launch_direct_nt<8, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 12: return launch_direct_nt<12, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 16: return launch_direct_nt<16, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 20: return launch_direct_nt<20, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 24: return launch_direct_nt<24, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+            case 32: return launch_direct_nt<32, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
             default: break;   // 448 keys (7 waves of 4 tiles) measured slower than the kernel above: 31.4 against 29.1 us
         }
     }

@@ -683,6 +683,50 @@ def test_attention_largest_probability_at_the_signed_limit(oracle, L, params, p_
     check_attention(q, k, v, table, rq, 0, oracle, f"largest P = {p_top}, {L} keys")
 
 
+SQUARE_LENGTHS = [1, 2, 15, 16, 17, 48, 63, 65, 100, 127, 129, 130, 191, 193, 197, 200, 208, 255, 257, 300, 319, 321,
+                  383, 385, 400, 447, 449, 500, 511]
+
+
+@pytest.mark.parametrize("L", SQUARE_LENGTHS)
+def test_attention_square_blocks_of_any_length(oracle, L):
+    """Square blocks whose length is no multiple of 64 (a vision encoder's 197 tokens among them): under the strict
+    band (P <= 127 proven) the resident kernel takes them with its last key tiles partly or wholly absent, under
+    a table that allows P > 127 the streaming kernel does.  Full-range inputs, every rescale form, and an output
+    buffer with guard values before and behind it."""
+    g = np.random.default_rng(1000 + L)
+    Bt, H, d = 3, 3, 64
+    q, k, v = (g.integers(-128, 128, size=(Bt, H, L, d), dtype=np.int8) for _ in range(3))
+    k[0, 0, L - 1] = 127                                  # the last key matters: large logits on it
+    q[0, 0, : min(L, 4)] = 127
+    strict = synth.head_params(H, L, 1, seed=L)
+    wide = _random_table(g, H, L, 0)
+    wide[0] = (min((255 << 15) // L, 32640), 127, 127)
+    assert binding.validate_params(wide, L, 0) == (0, -1)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    for table, band in ((strict, 1), (wide, 0)):
+        for rq in ([[100 + h, 16] for h in range(H)], [[900 + h, 20] for h in range(H)],
+                   [[4096 - h, 24 - (h % 3)] for h in range(H)]):
+            rq = np.array(rq, np.int32)
+            print(f"square block L={L} band={band} rq={rq[0].tolist()}", flush=True)
+            want, rc = oracle.attention(q, k, v, table, rq, band, threads=THREADS)
+            assert rc == 0
+            buf = torch.full((q.size + 512,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+            out = buf[256:256 + q.size].view(q.shape)
+            binding.attention_i8(dev(q), dev(k), dev(v), table, rq, band, out=out)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want), f"L={L} band={band} rq={rq[0].tolist()}"
+            assert bool((buf[:256] == 0x5A5A5A5A).all()) and bool((buf[256 + q.size:] == 0x5A5A5A5A).all())
+
+
+def test_attention_vision_encoder_length_full_size(oracle):
+    """[64, 12, 197, 197] with head size 64: as many items as the benchmark's fused shape, 197 tokens each."""
+    g = np.random.default_rng(197)
+    Bt, H, L, d = 64, 12, 197, 64
+    q, k, v = (g.integers(-64, 64, size=(Bt, H, L, d), dtype=np.int8) for _ in range(3))
+    check_attention(q, k, v, synth.head_params(H, L, 1, seed=197), synth.requant_params(H, seed=197), 1, oracle,
+                    "197 tokens, full size")
+
+
 def test_attention_full_size(oracle):
     w = synth.make_workload("fused_attention")
     check_attention(w["q"], w["k"], w["v"], w["table"], w["requant"], w["band"], oracle, "full")
@@ -771,9 +815,12 @@ def attention_sweep(oracle, seed, cases):
     for case in range(cases):
         Bt, H = int(g.integers(1, 3)), int(g.integers(1, 5))
         d = 64 if g.integers(3) else 128
-        pick = int(g.integers(5))
+        pick = int(g.integers(6))
         if pick == 0:                                    # resident: square, multiple of 64, d = 64
             Lq = Lk = 64 * int(g.integers(1, 9))
+            d = 64
+        elif pick == 5:                                  # square, any length up to 512, d = 64
+            Lq = Lk = int(g.integers(1, 513))
             d = 64
         elif pick == 1:
             Lq, Lk = int(g.integers(1, 200)), int(g.integers(1, 700))
