@@ -325,6 +325,17 @@ __device__ __forceinline__ void wait_vector_memory() { __builtin_amdgcn_s_waitcn
 // as above, and every LDS operation too: vmcnt(0) lgkmcnt(0)
 __device__ __forceinline__ void wait_memory() { __builtin_amdgcn_s_waitcnt(0x0070); }
 
+// The launcher lays a block out for the next multiple of 64 keys (beyond 384: for 512), so at most this many of the
+// last key tiles can be wholly absent.
+template <int NT>
+constexpr int kAbsentTiles = NT == 32 ? 7 : 3;
+// whether key tile t holds a key of an item of L keys (the same for the whole wave)
+template <int NT, bool PART>
+__device__ __forceinline__ bool has_keys(int t, int L)
+{
+    return !PART || t < NT - kAbsentTiles<NT> || 16 * t < L;
+}
+
 struct HeadRule {
     int B, S, D, mult, shift, lim_lo, lim_hi;
 };
@@ -337,9 +348,10 @@ __device__ __forceinline__ HeadRule head_rule(const HeadTable &table, const Requ
 // First half of a query tile: A^T tiles = K_tile . Q^T rescaled to 16-bit pairs tile by tile (the K
 // operand of a tile is read from LDS one tile ahead of the contraction that uses it), row maximum,
 // window clamp, sum and scores (Eq. (2), (3), (5)).  Leaves the scores in xp and 2*rho (Eq. (8)).
-// PART: the item has L < 16*NT keys and the key slots behind them repeat the last key (see k_rows_to_lds).  Copies
-// of a key leave the maximum as it is; the sum counts the last key's clamped logit 16*NT - L times too often, which
-// the lane that holds the very last slot (always a copy) takes off again; the scores of the copies meet zero rows of V.
+// PART: the item has L < 16*NT keys.  Key tiles wholly behind them are left out (wave-uniform branches) and get the
+// score 0.  In the tile of the last key the slots behind it repeat that key (see k_rows_to_lds): copies of a key
+// leave the maximum as it is; the sum counts the last key's clamped logit once per copy too often, which the lanes
+// that hold the tile's last slot take off again; the scores of the copies meet zero rows of V.
 template <int NT, int RQ, bool PART>
 __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, const v4i &qop, const HeadRule &r,
                                                short2_t (&xp)[NT][2], uint32_t &rho2, int L, int g)
@@ -354,8 +366,10 @@ __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, 
         v4i acc_next = acc;
         if (t + 1 < NT) acc_next = __builtin_amdgcn_mfma_i32_16x16x64_i8(knext, qop, (v4i){0, 0, 0, 0}, 0, 0, 0);
         if (t + 2 < NT) knext = k_operand(t + 2);
-        rescale_tile<RQ>(acc, r.mult, r.shift, round_c, r.lim_lo, r.lim_hi, xp[t][0], xp[t][1]);
-        mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(xp[t][0], xp[t][1]));
+        if (has_keys<NT, PART>(t, L)) {
+            rescale_tile<RQ>(acc, r.mult, r.shift, round_c, r.lim_lo, r.lim_hi, xp[t][0], xp[t][1]);
+            mx2 = __builtin_elementwise_max(mx2, __builtin_elementwise_max(xp[t][0], xp[t][1]));
+        }
         acc = acc_next;
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -374,24 +388,30 @@ __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, 
     if (__builtin_amdgcn_ballot_w64(mx > 127) != 0) {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            xp[t][0] = __builtin_elementwise_min(xp[t][0], hi2);
-            xp[t][1] = __builtin_elementwise_min(xp[t][1], hi2);
+            if (has_keys<NT, PART>(t, L)) {
+                xp[t][0] = __builtin_elementwise_min(xp[t][0], hi2);
+                xp[t][1] = __builtin_elementwise_min(xp[t][1], hi2);
+            }
         }
     }
-    // slot 16*NT - 1 (the lanes g = 3 hold it): with PART a copy of the last key
-    const int last_slot = clamp_i32((int)xp[NT - 1][1].y, (int)lo, 127);
+    int last_slot = 0;   // the last slot of the tile that holds the last key (the lanes g = 3 hold it)
     short2_t sum2 = {0, 0};
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
+        if (has_keys<NT, PART>(t, L)) {
+            if (PART && t >= NT - kAbsentTiles<NT> - 1 && 16 * t + 16 >= L) last_slot = (int)xp[t][1].y;   // the last key's tile
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const short2_t xc = __builtin_elementwise_max(xp[t][h], lo2);   // the window's lower edge, >= -128
-            sum2 += xc;                            // at most 64 values of magnitude <= 128 per half
-            xp[t][h] = __builtin_bit_cast(short2_t, __builtin_bit_cast(ushort2_t, xc) * s2 + c2);
+            for (int h = 0; h < 2; ++h) {
+                const short2_t xc = __builtin_elementwise_max(xp[t][h], lo2);   // the window's lower edge, >= -128
+                sum2 += xc;                            // at most 64 values of magnitude <= 128 per half
+                xp[t][h] = __builtin_bit_cast(short2_t, __builtin_bit_cast(ushort2_t, xc) * s2 + c2);
+            }
+        } else {
+            xp[t][0] = xp[t][1] = (short2_t){0, 0};
         }
     }
     int sx = (int)sum2.x + (int)sum2.y;
-    if constexpr (PART) sx -= g == 3 ? (16 * NT - L) * last_slot : 0;
+    if constexpr (PART) sx -= g == 3 ? (((L + 15) & ~15) - L) * clamp_i32(last_slot, (int)lo, 127) : 0;
     sx += xor16(sx);
     sx += xor32(sx);
     const uint32_t Z = (uint32_t)(L * r.B - r.S * (L * m - sx));
@@ -399,14 +419,15 @@ __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, 
 }
 
 // Second half: O^T tile = V^T . P^T.  Lane (g, qi) ends with columns 16*n16 + 4g .. +3 of query qi.
-template <int NT>
+template <int NT, bool PART>
 __device__ __forceinline__ void weighted_values_of_tile(const uint8_t *v_lds, const int (&v_off)[4],
-                                                        const short2_t (&xp)[NT][2], uint32_t rho2, v4i (&oacc)[4])
+                                                        const short2_t (&xp)[NT][2], uint32_t rho2, v4i (&oacc)[4], int L)
 {
 #pragma unroll
     for (int n16 = 0; n16 < 4; ++n16) oacc[n16] = (v4i){0, 0, 0, 0};
 #pragma unroll
     for (int T = 0; T < NT / 4; ++T) {
+        if (PART && T > 0 && 64 * T >= L) continue;   // 64 keys that the item lacks
         v4i vop[4];
 #pragma unroll
         for (int n16 = 0; n16 < 4; ++n16) {
@@ -419,7 +440,10 @@ __device__ __forceinline__ void weighted_values_of_tile(const uint8_t *v_lds, co
         for (int tt = 0; tt < 4; ++tt) {
             const uint32_t s01 = __builtin_bit_cast(uint32_t, xp[T * 4 + tt][0]);
             const uint32_t s23 = __builtin_bit_cast(uint32_t, xp[T * 4 + tt][1]);
-            pop[tt] = (int)probabilities_plain(s01, s23, rho2);
+            if (!has_keys<NT, PART>(T * 4 + tt, L))
+                pop[tt] = 0;
+            else
+                pop[tt] = (int)probabilities_plain(s01, s23, rho2);
         }
 #pragma unroll
         for (int n16 = 0; n16 < 4; ++n16)
@@ -491,7 +515,7 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
         }
         if (has_rows) {
             v4i oacc[4];
-            weighted_values_of_tile<NT>(v_lds, off.v, xp, rho2, oacc);
+            weighted_values_of_tile<NT, PART>(v_lds, off.v, xp, rho2, oacc, L);
             store_tile(o, item, L, rt, lane, oacc);
         }
     }

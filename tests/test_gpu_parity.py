@@ -718,6 +718,28 @@ def test_attention_square_blocks_of_any_length(oracle, L):
             assert bool((buf[:256] == 0x5A5A5A5A).all()) and bool((buf[256 + q.size:] == 0x5A5A5A5A).all())
 
 
+def test_attention_every_square_length_up_to_512(oracle):
+    """Every length from 1 to 512 once, with tables that prove P <= 127 from three keys on (so all but the first two
+    take the resident kernel), rows whose maximum is the last key, and inputs whose logits reach both saturations."""
+    g = np.random.default_rng(512)
+    H, d = 2, 64
+    for L in range(1, 513):
+        q, k, v = (g.integers(-128, 128, size=(1, H, L, d), dtype=np.int8) for _ in range(3))
+        if L % 3 == 0:
+            k[0, :, L - 1] = np.where(q[0, :, L // 2] >= 0, 127, -128)   # the last key is the largest for that query
+        table = np.array([[300, 2, 20], [280, 1, 20]] if L < 7 else [[100, 2, 20], [60, 1, 20]] if L <= 327
+                         else [[60, 1, 20], [50, 0, 9]], np.int32)
+        assert binding.validate_params(table, L, 1) == (0, -1)
+        rq = np.array([[3 + L % 50, 12], [900, 20]], np.int32)
+        want, rc = oracle.attention(q, k, v, table, rq, 1, threads=THREADS)
+        assert rc == 0
+        got = binding.attention_i8(torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(),
+                                   table, rq, 1)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), want), f"L={L}"
+    print("512 lengths equal", flush=True)
+
+
 def test_attention_vision_encoder_length_full_size(oracle):
     """[64, 12, 197, 197] with head size 64: as many items as the benchmark's fused shape, 197 tokens each."""
     g = np.random.default_rng(197)
