@@ -371,8 +371,8 @@ def main():
             torch.cuda.empty_cache()
 
         # ---- fused int8 attention block (resident kernels): the 256-token shape, and a vision encoder's 197 tokens
-        for label, shape, kernel in (("fused_attention", None, "hccs_attention_direct_kernel<16,0,8,false>"),
-                                     ("fused_attention_197", (64, 12, 197, 64), "hccs_attention_direct_kernel<16,0,8,true>")):
+        for label, shape, kernel in (("fused_attention", None, "hccs_attention_direct_kernel<16,0,8,false,false>"),
+                                     ("fused_attention_197", (64, 12, 197, 64), "hccs_attention_direct_kernel<16,0,8,true,false>")):
             a = synth.make_workload("fused_attention", shape=shape)
             sets = 18   # 1.5 GB of inputs and outputs at 256 tokens: six times the memory-side cache
             q, k, v = ([torch.from_numpy(a[t]).to(dev).clone() for _ in range(sets)] for t in ("q", "k", "v"))

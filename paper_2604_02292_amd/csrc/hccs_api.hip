@@ -136,10 +136,8 @@ int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t 
     hccs::RequantTable rq;
     for (int h = 0; h < HCCS_MAX_HEADS; ++h)
         rq.e[h] = h < H ? make_int4(requant_host[h].mult, requant_host[h].shift, 0, 0) : make_int4(1, 1, 0, 0);
-    // square blocks whose rows fit the register file go to the resident kernels: whole 64s of rows, and any other
-    // count when every probability fits a signed byte; everything else streams
-    const bool resident = d == 64 && Lq == Lk && Lk <= 512 &&
-                          (Lk % 64 == 0 || hccs::probabilities_fit_signed(tab, H, Lk));
+    // square blocks whose rows fit the register file go to the resident kernels, everything else streams
+    const bool resident = d == 64 && Lq == Lk && Lk <= 512;
     const hipError_t e =
         resident ? hccs::launch_attention(q_dev, k_dev, v_dev, o_dev, B, H, Lk, d, tab, rq, (hipStream_t)hip_stream)
                  : hccs::launch_attention_stream(q_dev, k_dev, v_dev, o_dev, B, H, Lq, Lk, d, tab, rq,

@@ -3,10 +3,9 @@
 // path of Sec. III-B, n = L), O = P.V (int8 MFMA).  Logits and probabilities stay
 // in registers; K and V are staged once per (batch, head) in LDS.
 //
-// Two kernels: the first takes every table (probabilities up to 255) and blocks of whole 64s of
-// keys; the second, further down, brings K and V straight into LDS and feeds P to the matrix unit
-// unsigned, for tables whose probabilities provably stay below 128, and also takes blocks of any
-// other length up to 512.  What follows describes the first.
+// Two kernels.  The first is launched for 448 keys only, where it measured faster.  The second,
+// further down, brings K and V straight into LDS, feeds P to the matrix unit as it is and takes
+// every other length up to 512, whole 64s of keys or not.  What follows describes the first.
 //
 // The matrix unit is used for the two dense contractions only.  Both use
 // v_mfma_i32_16x16x64_i8, whose operand layout on a 64-lane wave is
@@ -230,12 +229,15 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 4 : 2)) void hccs_attention
 // The second contraction runs transposed (O^T tile = V^T . P^T) like in the streaming kernels, so a
 // lane ends with four consecutive columns of one query per accumulator.
 //
-// The matrix unit multiplies signed bytes and P is unsigned: this kernel is launched only when
-// the host can show P <= 127 for every row the table allows (true for every table of the band of
-// Eq. (11) at 256 keys and more), and P goes in as it is; other tables take the kernel above.
-// Measured against it, same tables, about 88 MB of traffic each: L = 64 16.8 against 17.0 us, 128 16.4
-// against 18.3, 192 19.9 against 21.1, 256 19.3 against 20.8, 320 27.3 against 27.2, 384 30.8 against
-// 34.6, 512 35.0 against 41.8.
+// The matrix unit multiplies signed bytes and P is unsigned.  P goes in as it is.  When the host
+// can show P <= 127 for every row the table allows (true for every table of the band of Eq. (11) at
+// 256 keys and more) that is all; otherwise (WIDE) a tile whose rows can reach 128 (a row's largest
+// probability is (B*rho) >> 15, known before the contraction) adds what the unit lost, see
+// weighted_values_of_tile.  Measured against the kernel above, tables that prove P <= 127, about 88 MB
+// of traffic each: L = 64 16.8 against 17.0 us, 128 16.4 against 18.3, 192 19.9 against 21.1, 256 19.3
+// against 20.8, 320 27.3 against 27.2, 384 30.8 against 34.6, 512 35.0 against 41.8; tables that do not,
+// rows that reach P > 127, 768 items: 64 4.9 against 5.6, 256 20.8 against 22.4, 384 37.6 against 39.8,
+// 512 57.3 against 63.0, and 448 (as 512 slots) 53.3 against 48.1, hence its place there.
 // ---------------------------------------------------------------------------
 typedef const __attribute__((address_space(1))) void *global_void_ptr;
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
@@ -354,7 +356,7 @@ __device__ __forceinline__ HeadRule head_rule(const HeadTable &table, const Requ
 // that hold the tile's last slot take off again; the scores of the copies meet zero rows of V.
 template <int NT, int RQ, bool PART>
 __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, const v4i &qop, const HeadRule &r,
-                                               short2_t (&xp)[NT][2], uint32_t &rho2, int L, int g)
+                                               short2_t (&xp)[NT][2], uint32_t &rho2, uint32_t &p_top, int L, int g)
 {
     const int round_c = 1 << (r.shift - 1);
     short2_t mx2 = {-32768, -32768};
@@ -416,12 +418,17 @@ __device__ __forceinline__ void scores_of_tile(const uint8_t *k_lds, int k_off, 
     sx += xor32(sx);
     const uint32_t Z = (uint32_t)(L * r.B - r.S * (L * m - sx));
     rho2 = reciprocal_u8(Z) * 2u;                 // <= 65280: fits 16 bits
+    p_top = ((uint32_t)r.B * rho2) >> 16;         // the row's largest probability: its maximum has the score B
 }
 
 // Second half: O^T tile = V^T . P^T.  Lane (g, qi) ends with columns 16*n16 + 4g .. +3 of query qi.
-template <int NT, bool PART>
+// The matrix unit multiplies signed bytes.  top (wave-uniform): some query of the tile has a probability above 127 (a
+// row has at most one, its sum being at most 255), which the unit reads as P - 256.  Where a set of 64 keys holds
+// such a probability for any query, the top bits then go in again as 64s, four times, into the same accumulators.
+template <int NT, bool PART, bool WIDE>
 __device__ __forceinline__ void weighted_values_of_tile(const uint8_t *v_lds, const int (&v_off)[4],
-                                                        const short2_t (&xp)[NT][2], uint32_t rho2, v4i (&oacc)[4], int L)
+                                                        const short2_t (&xp)[NT][2], uint32_t rho2, v4i (&oacc)[4], int L,
+                                                        bool top)
 {
 #pragma unroll
     for (int n16 = 0; n16 < 4; ++n16) oacc[n16] = (v4i){0, 0, 0, 0};
@@ -448,6 +455,18 @@ __device__ __forceinline__ void weighted_values_of_tile(const uint8_t *v_lds, co
 #pragma unroll
         for (int n16 = 0; n16 < 4; ++n16)
             oacc[n16] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop[n16], pop, oacc[n16], 0, 0, 0);
+        if constexpr (WIDE) {
+            if (top && __builtin_amdgcn_ballot_w64(((pop[0] | pop[1] | pop[2] | pop[3]) & 0x80808080) != 0) != 0) {
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(((uint32_t)pop[tt] & 0x80808080u) >> 1);
+#pragma unroll
+                for (int rep = 0; rep < 4; ++rep) {
+#pragma unroll
+                    for (int n16 = 0; n16 < 4; ++n16)
+                        oacc[n16] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop[n16], pop, oacc[n16], 0, 0, 0);
+                }
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -465,7 +484,8 @@ __device__ __forceinline__ void store_tile(int32_t *o, int item, int L, int rt, 
 // PART: items of Lrows < 16*NT rows (else Lrows = 16*NT).  The rows of Q and K an item lacks are loaded as copies of
 // its last one and those of V are zero; their query rows are not stored, and a wave whose tile lies behind the
 // item's rows only keeps the barriers.
-template <int NT, int RQ, int WAVES, bool PART>
+// WIDE: the table does not prove P <= 127; a tile then looks at its rows' largest probabilities.
+template <int NT, int RQ, int WAVES, bool PART, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention_direct_kernel(
     const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v, int32_t *__restrict__ o,
     int H, int Lrows, HeadTable table, RequantTable requant)
@@ -504,8 +524,8 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
         const int rt = wave + i * WAVES;
         const bool has_rows = !PART || 16 * rt < L;   // wave-uniform
         short2_t xp[NT][2];
-        uint32_t rho2 = 0;
-        if (has_rows) scores_of_tile<NT, RQ, PART>(k_lds, off.k, qops[i], rule, xp, rho2, L, g);
+        uint32_t rho2 = 0, p_top = 0;
+        if (has_rows) scores_of_tile<NT, RQ, PART>(k_lds, off.k, qops[i], rule, xp, rho2, p_top, L, g);
         if (i == 0) {   // the wave's first tile: V must have landed by now
             if constexpr (PART)
                 wait_memory();   // and the zero rows this wave wrote
@@ -515,24 +535,33 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
         }
         if (has_rows) {
             v4i oacc[4];
-            weighted_values_of_tile<NT, PART>(v_lds, off.v, xp, rho2, oacc, L);
+            const bool top = WIDE && __builtin_amdgcn_ballot_w64(p_top > 127u) != 0;
+            weighted_values_of_tile<NT, PART, WIDE>(v_lds, off.v, xp, rho2, oacc, L, top);
             store_tile(o, item, L, rt, lane, oacc);
         }
     }
 }
 
+template <int NT, bool PART, bool WIDE>
+static hipError_t launch_direct_wide(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
+                                     int L, const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
+{
+    // as many waves as divide the query tiles evenly, at most 8
+    constexpr int WAVES = NT % 8 == 0 ? 8 : (NT % 7 == 0 ? 7 : (NT % 6 == 0 ? 6 : (NT % 5 == 0 ? 5 : 4)));
+    const dim3 grid((uint32_t)items), block(64 * WAVES);
+    if (kind == kRescaleHigh16)
+        return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, L, tab, rq);
+    if (kind == kRescaleShift)
+        return launch(hccs_attention_direct_kernel<NT, kRescaleShift, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, L, tab, rq);
+    return launch(hccs_attention_direct_kernel<NT, kRescalePreclamp, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, L, tab, rq);
+}
 template <int NT, bool PART>
 static hipError_t launch_direct_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
                                    int L, const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
 {
-    // as many waves as divide the query tiles evenly, at most 8
-    constexpr int WAVES = NT % 8 == 0 ? 8 : (NT % 6 == 0 ? 6 : (NT % 5 == 0 ? 5 : 4));
-    const dim3 grid((uint32_t)items), block(64 * WAVES);
-    if (kind == kRescaleHigh16)
-        return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES, PART>, grid, block, st, q, k, v, o, H, L, tab, rq);
-    if (kind == kRescaleShift)
-        return launch(hccs_attention_direct_kernel<NT, kRescaleShift, WAVES, PART>, grid, block, st, q, k, v, o, H, L, tab, rq);
-    return launch(hccs_attention_direct_kernel<NT, kRescalePreclamp, WAVES, PART>, grid, block, st, q, k, v, o, H, L, tab, rq);
+    if (probabilities_fit_signed(tab, H, L))
+        return launch_direct_wide<NT, PART, false>(q, k, v, o, items, H, L, tab, rq, kind, st);
+    return launch_direct_wide<NT, PART, true>(q, k, v, o, items, H, L, tab, rq, kind, st);
 }
 
 template <int NT>
@@ -556,7 +585,7 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
     const int64_t blocks = Bt * H;
-    if (L % 64 != 0) {   // the caller has checked that the probabilities fit: the kernel above takes whole 64s only
+    if (L % 64 != 0) {   // the kernel above takes whole 64s only
         switch ((L + 63) / 64) {
             case 1: return launch_direct_nt<4, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
             case 2: return launch_direct_nt<8, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
@@ -564,12 +593,12 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
             case 4: return launch_direct_nt<16, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
             case 5: return launch_direct_nt<20, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
             case 6: return launch_direct_nt<24, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 7:
+            case 7: return launch_direct_nt<28, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
             case 8: return launch_direct_nt<32, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
             default: return hipErrorInvalidValue;
         }
     }
-    if (probabilities_fit_signed(tab, H, L)) {
+    {
         switch (L / 16) {
             case 4: return launch_direct_nt<4, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
             case 8: return launch_direct_nt<8, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);

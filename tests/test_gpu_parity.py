@@ -740,6 +740,31 @@ def test_attention_every_square_length_up_to_512(oracle):
     print("512 lengths equal", flush=True)
 
 
+@pytest.mark.parametrize("L", [16, 64, 65, 100, 128, 197, 200, 256, 300, 320, 384, 390, 447, 448, 449, 511, 512])
+def test_attention_square_lengths_with_probabilities_above_127(oracle, L):
+    """Resident lengths under tables that allow P > 127, with rows that reach it: one key far above the others,
+    which sit at the window's edge; in head 1 that key is the last one, whose logit the partial-length kernel repeats
+    in the slots behind it.  The matrix unit reads such a byte as P - 256 and the kernel makes up for it."""
+    g = np.random.default_rng(2000 + L)
+    Bt, H, d = 2, 2, 64
+    q = g.integers(20, 100, size=(Bt, H, L, d), dtype=np.int8)
+    k = g.integers(-1, 2, size=(Bt, H, L, d), dtype=np.int8)
+    v = g.integers(-128, 128, size=(Bt, H, L, d), dtype=np.int8)
+    k[:, 0, L // 3] = 127
+    k[:, 1, L - 1] = 127
+    q[0, 0, ::5] = g.integers(-3, 4, size=q[0, 0, ::5].shape, dtype=np.int8)   # rows without a dominant key in between
+    floor = -(-256 // L) + 1
+    table = np.array([[12700 + floor, 100, 127], [32 * 100 + floor, 32, 100]], np.int32)
+    assert binding.validate_params(table, L, 0) == (0, -1)
+    for rq in ([[40, 16], [3, 12]], [[900, 20], [4096, 24]]):
+        rq = np.array(rq, np.int32)
+        x, rc = oracle.requant_logits(q, k, rq)
+        assert rc == 0
+        p, rc = oracle.softmax(x, table, 0, threads=THREADS)
+        assert rc == 0 and p[:, 0].max() > 127 and p[:, 1, :, L - 1].max() > 127   # the case does reach beyond 127
+        check_attention(q, k, v, table, rq, 0, oracle, f"P above 127, L={L} rq={rq[0].tolist()}")
+
+
 def test_attention_vision_encoder_length_full_size(oracle):
     """[64, 12, 197, 197] with head size 64: as many items as the benchmark's fused shape, 197 tokens each."""
     g = np.random.default_rng(197)
