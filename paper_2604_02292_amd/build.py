@@ -5,6 +5,8 @@
 import os
 import subprocess
 import sys
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -15,9 +17,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvi
          "-Wall", "-Wextra", "-Wno-unused-parameter"]
 
 
-def build(verbose=False):
-    """Always compiles (the caller decides when)."""
-    cmd = ["hipcc"] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd))
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -28,6 +28,17 @@ def build(verbose=False):
         raise RuntimeError("hipcc failed")
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose=False):
+    """Always compiles (the caller decides when): one object per source, side by side, then the link."""
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+    with tempfile.TemporaryDirectory(prefix="hccs_build_") as tmp:
+        objects = [os.path.join(tmp, s.replace(".hip", ".o")) for s in SOURCES]
+        jobs = [["hipcc"] + compile_flags + ["-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objects)]
+        with ThreadPoolExecutor(max_workers=min(len(jobs), os.cpu_count() or 1, 8)) as pool:
+            list(pool.map(lambda c: _run(c, verbose), jobs))
+        _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden"] + objects + ["-o", LIB], verbose)
     return LIB
 
 

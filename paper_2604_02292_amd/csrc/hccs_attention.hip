@@ -585,7 +585,7 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
     const int64_t blocks = Bt * H;
-    if (L % 64 != 0) {   // the kernel above takes whole 64s only
+    if (L % 64 != 0) {
         switch ((L + 63) / 64) {
             case 1: return launch_direct_nt<4, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
             case 2: return launch_direct_nt<8, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
@@ -598,29 +598,18 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
             default: return hipErrorInvalidValue;
         }
     }
-    {
-        switch (L / 16) {
-            case 4: return launch_direct_nt<4, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 8: return launch_direct_nt<8, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 12: return launch_direct_nt<12, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 16: return launch_direct_nt<16, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 20: return launch_direct_nt<20, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 24: return launch_direct_nt<24, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 32: return launch_direct_nt<32, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            default: break;   // 448 keys (7 waves of 4 tiles) measured slower than the kernel above: 31.4 against 29.1 us
-        }
-    }
     switch (L / 16) {
-        case 4: return launch_nt<4>(q, k, v, o, blocks, H, tab, rq, kind, st);
-        case 8: return launch_nt<8>(q, k, v, o, blocks, H, tab, rq, kind, st);
-        case 12: return launch_nt<12>(q, k, v, o, blocks, H, tab, rq, kind, st);
-        case 16: return launch_nt<16>(q, k, v, o, blocks, H, tab, rq, kind, st);
-        case 20: return launch_nt<20>(q, k, v, o, blocks, H, tab, rq, kind, st);
-        case 24: return launch_nt<24>(q, k, v, o, blocks, H, tab, rq, kind, st);
-        case 28: return launch_nt<28>(q, k, v, o, blocks, H, tab, rq, kind, st);
-        case 32: return launch_nt<32>(q, k, v, o, blocks, H, tab, rq, kind, st);
-        default: return hipErrorInvalidValue;
+        case 4: return launch_direct_nt<4, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+        case 8: return launch_direct_nt<8, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+        case 12: return launch_direct_nt<12, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+        case 16: return launch_direct_nt<16, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+        case 20: return launch_direct_nt<20, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+        case 24: return launch_direct_nt<24, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+        case 32: return launch_direct_nt<32, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+        default: break;   // 448 keys (7 waves of 4 tiles) measured slower than the first kernel: 31.4 against 29.1 us
     }
+    if (L == 448) return launch_nt<28>(q, k, v, o, blocks, H, tab, rq, kind, st);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace hccs
