@@ -134,6 +134,22 @@ __device__ __forceinline__ uint32_t probabilities_plain(uint32_t s01, uint32_t s
     return __builtin_amdgcn_perm(h23, h01, 0x05040100u);
 }
 
+// The matrix unit multiplies signed bytes, so it reads a probability above 127 as P - 256.  A row has at most one
+// such probability (its probabilities sum to at most 255), and only if its largest one, (B*rho) >> 15, exceeds 127;
+// top_tile (wave-uniform) says that some row of the tile can.  Then, if any lane holds such a byte among the four
+// registers p (64 keys of its query), p becomes the top bits as bytes of 64 and the call returns true: the caller
+// feeds them four more times into the same accumulators, P.V = (P - 256*b).V + 4*(64*b).V.
+template <bool PS>
+__device__ __forceinline__ bool top_bits_as_64s(bool top_tile, v4i &p)
+{
+    if constexpr (PS) return false;
+    if (!top_tile) return false;
+    if (__builtin_amdgcn_ballot_w64(((p[0] | p[1] | p[2] | p[3]) & (int)0x80808080) != 0) == 0) return false;
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) p[tt] = (int)(((uint32_t)p[tt] & 0x80808080u) >> 1);
+    return true;
+}
+
 // 4x4 byte transpose: r[k] holds 4 columns of key k; w[c] receives the 4 keys of column c.
 __device__ __forceinline__ void transpose4x4(const uint32_t (&r)[4], uint32_t (&w)[4])
 {

@@ -185,6 +185,8 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
     // Z = sum (B - S*(m - x')) = Lk*B - S*(Lk*m - sum x')      (Eq. (3), (5))
     const uint32_t Z = (uint32_t)(Lk * B - S * (Lk * m - sx));
     const uint32_t rho2 = reciprocal_u8(Z) * 2u;
+    // a row's largest probability is that of its maximum, whose score is B
+    const bool top_tile = !PS && __builtin_amdgcn_ballot_w64((((uint32_t)B * rho2) >> 16) > 127u) != 0;
     const ushort2_t s2 = {(unsigned short)S, (unsigned short)S};
     const unsigned short cc = (unsigned short)(B - S * m);
     const ushort2_t c2 = {cc, cc};
@@ -213,14 +215,13 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
                 s01 &= m01;
                 s23 &= m23;
             }
-            pop[tt] = (int)(PS ? probabilities_plain(s01, s23, rho2) : probabilities_minus_128(s01, s23, rho2));
+            pop[tt] = (int)probabilities_plain(s01, s23, rho2);
         }
         // V operand through the transposing LDS read (see the two-pass kernel below): lane pair j
         // of a 16-lane group points at the key of contraction slot j, the lane receives its column.
         // The contraction runs transposed, O^T tile = V^T . P^T, with V^T as the first operand.
-        // Unless every P is known to be <= 127: P = (P - 128) + 64 + 64, the offset goes through the
-        // matrix unit as well.
-        const v4i c64 = {0x40404040, 0x40404040, 0x40404040, 0x40404040};
+        v4i top = pop;
+        const bool fix = top_bits_as_64s<PS>(top_tile, top);
 #pragma unroll
         for (int n16 = 0; n16 < 4 * ND; ++n16) {
             const uint8_t *at = lds_v[buf] + v_lane_off + 16 * n16;
@@ -230,8 +231,10 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
             v4i &acc = oacc[n16 / 4][n16 % 4];
             acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, pop, acc, 0, 0, 0);
             if constexpr (!PS) {
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+                if (fix) {
+#pragma unroll
+                    for (int again = 0; again < 4; ++again) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, top, acc, 0, 0, 0);
+                }
             }
         }
     });
@@ -272,9 +275,9 @@ __global__ __launch_bounds__(256) void hccs_attention_stream_kernel(const int8_t
 // waves fit a compute unit, and rows up to 4096 keys fit two passes.  The shares exchange
 // their row maxima and clamped sums through LDS and hand their accumulators to the first share
 // at the end.
-// The matrix unit multiplies signed bytes, P is unsigned: it gets P - 128, and the missing
-// 128 = 64 + 64 as two more contractions of a constant operand with the same V operand, unless the
-// host has shown that no P of this table exceeds 127 (PS): then P goes in as it is.
+// The matrix unit multiplies signed bytes, P is unsigned: P goes in as it is.  Unless the host has
+// shown that no P of this table exceeds 127 (PS), a tile whose rows can reach 128 looks for such
+// bytes per 64 keys and makes up for what the unit lost (top_bits_as_64s).
 // ---------------------------------------------------------------------------
 template <int NCMAX, int ND, int RQ, int GPC, bool PS, int KS, bool KT>
 __global__ __launch_bounds__(256 * KS, KS > 1 ? 4 : (NCMAX <= 16 ? 3 : 2)) void hccs_attention_stream2_kernel(
@@ -483,6 +486,8 @@ __global__ __launch_bounds__(256 * KS, KS > 1 ? 4 : (NCMAX <= 16 ? 3 : 2)) void 
     }
     const uint32_t Z = (uint32_t)(Lk_all * B - S * sum_clamped);
     const RowAffine ra = row_affine(Z, B, S, D);
+    // a row's largest probability is that of its maximum, whose score is B
+    const bool top_tile = !PS && __builtin_amdgcn_ballot_w64((__umul24((uint32_t)B, reciprocal_u8(Z)) >> 15) > 127u) != 0;
 
     // ---- pass 2: O = P.V -----------------------------------------------------------------------
     v4i oacc[ND][4];
@@ -501,12 +506,13 @@ __global__ __launch_bounds__(256 * KS, KS > 1 ? 4 : (NCMAX <= 16 ? 3 : 2)) void 
     const int slot = qi >> 1;
     const int v_lane_off = (16 * (slot >> 2) + 4 * g + (slot & 3)) * KSTR + 8 * (qi & 1);
     auto chunk_pv = [&](const uint8_t *buf, const uint32_t *dist) {
-        const v4i c64 = {0x40404040, 0x40404040, 0x40404040, 0x40404040};
 #pragma unroll
         for (int T = 0; T < GPC; ++T) {
             v4i pop;
 #pragma unroll
-            for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)(normalise4(dist[T * 4 + tt], ra) ^ (PS ? 0u : 0x80808080u));
+            for (int tt = 0; tt < 4; ++tt) pop[tt] = (int)normalise4(dist[T * 4 + tt], ra);
+            v4i top = pop;
+            const bool fix = top_bits_as_64s<PS>(top_tile, top);
 #pragma unroll
             for (int n16 = 0; n16 < 4 * ND; ++n16) {
                 const uint8_t *at = buf + 64 * T * KSTR + v_lane_off + 16 * n16;
@@ -516,8 +522,11 @@ __global__ __launch_bounds__(256 * KS, KS > 1 ? 4 : (NCMAX <= 16 ? 3 : 2)) void 
                 v4i &acc = oacc[n16 / 4][n16 % 4];
                 acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, pop, acc, 0, 0, 0);
                 if constexpr (!PS) {
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, c64, acc, 0, 0, 0);
+                    if (fix) {
+#pragma unroll
+                        for (int again = 0; again < 4; ++again)
+                            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(vop, top, acc, 0, 0, 0);
+                    }
                 }
             }
         }

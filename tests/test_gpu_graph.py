@@ -52,12 +52,14 @@ def test_graph_replays_match_eager(oracle):
 
 
 def test_graph_replays_ragged_and_streaming(oracle):
-    """The kernels with LDS exchange and barriers (ragged rows, both streaming fused forms) under
-    graph replay: every replay equals the eager result, which equals the oracle."""
+    """The kernels with LDS exchange and barriers (ragged rows, both streaming fused forms, the resident fused form
+    at a length that is no multiple of 64) under graph replay: every replay equals the eager result, which equals
+    the oracle."""
     g0 = np.random.default_rng(5)
     xr = g0.integers(-128, 128, size=(3, 4, 61, 197), dtype=np.int8)
     tr = synth.head_params(4, 197, synth.BAND_STRICT, seed=9)
-    shapes = [(1, 2, 70, 300, 64), (1, 1, 40, 2300, 64)]      # two-pass and three-pass streaming forms
+    shapes = [(1, 2, 70, 300, 64), (1, 1, 40, 2300, 64),      # two-pass and three-pass streaming forms
+              (2, 3, 197, 197, 64)]                          # resident, partial last tiles
     att = []
     for Bt, H, Lq, Lk, d in shapes:
         q = g0.integers(-64, 64, size=(Bt, H, Lq, d), dtype=np.int8)
