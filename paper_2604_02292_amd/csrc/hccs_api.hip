@@ -11,7 +11,8 @@ hipError_t launch_softmax(const int8_t *x, void *out, int64_t Bt, int H, int Lq,
 hipError_t launch_reciprocal(const uint32_t *z, uint32_t *rho, int64_t count, hipStream_t st);
 hipError_t launch_copy(const void *src, void *dst, int64_t bytes, hipStream_t st);
 hipError_t launch_normalise_table(const int32_t *bsdz, uint8_t *out, int64_t count, hipStream_t st);
-hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H, int L,
+bool attention_is_resident(int Lq, int Lk);   // head size 64
+hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H, int Lq, int L,
                             int d, const HeadTable &tab, const RequantTable &rq, hipStream_t st);
 hipError_t launch_attention_stream(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H,
                                    int Lq, int Lk, int d, const HeadTable &tab, const RequantTable &rq,
@@ -136,10 +137,11 @@ int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t 
     hccs::RequantTable rq;
     for (int h = 0; h < HCCS_MAX_HEADS; ++h)
         rq.e[h] = h < H ? make_int4(requant_host[h].mult, requant_host[h].shift, 0, 0) : make_int4(1, 1, 0, 0);
-    // square blocks whose rows fit the register file go to the resident kernels, everything else streams
-    const bool resident = d == 64 && Lq == Lk && Lk <= 512;
+    // Blocks whose keys fit LDS and whose rows fit the register file go to the resident kernels (as many query
+    // tiles as key tiles at most), everything else streams
+    const bool resident = d == 64 && hccs::attention_is_resident(Lq, Lk);
     const hipError_t e =
-        resident ? hccs::launch_attention(q_dev, k_dev, v_dev, o_dev, B, H, Lk, d, tab, rq, (hipStream_t)hip_stream)
+        resident ? hccs::launch_attention(q_dev, k_dev, v_dev, o_dev, B, H, Lq, Lk, d, tab, rq, (hipStream_t)hip_stream)
                  : hccs::launch_attention_stream(q_dev, k_dev, v_dev, o_dev, B, H, Lq, Lk, d, tab, rq,
                                                  (hipStream_t)hip_stream);
     return e == hipSuccess ? HCCS_OK : HCCS_E_HIP;

@@ -481,18 +481,18 @@ __device__ __forceinline__ void store_tile(int32_t *o, int item, int L, int rt, 
 // when K has landed; V is asked for then and lands during it.  (Measured against blocks that take a
 // half or a quarter of an item's queries, and against blocks that stay and take item after item
 // with the next item's loads in flight: at 768 items this form was the fastest.)
-// PART: items of Lrows < 16*NT rows (else Lrows = 16*NT).  The rows of Q and K an item lacks are loaded as copies of
-// its last one and those of V are zero; their query rows are not stored, and a wave whose tile lies behind the
-// item's rows only keeps the barriers.
+// PART: items of Lq_rows <= 16*NT queries and Lk_rows <= 16*NT keys (else both are 16*NT).  The rows of Q and K an item
+// lacks are loaded as copies of its last one and those of V are zero; their query rows are not stored, and a wave
+// whose tile lies behind the item's queries only keeps the barriers.
 // WIDE: the table does not prove P <= 127; a tile then looks at its rows' largest probabilities.
 template <int NT, int RQ, int WAVES, bool PART, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention_direct_kernel(
     const int8_t *__restrict__ q, const int8_t *__restrict__ k, const int8_t *__restrict__ v, int32_t *__restrict__ o,
-    int H, int Lrows, HeadTable table, RequantTable requant)
+    int H, int Lq_rows, int Lk_rows, HeadTable table, RequantTable requant)
 {
     constexpr int KV = NT * 16 * 64;       // bytes of K (or V) of one item in LDS
     constexpr int kTiles = NT / WAVES;     // query tiles per wave
-    const int L = PART ? Lrows : NT * 16;
+    const int L = PART ? Lk_rows : NT * 16, Lq = PART ? Lq_rows : NT * 16;
     static_assert(NT % WAVES == 0, "equal shares of tiles and of loads");
     __shared__ __attribute__((aligned(16))) uint8_t k_lds[KV];
     __shared__ __attribute__((aligned(16))) uint8_t v_lds[KV];
@@ -500,14 +500,14 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
     const int item = (int)blockIdx.x;
-    const size_t base = (size_t)item * (size_t)(L * 64);
+    const size_t base = (size_t)item * (size_t)(L * 64), q_base = (size_t)item * (size_t)(Lq * 64);
 
     k_rows_to_lds<NT, WAVES>(k + base, k_lds, wave, lane, L - 1);
     // the Q operands of the wave's tiles: query 16*rt + qi, bytes 16g .. 16g+15
     v4i qops[kTiles];
 #pragma unroll
     for (int i = 0; i < kTiles; ++i)
-        qops[i] = *(const v4i *)(q + base + min((wave + i * WAVES) * 16 + qi, L - 1) * 64 + 16 * g);
+        qops[i] = *(const v4i *)(q + q_base + min((wave + i * WAVES) * 16 + qi, Lq - 1) * 64 + 16 * g);
     const HeadRule rule = head_rule(table, requant, item % H);
     const OperandOffsets off = operand_offsets(lane);
 
@@ -522,7 +522,7 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
 #pragma unroll
     for (int i = 0; i < kTiles; ++i) {
         const int rt = wave + i * WAVES;
-        const bool has_rows = !PART || 16 * rt < L;   // wave-uniform
+        const bool has_rows = !PART || 16 * rt < Lq;   // wave-uniform
         short2_t xp[NT][2];
         uint32_t rho2 = 0, p_top = 0;
         if (has_rows) scores_of_tile<NT, RQ, PART>(k_lds, off.k, qops[i], rule, xp, rho2, p_top, L, g);
@@ -537,31 +537,31 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
             v4i oacc[4];
             const bool top = WIDE && __builtin_amdgcn_ballot_w64(p_top > 127u) != 0;
             weighted_values_of_tile<NT, PART, WIDE>(v_lds, off.v, xp, rho2, oacc, L, top);
-            store_tile(o, item, L, rt, lane, oacc);
+            store_tile(o, item, Lq, rt, lane, oacc);
         }
     }
 }
 
 template <int NT, bool PART, bool WIDE>
 static hipError_t launch_direct_wide(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
-                                     int L, const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
+                                     int Lq, int L, const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
 {
     // as many waves as divide the query tiles evenly, at most 8
     constexpr int WAVES = NT % 8 == 0 ? 8 : (NT % 7 == 0 ? 7 : (NT % 6 == 0 ? 6 : (NT % 5 == 0 ? 5 : 4)));
     const dim3 grid((uint32_t)items), block(64 * WAVES);
     if (kind == kRescaleHigh16)
-        return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, L, tab, rq);
+        return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, Lq, L, tab, rq);
     if (kind == kRescaleShift)
-        return launch(hccs_attention_direct_kernel<NT, kRescaleShift, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, L, tab, rq);
-    return launch(hccs_attention_direct_kernel<NT, kRescalePreclamp, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, L, tab, rq);
+        return launch(hccs_attention_direct_kernel<NT, kRescaleShift, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, Lq, L, tab, rq);
+    return launch(hccs_attention_direct_kernel<NT, kRescalePreclamp, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, Lq, L, tab, rq);
 }
 template <int NT, bool PART>
 static hipError_t launch_direct_nt(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t items, int H,
-                                   int L, const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
+                                   int Lq, int L, const HeadTable &tab, const RequantTable &rq, int kind, hipStream_t st)
 {
     if (probabilities_fit_signed(tab, H, L))
-        return launch_direct_wide<NT, PART, false>(q, k, v, o, items, H, L, tab, rq, kind, st);
-    return launch_direct_wide<NT, PART, true>(q, k, v, o, items, H, L, tab, rq, kind, st);
+        return launch_direct_wide<NT, PART, false>(q, k, v, o, items, H, Lq, L, tab, rq, kind, st);
+    return launch_direct_wide<NT, PART, true>(q, k, v, o, items, H, Lq, L, tab, rq, kind, st);
 }
 
 template <int NT>
@@ -578,34 +578,52 @@ static hipError_t launch_nt(const int8_t *q, const int8_t *k, const int8_t *v, i
     return launch(hccs_attention_kernel<NT, kRescalePreclamp, WAVES>, grid, block, st, q, k, v, o, H, tab, rq);
 }
 
-hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H, int L,
-                            int d, const HeadTable &tab, const RequantTable &rq_in, hipStream_t st)
+// key slots of the resident block for Lk keys; 0: too many keys for it
+static int attention_key_slots(int Lk)
+{
+    const int sets = (Lk + 63) / 64;   // of 64 keys
+    return sets <= 8 ? 64 * sets : 0;
+}
+
+// Whether a block of Lq queries and Lk keys (head size 64) goes to the resident kernel: its keys fit LDS and it has
+// no more query tiles than key tiles.  Side by side with the streaming kernels (768 items, us, resident / streaming):
+// 64 x 256 9.7 / 12.9, 197 x 256 20.0 / 33.0, 77 x 197 9.2 / 18.5, 100 x 400 18.6 / 27.0, 1 x 256 6.8 / 9.5, 16 x 384 11.1 /
+// 12.5, 16 x 448 12.8 / 15.1, 250 x 500 38.4 / 47.8, 128 x 512 24.2 / 27.3; only the largest block (more than 448 keys) with
+// at most four query tiles loses: 16 x 512 17.9 / 14.5, 64 x 512 19.4 / 16.8 (97 x 512 22.6 / 26.2).
+bool attention_is_resident(int Lq, int Lk)
+{
+    const int slots = attention_key_slots(Lk);
+    return Lk >= 1 && Lq >= 1 && Lq <= slots && (Lk <= 448 || Lq > 64);
+}
+
+hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H, int Lq,
+                            int L, int d, const HeadTable &tab, const RequantTable &rq_in, hipStream_t st)
 {
     (void)d;   // 64, checked by the caller
+    if (L < 1 || Lq < 1 || Lq > attention_key_slots(L)) return hipErrorInvalidValue;
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
     const int64_t blocks = Bt * H;
-    if (L % 64 != 0) {
+    if (L % 64 != 0 || Lq != L) {
         switch ((L + 63) / 64) {
-            case 1: return launch_direct_nt<4, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 2: return launch_direct_nt<8, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 3: return launch_direct_nt<12, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 4: return launch_direct_nt<16, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 5: return launch_direct_nt<20, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 6: return launch_direct_nt<24, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 7: return launch_direct_nt<28, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            case 8: return launch_direct_nt<32, true>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-            default: return hipErrorInvalidValue;
+            case 1: return launch_direct_nt<4, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
+            case 2: return launch_direct_nt<8, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
+            case 3: return launch_direct_nt<12, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
+            case 4: return launch_direct_nt<16, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
+            case 5: return launch_direct_nt<20, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
+            case 6: return launch_direct_nt<24, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
+            case 7: return launch_direct_nt<28, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
+            default: return launch_direct_nt<32, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
         }
     }
     switch (L / 16) {
-        case 4: return launch_direct_nt<4, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-        case 8: return launch_direct_nt<8, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-        case 12: return launch_direct_nt<12, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-        case 16: return launch_direct_nt<16, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-        case 20: return launch_direct_nt<20, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-        case 24: return launch_direct_nt<24, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
-        case 32: return launch_direct_nt<32, false>(q, k, v, o, blocks, H, L, tab, rq, kind, st);
+        case 4: return launch_direct_nt<4, false>(q, k, v, o, blocks, H, L, L, tab, rq, kind, st);
+        case 8: return launch_direct_nt<8, false>(q, k, v, o, blocks, H, L, L, tab, rq, kind, st);
+        case 12: return launch_direct_nt<12, false>(q, k, v, o, blocks, H, L, L, tab, rq, kind, st);
+        case 16: return launch_direct_nt<16, false>(q, k, v, o, blocks, H, L, L, tab, rq, kind, st);
+        case 20: return launch_direct_nt<20, false>(q, k, v, o, blocks, H, L, L, tab, rq, kind, st);
+        case 24: return launch_direct_nt<24, false>(q, k, v, o, blocks, H, L, L, tab, rq, kind, st);
+        case 32: return launch_direct_nt<32, false>(q, k, v, o, blocks, H, L, L, tab, rq, kind, st);
         default: break;   // 448 keys (7 waves of 4 tiles) measured slower than the first kernel: 31.4 against 29.1 us
     }
     if (L == 448) return launch_nt<28>(q, k, v, o, blocks, H, tab, rq, kind, st);

@@ -765,6 +765,38 @@ def test_attention_square_lengths_with_probabilities_above_127(oracle, L):
         check_attention(q, k, v, table, rq, 0, oracle, f"P above 127, L={L} rq={rq[0].tolist()}")
 
 
+RESIDENT_RECT = [(2, 3, 64, 256), (1, 2, 197, 256), (2, 2, 77, 197), (1, 3, 100, 400), (3, 2, 1, 256), (1, 2, 16, 384),
+                 (1, 2, 250, 500), (1, 2, 128, 512), (1, 2, 65, 512), (1, 2, 64, 512), (2, 2, 192, 130), (1, 2, 193, 130),
+                 (1, 2, 300, 448), (1, 2, 17, 1), (1, 2, 64, 63), (2, 1, 33, 447), (1, 1, 448, 385), (1, 2, 5, 449)]
+
+
+@pytest.mark.parametrize("Bt,H,Lq,Lk", RESIDENT_RECT)
+def test_attention_resident_rectangular_blocks(oracle, Bt, H, Lq, Lk):
+    """Head size 64, up to 512 keys, queries and keys of different counts: the resident kernel takes these while the
+    queries need no more tiles than the block has key tiles (and, beyond 448 keys, more than 64 queries); the shapes
+    just outside those limits are here too and stream.  Full-range inputs, a table that proves P <= 127 and one that
+    does not, two rescale forms, guard values around the output."""
+    g = np.random.default_rng(Lq * 1000 + Lk)
+    q, k, v = rect_qkv(Lq + Lk, Bt, H, Lq, Lk, 64, lo=-128, hi=127)
+    k[:, 0, Lk - 1] = 127
+    floor = -(-256 // Lk) + 1
+    tables = [(synth.head_params(H, Lk, 1, seed=Lk), 1),
+              (np.array([[12700 + floor + h, 100, 127] for h in range(H)], np.int32), 0)]
+    for table, band in tables:
+        assert binding.validate_params(table, Lk, band) == (0, -1)
+        for rq in ([[100 + h, 16] for h in range(H)], [[4096 - h, 24 - (h % 3)] for h in range(H)]):
+            rq = np.array(rq, np.int32)
+            want, rc = oracle.attention(q, k, v, table, rq, band, threads=THREADS)
+            assert rc == 0
+            buf = torch.full((q.size + 512,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+            out = buf[256:256 + q.size].view(q.shape)
+            binding.attention_i8(torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(),
+                                 table, rq, band, out=out)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want), f"{(Bt, H, Lq, Lk)} band={band} rq={rq[0].tolist()}"
+            assert bool((buf[:256] == 0x5A5A5A5A).all()) and bool((buf[256 + q.size:] == 0x5A5A5A5A).all())
+
+
 def test_attention_vision_encoder_length_full_size(oracle):
     """[64, 12, 197, 197] with head size 64: as many items as the benchmark's fused shape, 197 tokens each."""
     g = np.random.default_rng(197)
