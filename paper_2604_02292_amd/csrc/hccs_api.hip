@@ -137,8 +137,7 @@ int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t 
     hccs::RequantTable rq;
     for (int h = 0; h < HCCS_MAX_HEADS; ++h)
         rq.e[h] = h < H ? make_int4(requant_host[h].mult, requant_host[h].shift, 0, 0) : make_int4(1, 1, 0, 0);
-    // Blocks whose keys fit LDS and whose rows fit the register file go to the resident kernels (as many query
-    // tiles as key tiles at most), everything else streams
+    // Blocks whose keys fit LDS go to the resident kernels, everything else streams
     const bool resident = d == 64 && hccs::attention_is_resident(Lq, Lk);
     const hipError_t e =
         resident ? hccs::launch_attention(q_dev, k_dev, v_dev, o_dev, B, H, Lq, Lk, d, tab, rq, (hipStream_t)hip_stream)

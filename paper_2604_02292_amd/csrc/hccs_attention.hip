@@ -472,18 +472,19 @@ __device__ __forceinline__ void weighted_values_of_tile(const uint8_t *v_lds, co
 }
 
 // rows of query tile rt of an item
-__device__ __forceinline__ void store_tile(int32_t *o, int item, int L, int rt, int lane, const v4i (&oacc)[4])
+__device__ __forceinline__ void store_tile(int32_t *o_rows, int L, int rt, int lane, const v4i (&oacc)[4])
 {
-    store_rows_whole_lines<4>(o + ((size_t)item * L + (size_t)rt * 16) * 64, 64, min(16, L - 16 * rt), lane, oacc);
+    store_rows_whole_lines<4>(o_rows + (size_t)rt * 16 * 64, 64, min(16, L - 16 * rt), lane, oacc);
 }
 
 // One block per (batch, head) item, NT / WAVES query tiles per wave.  The first contraction starts
 // when K has landed; V is asked for then and lands during it.  (Measured against blocks that take a
 // half or a quarter of an item's queries, and against blocks that stay and take item after item
 // with the next item's loads in flight: at 768 items this form was the fastest.)
-// PART: items of Lq_rows <= 16*NT queries and Lk_rows <= 16*NT keys (else both are 16*NT).  The rows of Q and K an item
-// lacks are loaded as copies of its last one and those of V are zero; their query rows are not stored, and a wave
-// whose tile lies behind the item's queries only keeps the barriers.
+// PART: items of Lq_rows queries and Lk_rows <= 16*NT keys (else both are 16*NT); block (x, y) takes the queries from
+// 16*NT*y on, 16*NT of them at most.  The rows of Q and K that a block lacks are loaded as copies of the last one and
+// those of V are zero; their query rows are not stored, and a wave whose tile lies behind the block's queries only
+// keeps the barriers.
 // WIDE: the table does not prove P <= 127; a tile then looks at its rows' largest probabilities.
 template <int NT, int RQ, int WAVES, bool PART, bool WIDE>
 __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention_direct_kernel(
@@ -492,7 +493,9 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
 {
     constexpr int KV = NT * 16 * 64;       // bytes of K (or V) of one item in LDS
     constexpr int kTiles = NT / WAVES;     // query tiles per wave
-    const int L = PART ? Lk_rows : NT * 16, Lq = PART ? Lq_rows : NT * 16;
+    const int L = PART ? Lk_rows : NT * 16;
+    const int q0 = PART ? (int)blockIdx.y * (NT * 16) : 0;          // the block's first query
+    const int Lq = PART ? min(NT * 16, Lq_rows - q0) : NT * 16;     // and how many it has
     static_assert(NT % WAVES == 0, "equal shares of tiles and of loads");
     __shared__ __attribute__((aligned(16))) uint8_t k_lds[KV];
     __shared__ __attribute__((aligned(16))) uint8_t v_lds[KV];
@@ -500,7 +503,8 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int qi = lane & 15, g = lane >> 4;
     const int item = (int)blockIdx.x;
-    const size_t base = (size_t)item * (size_t)(L * 64), q_base = (size_t)item * (size_t)(Lq * 64);
+    const size_t base = (size_t)item * (size_t)(L * 64);
+    const size_t q_base = ((size_t)item * (size_t)(PART ? Lq_rows : NT * 16) + (size_t)q0) * 64;
 
     k_rows_to_lds<NT, WAVES>(k + base, k_lds, wave, lane, L - 1);
     // the Q operands of the wave's tiles: query 16*rt + qi, bytes 16g .. 16g+15
@@ -537,7 +541,7 @@ __global__ __launch_bounds__(64 * WAVES, (NT <= 16 ? 6 : 4)) void hccs_attention
             v4i oacc[4];
             const bool top = WIDE && __builtin_amdgcn_ballot_w64(p_top > 127u) != 0;
             weighted_values_of_tile<NT, PART, WIDE>(v_lds, off.v, xp, rho2, oacc, L, top);
-            store_tile(o, item, Lq, rt, lane, oacc);
+            store_tile(o + q_base, Lq, rt, lane, oacc);
         }
     }
 }
@@ -548,7 +552,7 @@ static hipError_t launch_direct_wide(const int8_t *q, const int8_t *k, const int
 {
     // as many waves as divide the query tiles evenly, at most 8
     constexpr int WAVES = NT % 8 == 0 ? 8 : (NT % 7 == 0 ? 7 : (NT % 6 == 0 ? 6 : (NT % 5 == 0 ? 5 : 4)));
-    const dim3 grid((uint32_t)items), block(64 * WAVES);
+    const dim3 grid((uint32_t)items, (uint32_t)((Lq + NT * 16 - 1) / (NT * 16))), block(64 * WAVES);
     if (kind == kRescaleHigh16)
         return launch(hccs_attention_direct_kernel<NT, kRescaleHigh16, WAVES, PART, WIDE>, grid, block, st, q, k, v, o, H, Lq, L, tab, rq);
     if (kind == kRescaleShift)
@@ -585,22 +589,22 @@ static int attention_key_slots(int Lk)
     return sets <= 8 ? 64 * sets : 0;
 }
 
-// Whether a block of Lq queries and Lk keys (head size 64) goes to the resident kernel: its keys fit LDS and it has
-// no more query tiles than key tiles.  Side by side with the streaming kernels (768 items, us, resident / streaming):
+// Whether a block of Lq queries and Lk keys (head size 64) goes to the resident kernel: its keys fit LDS.  Side by side with the streaming kernels (768 items, us, resident / streaming):
 // 64 x 256 9.7 / 12.9, 197 x 256 20.0 / 33.0, 77 x 197 9.2 / 18.5, 100 x 400 18.6 / 27.0, 1 x 256 6.8 / 9.5, 16 x 384 11.1 /
 // 12.5, 16 x 448 12.8 / 15.1, 250 x 500 38.4 / 47.8, 128 x 512 24.2 / 27.3; only the largest block (more than 448 keys) with
-// at most four query tiles loses: 16 x 512 17.9 / 14.5, 64 x 512 19.4 / 16.8 (97 x 512 22.6 / 26.2).
+// at most four query tiles loses: 16 x 512 17.9 / 14.5, 64 x 512 19.4 / 16.8 (97 x 512 22.6 / 26.2).  Items with more queries than
+// the block has key slots get several blocks: 197 x 77 12.0 / 23.4, 2048 x 64 (48 items) 7.6 / 13.8, 2048 x 512 (192 items) 60.2 / 86.2.
 bool attention_is_resident(int Lq, int Lk)
 {
     const int slots = attention_key_slots(Lk);
-    return Lk >= 1 && Lq >= 1 && Lq <= slots && (Lk <= 448 || Lq > 64);
+    return Lk >= 1 && Lq >= 1 && slots > 0 && (Lk <= 448 || Lq > 64);
 }
 
 hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, int32_t *o, int64_t Bt, int H, int Lq,
                             int L, int d, const HeadTable &tab, const RequantTable &rq_in, hipStream_t st)
 {
     (void)d;   // 64, checked by the caller
-    if (L < 1 || Lq < 1 || Lq > attention_key_slots(L)) return hipErrorInvalidValue;
+    if (L < 1 || Lq < 1 || attention_key_slots(L) == 0 || (Lq + 15) / 16 > 65535 * 4) return hipErrorInvalidValue;
     RequantTable rq;
     const int kind = choose_rescale(rq_in, H, (int64_t)1 << 20, rq);   // |acc| <= 64*128*128 = 2^20
     const int64_t blocks = Bt * H;
