@@ -889,6 +889,48 @@ def test_attention_random_sweep(oracle):
     attention_sweep(oracle, 20260428, 200)
 
 
+def test_attention_resident_random_sweep(oracle):
+    """300 seeded random fused blocks with head size 64 and up to 512 keys: square, fewer and more queries than keys,
+    tables with large and with small floors (probabilities above 127 possible), uniform keys and one dominant key
+    (also as the last key), every rescale form."""
+    g = np.random.default_rng(20260429)
+    for case in range(300):
+        Bt, H = int(g.integers(1, 4)), int(g.integers(1, 5))
+        Lk = int(g.integers(1, 513)) if g.integers(4) else 64 * int(g.integers(1, 9))
+        pick = int(g.integers(4))
+        Lq = (Lk if pick == 0 else int(g.integers(1, 130)) if pick == 1 else int(g.integers(1, 1100)) if pick == 2
+              else max(1, Lk + int(g.integers(-20, 21))))
+        band = int(g.integers(2))
+        table = _random_table(g, H, Lk, band)
+        if g.integers(2):
+            floor = -(-256 // Lk) + 1
+            cap = min((32767 if band == 1 else 255 << 15) // Lk, 32767)
+            for h in range(H):
+                S, D = int(g.integers(1, 101)), int(g.integers(60, 128))
+                if S * D + floor <= cap:
+                    table[h] = (S * D + floor, S, D)
+        assert binding.validate_params(table, Lk, band) == (0, -1)
+        lo, hi = (-128, 128) if g.integers(2) else (-64, 64)
+        q = g.integers(lo, hi, size=(Bt, H, Lq, 64), dtype=np.int8)
+        k = g.integers(lo, hi, size=(Bt, H, Lk, 64), dtype=np.int8)
+        v = g.integers(-128, 128, size=(Bt, H, Lk, 64), dtype=np.int8)
+        peaky = g.integers(2) == 0
+        if peaky:
+            q = np.abs(q.astype(np.int16)).clip(0, 127).astype(np.int8)
+            k = g.integers(-1, 2, size=k.shape, dtype=np.int8)
+            k[:, :, int(g.integers(Lk))] = 127
+            k[:, -1, Lk - 1] = 127
+        kind = int(g.integers(3))
+        if kind == 0:
+            rq = np.stack([g.integers(1, 256, H), g.integers(10, 17, H)], 1)
+        elif kind == 1:
+            rq = np.stack([g.integers(1, 4097, H), g.integers(17, 25, H)], 1)
+        else:
+            rq = np.stack([g.integers(2048, 4097, H), g.integers(1, 25, H)], 1)
+        check_attention(q, k, v, table, rq.astype(np.int32), band, oracle,
+                        f"resident sweep {case} Lq={Lq} Lk={Lk} band={band} peaky={peaky} rq={kind}")
+
+
 def attention_sweep(oracle, seed, cases):
     g = np.random.default_rng(seed)
     for case in range(cases):
