@@ -147,7 +147,7 @@ HCCS_API int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const i
  *   q_dev [B,H,Lq,d], k_dev and v_dev [B,H,Lk,d] int8, o_dev [B,H,Lq,d] int32, all 16-byte aligned.
  *   d = 64 or 128; 1 <= Lk <= HCCS_MAX_ROW_LENGTH; Lq >= 0 (0 is a no-op);
  *   B*H*Lq < 2^31.  The row length of HCCS, and of the band check, is n = Lk.
- * Blocks with d = 64 and up to 768 keys keep a query tile's logits in registers and K, V in LDS
+ * Blocks with d = 64 and up to 896 keys keep a query tile's logits in registers and K, V in LDS
  * (beyond 448 keys only with more than 64 queries); every other shape streams K and V through
  * LDS in chunks.  Up to
  * 2048 keys a query tile's logits stay in registers as bytes (Q.K^T once, two passes); beyond

@@ -5,7 +5,7 @@
 //
 // Two kernels.  The first is launched for 448 keys only, where it measured faster.  The second,
 // further down, brings K and V straight into LDS, feeds P to the matrix unit as it is and takes
-// every other length up to 768, whole 64s of keys or not.  What follows describes the first.
+// every other length up to 896, whole 64s of keys or not.  What follows describes the first.
 //
 // The matrix unit is used for the two dense contractions only.  Both use
 // v_mfma_i32_16x16x64_i8, whose operand layout on a 64-lane wave is
@@ -327,7 +327,7 @@ __device__ __forceinline__ void wait_vector_memory() { __builtin_amdgcn_s_waitcn
 // as above, and every LDS operation too: vmcnt(0) lgkmcnt(0)
 __device__ __forceinline__ void wait_memory() { __builtin_amdgcn_s_waitcnt(0x0070); }
 
-// The launcher lays a block out for the next multiple of 64 keys up to 512, then for 640 or 768, so at most this many of the
+// The launcher lays a block out for the next multiple of 64 keys up to 512, then for 640, 768 or 896, so at most this many of the
 // last key tiles can be wholly absent.
 template <int NT>
 constexpr int kAbsentTiles = NT >= 32 ? 7 : 3;
@@ -586,7 +586,7 @@ static hipError_t launch_nt(const int8_t *q, const int8_t *k, const int8_t *v, i
 static int attention_key_slots(int Lk)
 {
     const int sets = (Lk + 63) / 64;   // of 64 keys
-    return sets <= 8 ? 64 * sets : (sets <= 10 ? 640 : (sets <= 12 ? 768 : 0));
+    return sets <= 8 ? 64 * sets : (sets <= 10 ? 640 : (sets <= 12 ? 768 : (sets <= 14 ? 896 : 0)));
 }
 
 // Whether a block of Lq queries and Lk keys (head size 64) goes to the resident kernel: its keys fit LDS.  Side by side with the streaming kernels (768 items, us, resident / streaming):
@@ -594,8 +594,9 @@ static int attention_key_slots(int Lk)
 // 12.5, 16 x 448 12.8 / 15.1, 250 x 500 38.4 / 47.8, 128 x 512 24.2 / 27.3; only the largest block (more than 448 keys) with
 // at most four query tiles loses: 16 x 512 17.9 / 14.5, 64 x 512 19.4 / 16.8 (97 x 512 22.6 / 26.2).  Items with more queries than
 // the block has key slots get several blocks: 197 x 77 12.0 / 23.4, 2048 x 64 (48 items) 7.6 / 13.8, 2048 x 512 (192 items) 60.2 / 86.2.
-// Blocks of 640 and 768 key slots (80 and 96 KB of LDS, one block per compute unit): 513 x 513 74.0 / 107.8, 577 x 577 87.8 / 122.0,
-// 640 x 640 94.5 / 118.9, 700 x 700 118.0 / 150.2, 768 x 768 139.0 / 162.8, 100 x 700 33.6 / 35.6, 2048 x 768 (192 items) 103.0 / 111.2.
+// Blocks of 640, 768 and 896 key slots (80, 96 and 112 KB of LDS, one block per compute unit): 513 x 513 74.0 / 107.8, 577 x 577 87.8 / 122.0,
+// 640 x 640 94.5 / 118.9, 700 x 700 118.0 / 150.2, 768 x 768 139.0 / 162.8, 100 x 700 33.6 / 35.6, 2048 x 768 (192 items) 103.0 / 111.2, 800 x 800 156 / 192,
+// 896 x 896 183 / 205; 1024 slots lose: 1024 x 1024 283 / 265, 2048 x 1024 (192 items) 178 / 136.
 bool attention_is_resident(int Lq, int Lk)
 {
     const int slots = attention_key_slots(Lk);
@@ -624,6 +625,8 @@ hipError_t launch_attention(const int8_t *q, const int8_t *k, const int8_t *v, i
             case 10: return launch_direct_nt<40, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
             case 11:
             case 12: return launch_direct_nt<48, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
+            case 13:
+            case 14: return launch_direct_nt<56, true>(q, k, v, o, blocks, H, Lq, L, tab, rq, kind, st);
             default: return hipErrorInvalidValue;
         }
     }

@@ -717,17 +717,17 @@ def test_attention_square_blocks_of_any_length(oracle, L):
             assert bool((buf[:256] == 0x5A5A5A5A).all()) and bool((buf[256 + q.size:] == 0x5A5A5A5A).all())
 
 
-def test_attention_every_square_length_up_to_768(oracle):
-    """Every length from 1 to 768 once, with tables that prove P <= 127 from three keys on (so all but the first two
+def test_attention_every_square_length_up_to_896(oracle):
+    """Every length from 1 to 896 once, with tables that prove P <= 127 from three keys on (so all but the first two
     take the resident kernel), rows whose maximum is the last key, and inputs whose logits reach both saturations."""
     g = np.random.default_rng(512)
     H, d = 2, 64
-    for L in range(1, 769):
+    for L in range(1, 897):
         q, k, v = (g.integers(-128, 128, size=(1, H, L, d), dtype=np.int8) for _ in range(3))
         if L % 3 == 0:
             k[0, :, L - 1] = np.where(q[0, :, L // 2] >= 0, 127, -128)   # the last key is the largest for that query
         table = np.array([[300, 2, 20], [280, 1, 20]] if L < 7 else [[100, 2, 20], [60, 1, 20]] if L <= 327
-                         else [[60, 1, 20], [50, 0, 9]] if L <= 546 else [[40, 1, 20], [42, 0, 9]], np.int32)
+                         else [[60, 1, 20], [50, 0, 9]] if L <= 546 else [[36, 1, 20], [30, 0, 9]], np.int32)
         assert binding.validate_params(table, L, 1) == (0, -1)
         rq = np.array([[3 + L % 50, 12], [900, 20]], np.int32)
         want, rc = oracle.attention(q, k, v, table, rq, 1, threads=THREADS)
@@ -736,11 +736,11 @@ def test_attention_every_square_length_up_to_768(oracle):
                                    table, rq, 1)
         torch.cuda.synchronize()
         assert np.array_equal(got.cpu().numpy(), want), f"L={L}"
-    print("768 lengths equal", flush=True)
+    print("896 lengths equal", flush=True)
 
 
 @pytest.mark.parametrize("L", [16, 64, 65, 100, 128, 197, 200, 256, 300, 320, 384, 390, 447, 448, 449, 511, 512, 513, 577, 640,
-                               641, 700, 768])
+                               641, 700, 768, 769, 850, 896])
 def test_attention_square_lengths_with_probabilities_above_127(oracle, L):
     """Resident lengths under tables that allow P > 127, with rows that reach it: one key far above the others,
     which sit at the window's edge; in head 1 that key is the last one, whose logit the partial-length kernel repeats
@@ -754,7 +754,7 @@ def test_attention_square_lengths_with_probabilities_above_127(oracle, L):
     k[:, 1, L - 1] = 127
     q[0, 0, ::5] = g.integers(-3, 4, size=q[0, 0, ::5].shape, dtype=np.int8)   # rows without a dominant key in between
     floor = -(-256 // L) + 1
-    S0 = 100 if L <= 640 else 80                          # n*B stays within the 8-bit band
+    S0 = 100 if L <= 640 else 70                          # n*B stays within the 8-bit band
     table = np.array([[S0 * 127 + floor, S0, 127], [32 * 100 + floor, 32, 100]], np.int32)
     assert binding.validate_params(table, L, 0) == (0, -1)
     for rq in ([[40, 16], [3, 12]], [[900, 20], [4096, 24]]):
@@ -770,12 +770,13 @@ RESIDENT_RECT = [(2, 3, 64, 256), (1, 2, 197, 256), (2, 2, 77, 197), (1, 3, 100,
                  (1, 2, 250, 500), (1, 2, 128, 512), (1, 2, 65, 512), (1, 2, 64, 512), (2, 2, 192, 130), (1, 2, 193, 130),
                  (1, 2, 300, 448), (1, 2, 17, 1), (1, 2, 64, 63), (2, 1, 33, 447), (1, 1, 448, 385), (1, 2, 5, 449),
                  (2, 2, 197, 77), (1, 2, 128, 64), (1, 1, 1000, 64), (1, 2, 700, 300), (1, 1, 513, 512), (1, 2, 449, 385),
-                 (1, 2, 100, 600), (1, 1, 700, 577), (2, 1, 65, 768), (1, 2, 64, 768), (1, 1, 300, 769), (1, 2, 1300, 641)]
+                 (1, 2, 100, 600), (1, 1, 700, 577), (2, 1, 65, 768), (1, 2, 64, 768), (1, 1, 300, 769), (1, 2, 1300, 641),
+                 (1, 2, 900, 896), (1, 1, 65, 897), (2, 1, 200, 833)]
 
 
 @pytest.mark.parametrize("Bt,H,Lq,Lk", RESIDENT_RECT)
 def test_attention_resident_rectangular_blocks(oracle, Bt, H, Lq, Lk):
-    """Head size 64, up to 768 keys, queries and keys of different counts: the resident kernel takes these (beyond 448
+    """Head size 64, up to 896 keys, queries and keys of different counts: the resident kernel takes these (beyond 448
     keys only with more than 64 queries; the shapes just outside are here too and stream), in several blocks per
     item when there are more queries than key slots.  Full-range inputs, a table that proves P <= 127 and one that
     does not, two rescale forms, guard values around the output."""
@@ -784,7 +785,7 @@ def test_attention_resident_rectangular_blocks(oracle, Bt, H, Lq, Lk):
     k[:, 0, Lk - 1] = 127
     floor = -(-256 // Lk) + 1
     tables = [(synth.head_params(H, Lk, 1, seed=Lk), 1),
-              (np.array([[(100 if Lk <= 640 else 80) * 127 + floor + h, 100 if Lk <= 640 else 80, 127] for h in range(H)],
+              (np.array([[(100 if Lk <= 640 else 70) * 127 + floor + h, 100 if Lk <= 640 else 70, 127] for h in range(H)],
                         np.int32), 0)]
     for table, band in tables:
         assert binding.validate_params(table, Lk, band) == (0, -1)
@@ -894,13 +895,13 @@ def test_attention_random_sweep(oracle):
 
 
 def test_attention_resident_random_sweep(oracle):
-    """300 seeded random fused blocks with head size 64 and up to 768 keys: square, fewer and more queries than keys,
+    """300 seeded random fused blocks with head size 64 and up to 896 keys: square, fewer and more queries than keys,
     tables with large and with small floors (probabilities above 127 possible), uniform keys and one dominant key
     (also as the last key), every rescale form."""
     g = np.random.default_rng(20260429)
     for case in range(300):
         Bt, H = int(g.integers(1, 4)), int(g.integers(1, 5))
-        Lk = int(g.integers(1, 769)) if g.integers(4) else 64 * int(g.integers(1, 13))
+        Lk = int(g.integers(1, 897)) if g.integers(4) else 64 * int(g.integers(1, 15))
         pick = int(g.integers(4))
         Lq = (Lk if pick == 0 else int(g.integers(1, 130)) if pick == 1 else int(g.integers(1, 1100)) if pick == 2
               else max(1, Lk + int(g.integers(-20, 21))))
