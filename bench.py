@@ -372,9 +372,10 @@ def main():
 
         # ---- fused int8 attention block (resident kernels): the 256-token shape, and a vision encoder's 197 tokens
         for label, shape, kernel in (("fused_attention", None, "hccs_attention_direct_kernel<16,0,8,false,false>"),
-                                     ("fused_attention_197", (64, 12, 197, 64), "hccs_attention_direct_kernel<16,0,8,true,false>")):
+                                     ("fused_attention_197", (64, 12, 197, 64), "hccs_attention_direct_kernel<16,0,8,true,false>"),
+                                     ("fused_attention_577", (64, 12, 577, 64), "hccs_attention_direct_kernel<40,0,8,true,false>")):
             a = synth.make_workload("fused_attention", shape=shape)
-            sets = 18   # 1.5 GB of inputs and outputs at 256 tokens: six times the memory-side cache
+            sets = 18 if label != "fused_attention_577" else 8   # 1.5 GB of inputs and outputs: six times the memory-side cache
             q, k, v = ([torch.from_numpy(a[t]).to(dev).clone() for _ in range(sets)] for t in ("q", "k", "v"))
             o = [torch.empty(a["q"].shape, dtype=torch.int32, device=dev) for _ in range(sets)]
             ms = timed_graphs([binding.prepare_attention(q[i], k[i], v[i], o[i], a["table"], a["requant"], a["band"])
@@ -390,7 +391,9 @@ def main():
                  "mfma_utilisation": round(ops / t / 1e12 / INT8_MFMA_PEAK_TOPS, 4),
                  "note": "one round of 768 blocks: loads, then arithmetic bound by vector-instruction issue (requantisation "
                          "and HCCS stage; the matrix unit carries only the two contractions), then the last tile's stores"
-                         + ("" if shape is None else "; 13 of the 16 query tiles and 197 of the 256 key slots of a block exist")})
+                         + {"fused_attention": "", "fused_attention_197": "; 13 of the 16 query tiles and 197 of the 256 key slots of a block exist",
+                            "fused_attention_577": "; 37 of the 40 query tiles and 577 of the 640 key slots of a block exist, one block per "
+                                                   "compute unit, three rounds"}[label]})
             del q, k, v, o
             torch.cuda.empty_cache()
 
