@@ -487,7 +487,7 @@ __global__ __launch_bounds__(256 * KS, KS > 1 ? 4 : (NCMAX <= 16 ? 3 : 2)) void 
     const uint32_t Z = (uint32_t)(Lk_all * B - S * sum_clamped);
     const RowAffine ra = row_affine(Z, B, S, D);
     // a row's largest probability is that of its maximum, whose score is B
-    const bool top_tile = !PS && __builtin_amdgcn_ballot_w64((__umul24((uint32_t)B, reciprocal_u8(Z)) >> 15) > 127u) != 0;
+    const bool top_tile = !PS && __builtin_amdgcn_ballot_w64((((uint32_t)B * reciprocal_u8(Z)) >> 15) > 127u) != 0;
 
     // ---- pass 2: O = P.V -----------------------------------------------------------------------
     v4i oacc[ND][4];
