@@ -161,6 +161,8 @@ def main():
                     help="for rocprofv3 --pmc: --steps eager launches of one workload's kernel, nothing else; "
                          "`rows` also launches the plain copy kernel on the same buffers (counter scaling)")
     ap.add_argument("--workload", default=HEADLINE, help="stand-alone workload of a `rows` counter run")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="tokens per (batch, head) item of an `attention` counter run (default: the 256 of the fused workload)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: rows are independent and shard with no exchange step, "
@@ -194,7 +196,7 @@ def main():
         return (Bs, Hs, Ls, ds), (lambda: binding.attention_i8(qs, ks, vs, tab_s, rq_s, synth.BAND_U8, out=os_))
 
     if args.counter_run == "attention":
-        a = synth.make_workload("fused_attention")
+        a = synth.make_workload("fused_attention", shape=None if args.tokens is None else (64, 12, args.tokens, 64))
         q, k, v = (torch.from_numpy(a[t]).to(dev) for t in ("q", "k", "v"))
         o = torch.empty(a["q"].shape, dtype=torch.int32, device=dev)
         launch = binding.prepare_attention(q, k, v, o, a["table"], a["requant"], a["band"])
