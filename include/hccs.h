@@ -149,10 +149,10 @@ HCCS_API int hccs_attention_i8(const int8_t *q_dev, const int8_t *k_dev, const i
  *   B*H*Lq < 2^31.  The row length of HCCS, and of the band check, is n = Lk.
  * Blocks with d = 64 and up to 896 keys keep a query tile's logits in registers and K, V in LDS
  * (beyond 448 keys only with more than 64 queries); every other shape streams K and V through
- * LDS in chunks.  Up to
- * 2048 keys a query tile's logits stay in registers as bytes (Q.K^T once, two passes); beyond
- * that Q.K^T is recomputed three times (maximum, sum, output), because the floors of HCCS do
- * not allow partial results to be rescaled.  All are bit-exact to the same definition. */
+ * LDS in chunks.  Up to 4096 keys at d = 64 and 2048 at d = 128 a query tile's logits stay in
+ * registers as bytes (Q.K^T once, two passes); beyond that Q.K^T is recomputed three times
+ * (maximum, sum, output), because the floors of HCCS do not allow partial results to be
+ * rescaled.  All are bit-exact to the same definition. */
 HCCS_API int hccs_attention_i8_ex(const int8_t *q_dev, const int8_t *k_dev, const int8_t *v_dev, int32_t *o_dev,
                                   int32_t B, int32_t H, int32_t Lq, int32_t Lk, int32_t d,
                                   const hccs_head_params *table_host, const hccs_requant *requant_host,
